@@ -1,0 +1,154 @@
+/*
+ * libmrfmp -- min-sum message passing on grid pairwise MRFs for AMD MI355X (gfx950).
+ *
+ * C ABI of the ISGMR and TRWP forward sweeps and their index-driven backward passes
+ * ("Fast and Differentiable Message Passing on Pairwise Markov Random Fields",
+ * Alg. 1-4).  Plain pointers and sizes only.
+ *
+ * Conventions shared by every entry point
+ * ----------------------------------------
+ *  - Pointers marked DEVICE are HIP device pointers on the current device; pointers
+ *    marked HOST are ordinary host memory read during the call.
+ *  - All tensors are dense, row-major, last index fastest:
+ *        unary, cost, grad_cost, grad_unary   [B][H][W][L]   float
+ *        pairwise, grad_pairwise              [L][L]         float  V[mu at i-r][lambda at i]
+ *        edge_weight, grad_edge_weight        [R][B][H][W]   float  entry (r,i) = theta_{i-r,i}
+ *        messages                             [R][B][H][W][L] float
+ *        p                                    [K][R][B][H][W][L] uint8  (argmin over mu)
+ *        q                                    [K][R][B][H][W]    uint8  (argmin over lambda)
+ *        labels                               [B][H][W]      uint8
+ *  - A node whose predecessor i-r is outside the grid is the first node of its scanline
+ *    in direction r: its message is 0, its p and q entries are written as 0, its edge
+ *    weight is never read and its edge-weight gradient is 0.
+ *  - Ties in every argmin go to the lowest label.
+ *  - Ownership: the caller owns every buffer, including the workspace; the library
+ *    allocates no device memory and keeps no state between calls.  Outputs are fully
+ *    overwritten (gradients are assigned, not accumulated into what the caller passed).
+ *  - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return
+ *    without synchronising.  Calls that share a workspace must be ordered by the caller.
+ *  - Return value: MRF_OK (0) or a negative mrf_status.  Argument errors are detected
+ *    before any GPU work is enqueued.  Nothing is printed and nothing aborts.
+ *  - Inputs must be finite; NaN or infinity in unary, pairwise, edge_weight or grad_cost
+ *    gives unspecified values (never out-of-bounds accesses: indices read from p and q
+ *    are clamped to [0, L)).
+ */
+#ifndef MRFMP_H
+#define MRFMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MRF_MAX_DIRECTIONS 16
+#define MRF_MAX_LABELS 256
+
+typedef enum {
+    MRF_OK = 0,
+    MRF_ERR_NULL_POINTER = -1,      /* a required pointer is NULL */
+    MRF_ERR_BAD_SHAPE = -2,         /* B, H or W < 1, or a tensor would exceed 2^31-1 label vectors */
+    MRF_ERR_BAD_LABELS = -3,        /* L outside [1, 256] (p, q are 8-bit, Sec. 4) */
+    MRF_ERR_BAD_ITERATIONS = -4,    /* K < 1 */
+    MRF_ERR_BAD_DIRECTIONS = -5,    /* R outside [1, 16], a zero step, or a repeated direction */
+    MRF_ERR_WORKSPACE_TOO_SMALL = -6,
+    MRF_ERR_BAD_PAIRWISE_KIND = -7, /* unknown pairwise_kind, or trunc/scale invalid for it */
+    MRF_ERR_BAD_ALGORITHM = -8,     /* algo argument is neither MRF_ISGMR nor MRF_TRWP */
+    MRF_ERR_HIP = -9                /* a HIP runtime call or kernel launch failed */
+} mrf_status;
+
+enum { MRF_ISGMR = 0, MRF_TRWP = 1 };
+
+/* pairwise_kind: a promise about the contents of `pairwise` that lets the forward pass
+ * skip work; `pairwise` must still hold the full L x L table (it is what is read). */
+enum {
+    MRF_PAIRWISE_DENSE = 0,            /* no structure assumed */
+    MRF_PAIRWISE_TRUNC_LINEAR = 1,     /* V(mu,lambda) = scale * min(|mu-lambda|, trunc)      */
+    MRF_PAIRWISE_TRUNC_QUADRATIC = 2   /* V(mu,lambda) = scale * min((mu-lambda)^2, trunc)    */
+};
+
+/* The problem as the paper states it: energy parameters Theta = {theta_i, theta_ij} with
+ * theta_{i-r,i}(mu,lambda) = theta_{i-r,i} V(mu,lambda) (Sec. 5.1), direction set R,
+ * iteration count K, TRW coefficients rho (Eq. trwp). */
+typedef struct {
+    int32_t B, H, W, L;         /* batch, grid height, width, labels (1..256) */
+    int32_t R;                  /* number of directions, 1..16 */
+    const int32_t *dirs;        /* HOST  [R][2] steps (dh, dw); order = TRWP sweep order;
+                                   r- is the entry (-dh,-dw) if present, else its term is absent */
+    int32_t K;                  /* iterations >= 1 */
+    const float *unary;         /* DEVICE [B][H][W][L]; forward only (may be NULL for backward) */
+    const float *pairwise;      /* DEVICE [L][L] */
+    const float *edge_weight;   /* DEVICE [R][B][H][W], or NULL => edge_weight_scalar on every edge */
+    float edge_weight_scalar;
+    const float *rho;           /* HOST  [R] rho_{i-r,i} per direction; TRWP only, ignored by ISGMR */
+    int32_t pairwise_kind;      /* MRF_PAIRWISE_* */
+    float trunc, scale;         /* parameters of kinds 1 and 2 (trunc > 0) */
+} mrf_problem;
+
+/* Bytes of DEVICE workspace (256-byte aligned base required) that the forward
+ * (backward = 0) or backward (backward != 0) pass of `algo` needs for this problem;
+ * 0 if the problem is invalid.  Pure host arithmetic.  The backward figure covers the
+ * case that grad_pairwise is requested. */
+size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward);
+
+/* Checks a problem description the way the entry points do; no GPU work. */
+int mrf_validate(const mrf_problem *prob, int algo);
+
+/* Forward propagation of ISGMR (Alg. 1; update Eq. isgmr, reparametrisation
+ * Eq. isgmr-norm, final costs Eq. isgmr-aggregation, labelling Eq. disp).
+ *   cost      DEVICE out, required
+ *   labels    DEVICE out, may be NULL
+ *   p, q      DEVICE out, required: the indices the backward pass replays (Sec. 4)
+ *   messages  DEVICE out, may be NULL: final messages m of all directions */
+int mrf_isgmr_forward(const mrf_problem *prob, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                      float *messages, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Forward propagation of TRWP (Alg. 2; update Eq. trwp).  Directions are swept one after
+ * the other in the order of prob->dirs, messages are updated in place.  Same outputs. */
+int mrf_trwp_forward(const mrf_problem *prob, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                     float *messages, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backpropagation of ISGMR (Alg. 3, Appendix A; gradients Eq. supp-gradient-unary,
+ * supp-gradient-edge, supp-gradient-smoothness).
+ *   grad_cost         DEVICE in,  dL/dc
+ *   p, q              DEVICE in,  as written by mrf_isgmr_forward for the same problem
+ *   grad_unary        DEVICE out, required
+ *   grad_edge_weight  DEVICE out, may be NULL.  One value per directed edge; a caller that
+ *                     stores theta_ij = theta_ji once adds the two directed entries itself.
+ *   grad_pairwise     DEVICE out, may be NULL */
+int mrf_isgmr_backward(const mrf_problem *prob, const float *grad_cost, const uint8_t *p, const uint8_t *q,
+                       float *grad_unary, float *grad_edge_weight, float *grad_pairwise,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backpropagation of TRWP (Alg. 4, Appendix A).  Directions are swept in the reverse of
+ * the forward order.  rho does not enter the pairwise gradients.  Same arguments. */
+int mrf_trwp_backward(const mrf_problem *prob, const float *grad_cost, const uint8_t *p, const uint8_t *q,
+                      float *grad_unary, float *grad_edge_weight, float *grad_pairwise,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Scanline geometry used by the kernels ("tree parallelisation", Sec. 3.5 and Appendix C):
+ * the scanlines of direction (dh,dw) are the maximal in-grid chains i, i+r, i+2r, ...
+ * mrf_scanline_count returns how many there are in one H x W image (for |dh| = 1 this is
+ * W + (H-1)|dw|, Eq. supp-wide); mrf_scanline_head gives the first node and the number of
+ * nodes of scanline t in [0, count).  Host arithmetic, shared with the device code.
+ * Returns MRF_OK or MRF_ERR_BAD_SHAPE / MRF_ERR_BAD_DIRECTIONS. */
+int64_t mrf_scanline_count(int32_t H, int32_t W, int32_t dh, int32_t dw);
+int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
+                      int32_t *y0, int32_t *x0, int32_t *len);
+
+/* Static text for a status code. */
+const char *mrf_strerror(int status);
+
+/* Process-global tuning knobs for experiments; results never depend on them.
+ *   knob 0: source labels per wavefront in the dense forward sweep (8, 16 or 32; 0 = heuristic)
+ * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
+int mrf_tune(int knob, int value);
+
+/* Library version, e.g. "0.1.0". */
+const char *mrf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MRFMP_H */

@@ -1,0 +1,40 @@
+"""Build step of libmrfmp: one hipcc command, in-tree output next to the sources."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+CSRC = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+LIB_PATH = os.path.join(CSRC, "libmrfmp.so")
+SOURCES = ["mrfmp.hip"]
+HEADERS = ["mrfmp_device.h", "mrfmp_fwd.h", "mrfmp_bwd.h", "../../include/mrfmp.h"]
+
+# -ffp-contract=off: the only fused multiply-add is the explicit one of the message update,
+#   so that floating point decisions (argmins) match a plain C evaluation order.
+# packed-fp32 instructions are switched off for the test machines of machines.
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall"]
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB_PATH):
+        return True
+    t = os.path.getmtime(LIB_PATH)
+    return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile libmrfmp.so for gfx950 (cross-compiles without a GPU)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB_PATH, *SOURCES]
+    res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building libmrfmp.so")
+    return LIB_PATH
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

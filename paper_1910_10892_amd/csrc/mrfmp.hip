@@ -1,0 +1,390 @@
+// libmrfmp host side: argument checks, workspace layout and launch schedules of the
+// ISGMR / TRWP forward and backward passes (Alg. 1-4).  Allocates nothing.
+#include "../../include/mrfmp.h"
+#include "mrfmp_device.h"
+#include "mrfmp_fwd.h"
+#include "mrfmp_bwd.h"
+
+#include <string.h>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr long long kGradVSlots = 1024;   // wavefront-private V-gradient accumulators
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int check_problem(const mrf_problem *pr, int algo, bool forward)
+{
+    if (!pr) return MRF_ERR_NULL_POINTER;
+    if (algo != MRF_ISGMR && algo != MRF_TRWP) return MRF_ERR_BAD_ALGORITHM;
+    if (pr->B < 1 || pr->H < 1 || pr->W < 1) return MRF_ERR_BAD_SHAPE;
+    if (pr->L < 1 || pr->L > MRF_MAX_LABELS) return MRF_ERR_BAD_LABELS;
+    if (pr->K < 1) return MRF_ERR_BAD_ITERATIONS;
+    if (pr->R < 1 || pr->R > MRF_MAX_DIRECTIONS) return MRF_ERR_BAD_DIRECTIONS;
+    if (!pr->dirs) return MRF_ERR_NULL_POINTER;
+    for (int r = 0; r < pr->R; ++r) {
+        const int dh = pr->dirs[2 * r], dw = pr->dirs[2 * r + 1];
+        if (dh == 0 && dw == 0) return MRF_ERR_BAD_DIRECTIONS;
+        for (int d = 0; d < r; ++d)
+            if (pr->dirs[2 * d] == dh && pr->dirs[2 * d + 1] == dw) return MRF_ERR_BAD_DIRECTIONS;
+    }
+    const long long N = (long long)pr->B * pr->H * pr->W;
+    if (N > 0x7fffffffLL) return MRF_ERR_BAD_SHAPE;
+    if (!pr->pairwise) return MRF_ERR_NULL_POINTER;
+    if (forward && !pr->unary) return MRF_ERR_NULL_POINTER;
+    if (algo == MRF_TRWP && !pr->rho) return MRF_ERR_NULL_POINTER;
+    if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && pr->pairwise_kind != MRF_PAIRWISE_TRUNC_LINEAR &&
+        pr->pairwise_kind != MRF_PAIRWISE_TRUNC_QUADRATIC)
+        return MRF_ERR_BAD_PAIRWISE_KIND;
+    if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && !(pr->trunc > 0.0f)) return MRF_ERR_BAD_PAIRWISE_KIND;
+    return MRF_OK;
+}
+
+void fill_geom(const mrf_problem *pr, MrfGeom &g)
+{
+    memset(&g, 0, sizeof(g));
+    g.B = pr->B; g.H = pr->H; g.W = pr->W; g.L = pr->L; g.R = pr->R;
+    g.N = (long long)pr->B * pr->H * pr->W;
+    for (int r = 0; r < pr->R; ++r) {
+        g.dh[r] = pr->dirs[2 * r];
+        g.dw[r] = pr->dirs[2 * r + 1];
+    }
+    for (int r = 0; r < pr->R; ++r) {
+        g.opp[r] = -1;
+        for (int d = 0; d < pr->R; ++d)
+            if (g.dh[d] == -g.dh[r] && g.dw[d] == -g.dw[r]) g.opp[r] = d;
+        g.nscan[r] = (int)mrf_geom_scanlines(g.H, g.W, g.dh[r], g.dw[r]);
+    }
+}
+
+size_t msg_bytes(const mrf_problem *pr)
+{
+    return align_up((size_t)pr->R * pr->B * pr->H * pr->W * pr->L * sizeof(float));
+}
+
+size_t gradv_bytes(const mrf_problem *pr)
+{
+    return align_up((size_t)kGradVSlots * pr->L * pr->L * sizeof(float));
+}
+
+// ---- forward sweep dispatch -------------------------------------------------------------
+// tuning knobs (0 = heuristic)
+int g_tune_mch = 0;
+
+template <int LP, int MCH>
+hipError_t launch_fwd(const MrfFwdParams &P, long long blocks, hipStream_t st)
+{
+    const int NW = P.NW;
+    const size_t lds = (size_t)NW * NW * MCH * sizeof(float) + (size_t)2 * NW * 64 * LP * (sizeof(float) + 1);
+    hipLaunchKernelGGL((mrf_fwd_sweep<LP, MCH>), dim3((unsigned)blocks), dim3(64 * NW), lds, st, P);
+    return hipGetLastError();
+}
+
+int pick_mch(int L, int LP)
+{
+    int mch = g_tune_mch;
+    if (mch != 8 && mch != 16 && mch != 32) mch = (L <= 32) ? 32 : (L <= 64 ? 16 : 32);
+    while (mch < 32 && (L + mch - 1) / mch > 16) mch *= 2;       // at most 16 wavefronts
+    while (mch < 4 * LP) mch *= 2;                                // launch bound 64*(64*LP/MCH) <= 1024
+    if (LP == 3 && mch == 8) mch = 16;
+    return mch;
+}
+
+hipError_t dispatch_fwd(MrfFwdParams &P, long long blocks, hipStream_t st)
+{
+    const int L = P.g.L;
+    const int LP = (L + 63) / 64;
+    const int mch = pick_mch(L, LP);
+    P.NW = (L + mch - 1) / mch;
+#define MRF_CASE(lp, m) if (LP == lp && mch == m) return launch_fwd<lp, m>(P, blocks, st);
+    MRF_CASE(1, 8) MRF_CASE(1, 16) MRF_CASE(1, 32)
+    MRF_CASE(2, 8) MRF_CASE(2, 16) MRF_CASE(2, 32)
+    MRF_CASE(3, 16) MRF_CASE(3, 32)
+    MRF_CASE(4, 16) MRF_CASE(4, 32)
+#undef MRF_CASE
+    return hipErrorInvalidValue;
+}
+
+int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                float *messages, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_problem(pr, algo, true);
+    if (rc != MRF_OK) return rc;
+    if (!cost || !p || !q) return MRF_ERR_NULL_POINTER;
+    const size_t need = mrf_workspace_bytes(pr, algo, 0);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return workspace ? MRF_ERR_WORKSPACE_TOO_SMALL : MRF_ERR_NULL_POINTER;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    MrfFwdParams P;
+    memset(&P, 0, sizeof(P));
+    fill_geom(pr, P.g);
+    const long long N = P.g.N;
+    const int R = pr->R, L = pr->L, K = pr->K;
+    P.algo = algo;
+    P.unary = pr->unary; P.V = pr->pairwise; P.w = pr->edge_weight; P.w_scalar = pr->edge_weight_scalar;
+    for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP) ? pr->rho[r] : 1.0f;
+
+    float *bufA = (float *)workspace;
+    float *bufB = (float *)((char *)workspace + msg_bytes(pr));
+    const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
+    float *final_m = nullptr;
+
+    if (algo == MRF_ISGMR) {
+        // all directions of one iteration in one launch; messages ping-pong between two buffers
+        P.r_first = 0; P.r_count = R;
+        long long blocks = 0;
+        for (int r = 0; r < R; ++r) { P.blk_begin[r] = blocks; blocks += (long long)pr->B * P.g.nscan[r]; }
+        P.blk_begin[R] = blocks;
+        for (int k = 0; k < K; ++k) {
+            P.m_in = (k & 1) ? bufB : bufA;      // written by iteration k-1 (unused when k = 0)
+            P.m_out = (k & 1) ? bufA : bufB;
+            P.live_mask = k == 0 ? 0u : 0xffffffffu;
+            P.p = p + (size_t)k * pk;
+            P.q = q + (size_t)k * qk;
+            if (dispatch_fwd(P, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+            final_m = P.m_out;
+        }
+    } else {
+        // one launch per (iteration, direction); messages updated in place
+        P.m_in = bufA; P.m_out = bufA;
+        for (int k = 0; k < K; ++k) {
+            for (int r = 0; r < R; ++r) {
+                P.r_first = r; P.r_count = 1;
+                P.blk_begin[0] = 0;
+                const long long blocks = (long long)pr->B * P.g.nscan[r];
+                P.blk_begin[1] = blocks;
+                // in the first iteration the directions after r have not been written yet: they read as 0
+                P.live_mask = k == 0 ? ((1u << r) - 1u) : 0xffffffffu;
+                P.p = p + (size_t)k * pk;
+                P.q = q + (size_t)k * qk;
+                if (dispatch_fwd(P, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+            }
+        }
+        final_m = bufA;
+    }
+
+    MrfAggParams A;
+    A.N = N; A.L = L; A.R = R;
+    A.unary = pr->unary; A.m = final_m; A.cost = cost; A.labels = labels;
+    long long ablocks = (N + 3) / 4;
+    if (ablocks > 65536) ablocks = 65536;
+    hipLaunchKernelGGL(mrf_aggregate, dim3((unsigned)ablocks), dim3(256), 0, st, A);
+    if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+    if (messages) {
+        if (hipMemcpyAsync(messages, final_m, pk * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return MRF_ERR_HIP;
+    }
+    return MRF_OK;
+}
+
+template <int LP>
+hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL((mrf_bwd_sweep<LP>), dim3((unsigned)blocks), dim3(64 * MRF_BWD_WAVES), 0, st, P);
+    return hipGetLastError();
+}
+
+hipError_t dispatch_bwd(const MrfBwdParams &P, hipStream_t st)
+{
+    long long blocks = (P.total_scanlines + MRF_BWD_WAVES - 1) / MRF_BWD_WAVES;
+    if (P.gV && blocks > kGradVSlots / MRF_BWD_WAVES) blocks = kGradVSlots / MRF_BWD_WAVES;
+    const int LP = (P.g.L + 63) / 64;
+    switch (LP) {
+    case 1: return launch_bwd<1>(P, blocks, st);
+    case 2: return launch_bwd<2>(P, blocks, st);
+    case 3: return launch_bwd<3>(P, blocks, st);
+    default: return launch_bwd<4>(P, blocks, st);
+    }
+}
+
+hipError_t fill(float *dst, long long n, float v, hipStream_t st)
+{
+    long long blocks = (n + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(mrf_fill_f32, dim3((unsigned)blocks), dim3(256), 0, st, dst, n, v);
+    return hipGetLastError();
+}
+
+hipError_t broadcast(const float *src, float *dst, long long n, int copies, hipStream_t st)
+{
+    long long blocks = (n + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(mrf_broadcast_f32, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, n, copies);
+    return hipGetLastError();
+}
+
+int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const uint8_t *p, const uint8_t *q,
+                 float *grad_unary, float *grad_w, float *grad_V, void *workspace, size_t workspace_bytes,
+                 void *hip_stream)
+{
+    int rc = check_problem(pr, algo, false);
+    if (rc != MRF_OK) return rc;
+    if (!grad_cost || !p || !q || !grad_unary) return MRF_ERR_NULL_POINTER;
+    const size_t need = mrf_workspace_bytes(pr, algo, 1);
+    if (!workspace) return MRF_ERR_NULL_POINTER;
+    if (workspace_bytes < need) return MRF_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    MrfBwdParams P;
+    memset(&P, 0, sizeof(P));
+    fill_geom(pr, P.g);
+    const long long N = P.g.N;
+    const int R = pr->R, L = pr->L, K = pr->K;
+    const long long NL = N * L;
+    P.algo = algo;
+    P.V = pr->pairwise; P.w = pr->edge_weight; P.w_scalar = pr->edge_weight_scalar;
+    for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP) ? pr->rho[r] : 1.0f;
+    P.gw = grad_w;
+    const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
+
+    char *ws = (char *)workspace;
+    float *buf0 = (float *)ws;                       // ISGMR: grad m-hat   TRWP: grad m
+    float *buf1 = (float *)(ws + msg_bytes(pr));     // ISGMR: S
+    float *gvslots = (float *)(ws + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
+
+    if (grad_w && fill(grad_w, (long long)R * N, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
+    if (grad_V) {
+        P.gV = gvslots;
+        if (fill(gvslots, kGradVSlots * L * L, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
+    }
+
+    if (algo == MRF_ISGMR) {
+        P.r_first = 0; P.r_count = R;
+        long long tot = 0;
+        for (int r = 0; r < R; ++r) { P.blk_begin[r] = tot; tot += (long long)pr->B * P.g.nscan[r]; }
+        P.blk_begin[R] = tot;
+        P.total_scanlines = tot;
+        P.S = buf1;
+        MrfCombineParams C;
+        memset(&C, 0, sizeof(C));
+        C.NL = NL; C.R = R;
+        for (int r = 0; r < R; ++r) C.opp[r] = P.g.opp[r];
+        C.S = buf1; C.gc = grad_cost; C.gunary = grad_unary;
+        long long cblocks = (NL + 255) / 256;
+        if (cblocks > 32768) cblocks = 32768;
+        for (int k = K - 1; k >= 0; --k) {
+            if (k == K - 1) { P.gin = grad_cost; P.gin_stride = 0; }   // back Eq. isgmr-aggregation
+            else { P.gin = buf0; P.gin_stride = NL; }
+            P.p = p + (size_t)k * pk;
+            P.q = q + (size_t)k * qk;
+            if (dispatch_bwd(P, st) != hipSuccess) return MRF_ERR_HIP;
+            C.first = (k == K - 1);
+            C.ghat = (k > 0) ? buf0 : nullptr;
+            hipLaunchKernelGGL(mrf_isgmr_bwd_combine, dim3((unsigned)cblocks), dim3(256), 0, st, C);
+            if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+        }
+    } else {
+        P.G = buf0;
+        P.gunary = grad_unary;
+        if (broadcast(grad_cost, buf0, NL, R, st) != hipSuccess) return MRF_ERR_HIP;
+        if (broadcast(grad_cost, grad_unary, NL, 1, st) != hipSuccess) return MRF_ERR_HIP;
+        for (int k = K - 1; k >= 0; --k) {
+            for (int r = R - 1; r >= 0; --r) {      // reverse of the forward direction order
+                P.r_first = r; P.r_count = 1;
+                P.blk_begin[0] = 0;
+                P.total_scanlines = (long long)pr->B * P.g.nscan[r];
+                P.blk_begin[1] = P.total_scanlines;
+                P.p = p + (size_t)k * pk;
+                P.q = q + (size_t)k * qk;
+                if (dispatch_bwd(P, st) != hipSuccess) return MRF_ERR_HIP;
+            }
+        }
+    }
+    if (grad_V) {
+        const long long n = (long long)L * L;
+        hipLaunchKernelGGL(mrf_reduce_slots, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                           (const float *)gvslots, grad_V, n, kGradVSlots);
+        if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+    }
+    return MRF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward)
+{
+    if (check_problem(prob, algo, false) != MRF_OK) return 0;
+    if (!backward) return (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob);
+    return (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob) + gradv_bytes(prob);
+}
+
+int mrf_validate(const mrf_problem *prob, int algo) { return check_problem(prob, algo, true); }
+
+int mrf_isgmr_forward(const mrf_problem *prob, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                      float *messages, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_forward(prob, MRF_ISGMR, cost, labels, p, q, messages, workspace, workspace_bytes, hip_stream);
+}
+
+int mrf_trwp_forward(const mrf_problem *prob, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                     float *messages, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_forward(prob, MRF_TRWP, cost, labels, p, q, messages, workspace, workspace_bytes, hip_stream);
+}
+
+int mrf_isgmr_backward(const mrf_problem *prob, const float *grad_cost, const uint8_t *p, const uint8_t *q,
+                       float *grad_unary, float *grad_edge_weight, float *grad_pairwise,
+                       void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_backward(prob, MRF_ISGMR, grad_cost, p, q, grad_unary, grad_edge_weight, grad_pairwise,
+                        workspace, workspace_bytes, hip_stream);
+}
+
+int mrf_trwp_backward(const mrf_problem *prob, const float *grad_cost, const uint8_t *p, const uint8_t *q,
+                      float *grad_unary, float *grad_edge_weight, float *grad_pairwise,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_backward(prob, MRF_TRWP, grad_cost, p, q, grad_unary, grad_edge_weight, grad_pairwise,
+                        workspace, workspace_bytes, hip_stream);
+}
+
+int64_t mrf_scanline_count(int32_t H, int32_t W, int32_t dh, int32_t dw)
+{
+    if (H < 1 || W < 1) return MRF_ERR_BAD_SHAPE;
+    if (dh == 0 && dw == 0) return MRF_ERR_BAD_DIRECTIONS;
+    return mrf_geom_scanlines(H, W, dh, dw);
+}
+
+int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
+                      int32_t *y0, int32_t *x0, int32_t *len)
+{
+    if (!y0 || !x0 || !len) return MRF_ERR_NULL_POINTER;
+    if (H < 1 || W < 1) return MRF_ERR_BAD_SHAPE;
+    if (dh == 0 && dw == 0) return MRF_ERR_BAD_DIRECTIONS;
+    if (t < 0 || t >= mrf_geom_scanlines(H, W, dh, dw)) return MRF_ERR_BAD_SHAPE;
+    int a, b, c;
+    mrf_geom_head(H, W, dh, dw, t, a, b, c);
+    *y0 = a; *x0 = b; *len = c;
+    return MRF_OK;
+}
+
+const char *mrf_strerror(int status)
+{
+    switch (status) {
+    case MRF_OK: return "ok";
+    case MRF_ERR_NULL_POINTER: return "a required pointer is NULL";
+    case MRF_ERR_BAD_SHAPE: return "B, H, W must be >= 1 and B*H*W < 2^31";
+    case MRF_ERR_BAD_LABELS: return "L must be in [1, 256]";
+    case MRF_ERR_BAD_ITERATIONS: return "K must be >= 1";
+    case MRF_ERR_BAD_DIRECTIONS: return "R must be in [1, 16], steps non-zero and distinct";
+    case MRF_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than mrf_workspace_bytes()";
+    case MRF_ERR_BAD_PAIRWISE_KIND: return "unknown pairwise_kind or invalid trunc";
+    case MRF_ERR_BAD_ALGORITHM: return "algo must be MRF_ISGMR or MRF_TRWP";
+    case MRF_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    default: return "unknown status";
+    }
+}
+
+const char *mrf_version(void) { return "0.1.0"; }
+
+int mrf_tune(int knob, int value)
+{
+    if (knob == 0) { g_tune_mch = value; return MRF_OK; }
+    return MRF_ERR_BAD_ALGORITHM;
+}
+
+}  // extern "C"

@@ -1,0 +1,129 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, rejects bad problems before touching the device, and its scanline
+geometry (Appendix C) enumerates exactly the maximal in-grid chains."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1910_10892_amd as mrf
+from paper_1910_10892_amd.mrfmp import _CProblem
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mrfmp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mrf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mrf.load_library()
+    names = declared_functions()
+    assert {"mrf_isgmr_forward", "mrf_isgmr_backward", "mrf_trwp_forward", "mrf_trwp_backward",
+            "mrf_workspace_bytes", "mrf_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert mrf.mrf_version().count(".") == 2
+
+
+def _cprob(**kw):
+    dirs = np.array(kw.pop("dirs", [(0, 1), (0, -1), (1, 0), (-1, 0)]), np.int32)
+    rho = np.full(len(dirs), 0.5, np.float32)
+    c = _CProblem()
+    c.B, c.H, c.W, c.L, c.R, c.K = 1, 8, 8, 4, len(dirs), 2
+    c.dirs = dirs.ctypes.data
+    c.unary = 0x1000      # never dereferenced by the host checks
+    c.pairwise = 0x1000
+    c.edge_weight = None
+    c.edge_weight_scalar = 1.0
+    c.rho = rho.ctypes.data
+    c.pairwise_kind = 0
+    for k, v in kw.items():
+        setattr(c, k, v)
+    c._keep = (dirs, rho)
+    return c
+
+
+def test_validation_codes_without_gpu():
+    lib = mrf.load_library()
+    V = lambda c, algo=0: lib.mrf_validate(ctypes.byref(c), algo)
+    assert V(_cprob()) == 0
+    assert V(_cprob(), 1) == 0
+    assert V(_cprob(), 7) == -8
+    assert V(_cprob(L=0)) == -3 and V(_cprob(L=257)) == -3
+    assert V(_cprob(L=256)) == 0
+    assert V(_cprob(K=0)) == -4
+    assert V(_cprob(H=0)) == -2
+    assert V(_cprob(B=4096, H=1024, W=1024)) == -2
+    assert V(_cprob(dirs=[(0, 0)])) == -5
+    assert V(_cprob(dirs=[(0, 1), (0, 1)])) == -5
+    assert V(_cprob(R=17)) == -5
+    assert V(_cprob(unary=None)) == -1
+    assert V(_cprob(pairwise=None)) == -1
+    assert V(_cprob(rho=None), 1) == -1 and V(_cprob(rho=None), 0) == 0
+    assert V(_cprob(pairwise_kind=9)) == -7
+    assert V(_cprob(pairwise_kind=1, trunc=0.0)) == -7
+    assert lib.mrf_validate(None, 0) == -1
+    for code in range(0, -10, -1):
+        assert mrf.mrf_strerror(code) != "unknown status"
+
+
+def test_entry_points_reject_before_any_gpu_work():
+    """NULL outputs / short workspaces are reported before a kernel launch is attempted, so
+    this runs on a machine without a GPU."""
+    lib = mrf.load_library()
+    c = _cprob()
+    need = lib.mrf_workspace_bytes(ctypes.byref(c), 0, 0)
+    assert need >= 2 * 4 * 64 * 4 * 4
+    bad = _cprob(L=0)
+    assert lib.mrf_workspace_bytes(ctypes.byref(bad), 0, 0) == 0
+    fake = ctypes.c_void_p(0x1000)
+    for algo, name in ((0, "mrf_isgmr_forward"), (1, "mrf_trwp_forward")):
+        f = getattr(lib, name)
+        need = lib.mrf_workspace_bytes(ctypes.byref(c), algo, 0)
+        assert f(ctypes.byref(c), None, None, fake, fake, None, fake, need, None) == -1
+        assert f(ctypes.byref(c), fake, None, fake, fake, None, fake, need - 1, None) == -6
+        assert f(ctypes.byref(c), fake, None, fake, fake, None, None, 0, None) == -1
+        assert f(ctypes.byref(bad), fake, None, fake, fake, None, fake, need, None) == -3
+    for algo, name in ((0, "mrf_isgmr_backward"), (1, "mrf_trwp_backward")):
+        f = getattr(lib, name)
+        needb = lib.mrf_workspace_bytes(ctypes.byref(c), algo, 1)
+        assert f(ctypes.byref(c), None, fake, fake, fake, None, None, fake, needb, None) == -1
+        assert f(ctypes.byref(c), fake, fake, fake, fake, None, None, fake, needb - 1, None) == -6
+
+
+@pytest.mark.parametrize("H,W", [(1, 1), (1, 7), (6, 1), (5, 9), (9, 5), (4, 4)])
+def test_scanline_geometry_matches_definition(H, W):
+    for dh in range(-3, 4):
+        for dw in range(-3, 4):
+            if dh == 0 and dw == 0:
+                continue
+            heads = {(y, x) for y in range(H) for x in range(W)
+                     if not (0 <= y - dh < H and 0 <= x - dw < W)}
+            n = mrf.mrf_scanline_count(H, W, dh, dw)
+            assert n == len(heads)
+            seen = set()
+            covered = 0
+            for t in range(n):
+                y0, x0, ln = mrf.mrf_scanline_head(H, W, dh, dw, t)
+                assert (y0, x0) in heads and (y0, x0) not in seen
+                seen.add((y0, x0))
+                y, x, k = y0, x0, 0
+                while 0 <= y < H and 0 <= x < W:
+                    y += dh; x += dw; k += 1
+                assert ln == k
+                covered += ln
+            assert covered == H * W     # each node lies on exactly one scanline
+            if abs(dh) == 1 and abs(dw) <= W:
+                assert n == W + (H - 1) * abs(dw)      # Eq. supp-wide
+
+
+def test_scanline_geometry_errors():
+    assert mrf.mrf_scanline_count(0, 4, 0, 1) == -2
+    assert mrf.mrf_scanline_count(4, 4, 0, 0) == -5
+    with pytest.raises(mrf.MrfError):
+        mrf.mrf_scanline_head(4, 4, 0, 1, 4)

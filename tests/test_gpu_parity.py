@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path (through the C-ABI library) against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Bar: p, q, labels bit-exact (the argmins are decided in float32 on both sides, lowest
+index on ties); costs and messages within 1e-5 relative / 1e-4 absolute (they are in fact
+expected to be identical: same operations in the same order); gradients within the same
+tolerance of the float32 oracle -- or, where float32 summation order makes the float32
+oracle itself drift by about that much, of the exact (double) replay of the same indices.
+"""
+import numpy as np
+import pytest
+
+from mrf_inputs import DIRS4, DIRS8, DIRS16, make_config, random_problem
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-4
+
+
+def oracle_forward(oracle, pr, threads=False):
+    return oracle.forward(pr.algo, pr.unary, pr.pairwise, pr.dirs, pr.K, edge_weight=pr.edge_weight,
+                          edge_weight_scalar=pr.edge_weight_scalar, rho=pr.rho, threads=threads)
+
+
+def oracle_backward(oracle, pr, p, q, dtype=np.float32):
+    c = lambda a: None if a is None else a.astype(dtype)
+    return oracle.backward(pr.algo, pr.shape, c(pr.pairwise), pr.dirs, pr.K, c(pr.grad_cost), p, q,
+                           edge_weight=c(pr.edge_weight), edge_weight_scalar=pr.edge_weight_scalar,
+                           rho=pr.rho, dtype=dtype)
+
+
+def check_forward(g, f):
+    np.testing.assert_array_equal(g.p, f.p)
+    np.testing.assert_array_equal(g.q, f.q)
+    np.testing.assert_array_equal(g.labels, f.labels)
+    np.testing.assert_allclose(g.messages, f.messages, rtol=RTOL, atol=ATOL)
+    np.testing.assert_allclose(g.cost, f.cost, rtol=RTOL, atol=ATOL)
+
+
+def check_grad(name, got, ref32, ref64):
+    assert np.isfinite(got).all(), name
+    e32 = np.abs(got.astype(np.float64) - ref32) / (ATOL + RTOL * np.abs(ref32))
+    e64 = np.abs(got.astype(np.float64) - ref64) / (ATOL + RTOL * np.abs(ref64))
+    worst = np.minimum(e32, e64).max()
+    assert worst <= 1.0, "%s: worst error/tolerance %.3f (vs f32 oracle %.3f, vs exact %.3f)" % (
+        name, worst, e32.max(), e64.max())
+
+
+def check_backward(g, b32, b64):
+    check_grad("grad_unary", g.grad_unary, b32.grad_unary, b64.grad_unary)
+    check_grad("grad_edge_weight", g.grad_edge_weight, b32.grad_edge_weight, b64.grad_edge_weight)
+    check_grad("grad_pairwise", g.grad_pairwise, b32.grad_pairwise, b64.grad_pairwise)
+
+
+def full_check(oracle, pr, threads=False):
+    from gpu_harness import run_gpu
+    g = run_gpu(pr)
+    f = oracle_forward(oracle, pr, threads=threads)
+    check_forward(g, f)
+    b32 = oracle_backward(oracle, pr, f.p, f.q, np.float32)
+    b64 = oracle_backward(oracle, pr, f.p, f.q, np.float64)
+    check_backward(g, b32, b64)
+    return g
+
+
+CONFIG_CASES = [
+    (1, None, "isgmr", None), (1, None, "trwp", None),
+    (2, (24, 40), "trwp", None), (2, (24, 40), "isgmr", None),
+    (3, (12, 20), "isgmr", None), (3, (12, 20), "trwp", None),
+    (4, (10, 12), "trwp", 3), (4, (10, 12), "isgmr", 2),
+    (5, (24, 32), "isgmr", None), (5, (24, 32), "trwp", None),
+]
+
+
+@pytest.mark.parametrize("index,crop,algo,K", CONFIG_CASES)
+def test_benchmark_configs_cropped(oracle, index, crop, algo, K):
+    print("case config", index, crop, algo, K, flush=True)
+    pr = make_config(index, crop=crop, algo=algo, K=K)
+    full_check(oracle, pr)
+
+
+RANDOM_CASES = [
+    # seed, algo, B, H, W, L, dirs, K, integer_valued, per_edge
+    (1, "isgmr", 1, 5, 7, 1, DIRS4, 2, False, True),
+    (2, "trwp", 1, 5, 7, 2, DIRS4, 2, False, True),
+    (3, "isgmr", 2, 6, 5, 33, DIRS8, 2, False, True),
+    (4, "trwp", 2, 6, 5, 65, DIRS8, 2, False, False),
+    (5, "isgmr", 1, 7, 6, 100, DIRS16, 2, False, True),
+    (6, "trwp", 1, 7, 6, 129, DIRS16, 2, False, True),
+    (7, "isgmr", 1, 4, 9, 200, DIRS4, 3, False, False),
+    (8, "trwp", 1, 9, 4, 255, DIRS4, 2, False, True),
+    (9, "isgmr", 1, 8, 8, 7, DIRS8, 3, True, True),      # integer data: many ties
+    (10, "trwp", 1, 8, 8, 70, DIRS4, 3, True, True),
+    (11, "isgmr", 1, 1, 12, 12, DIRS8, 2, False, True),   # one row: vertical/diagonal scanlines have one node
+    (12, "trwp", 1, 12, 1, 12, DIRS8, 2, False, True),    # one column
+    (13, "isgmr", 1, 6, 6, 16, [(0, 1), (1, 0)], 3, False, True),        # no opposite directions
+    (14, "trwp", 1, 6, 6, 16, [(0, 1), (1, 0), (-1, 0)], 3, False, True),
+    (15, "trwp", 3, 5, 5, 64, DIRS4, 2, False, True),
+    (16, "isgmr", 1, 1, 1, 5, DIRS4, 2, False, True),     # single node: nothing to pass
+]
+
+
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: "seed%d" % c[0])
+def test_random_shapes(oracle, case):
+    print("case random", case[:8], flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv, pe = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=pe,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    full_check(oracle, pr)
+
+
+@pytest.mark.parametrize("algo", ["isgmr", "trwp"])
+def test_asymmetric_pairwise(oracle, algo):
+    print("case asymmetric", algo, flush=True)
+    pr = random_problem(21, algo, 1, 6, 7, 40, DIRS8, 2, symmetric=False)
+    full_check(oracle, pr)
+
+
+@pytest.mark.parametrize("mch", [8, 16, 32])
+def test_wavefront_split_does_not_change_results(oracle, mch):
+    """The number of source labels per wavefront is a tuning knob; p, q and messages must not
+    depend on it."""
+    import paper_1910_10892_amd as mrf
+    print("case tune", mch, flush=True)
+    try:
+        assert mrf.mrf_tune(0, mch) == 0
+        for L in (48, 96, 130):
+            pr = random_problem(30 + L, "trwp", 1, 5, 6, L, DIRS4, 2)
+            full_check(oracle, pr)
+    finally:
+        mrf.mrf_tune(0, 0)
+
+
+def test_optional_outputs_may_be_null(oracle):
+    from gpu_harness import GpuProblem
+    import torch
+    print("case optional outputs", flush=True)
+    for algo in ("isgmr", "trwp"):
+        pr = make_config(1, algo=algo, K=2)
+        full = GpuProblem(pr)
+        full.forward(); full.backward()
+        ref = full.results()
+        g = GpuProblem(pr, want_messages=False)
+        fn = __import__("paper_1910_10892_amd").mrf_isgmr_forward if algo == "isgmr" else \
+            __import__("paper_1910_10892_amd").mrf_trwp_forward
+        fn(g.prob, g.cost, None, g.p, g.q, None, g.workspace)
+        g.backward(want_w=False, want_V=False)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(g.cost.cpu().numpy(), ref.cost)
+        np.testing.assert_array_equal(g.p.cpu().numpy(), ref.p)
+        np.testing.assert_array_equal(g.grad_unary.cpu().numpy(), ref.grad_unary)
+
+
+def test_backward_is_reproducible_run_to_run():
+    from gpu_harness import GpuProblem
+    print("case reproducible", flush=True)
+    for idx, crop, algo in ((2, (24, 40), "trwp"), (5, (24, 32), "isgmr")):
+        pr = make_config(idx, crop=crop, algo=algo)
+        g = GpuProblem(pr)
+        g.forward(); g.backward()
+        a = g.results()
+        g.poison_outputs()
+        g.forward(); g.backward()
+        b = g.results()
+        for name in ("cost", "p", "q", "grad_unary", "grad_edge_weight", "grad_pairwise"):
+            np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
+
+
+def test_workspace_too_small_is_an_error_not_a_fault():
+    from gpu_harness import GpuProblem
+    import paper_1910_10892_amd as mrf
+    print("case small workspace", flush=True)
+    pr = make_config(1)
+    g = GpuProblem(pr)
+    small = g.workspace[: 256]
+    with pytest.raises(mrf.MrfError) as ei:
+        mrf.mrf_isgmr_forward(g.prob, g.cost, g.labels, g.p, g.q, g.messages, small)
+    assert ei.value.status == -6
+
+
+def test_full_size_stereo_config_trwp(oracle):
+    """The configuration the bench times (TRWP, 256x512, L = 96, K = 5), whole grid, in the
+    launch configuration the bench uses; oracle forward on all host threads (bit-identical
+    to one thread, asserted in the CPU suite)."""
+    print("case full config 2", flush=True)
+    pr = make_config(2)
+    full_check(oracle, pr, threads=True)
