@@ -65,7 +65,7 @@ size_t msg_bytes(const mrf_problem *pr)
 
 size_t gradv_bytes(const mrf_problem *pr)
 {
-    return align_up((size_t)kGradVSlots * pr->L * pr->L * sizeof(float));
+    return align_up((size_t)kGradVSlots * pr->L * pr->L * sizeof(double));
 }
 
 // ---- forward sweep dispatch -------------------------------------------------------------
@@ -207,6 +207,14 @@ hipError_t fill(float *dst, long long n, float v, hipStream_t st)
     return hipGetLastError();
 }
 
+hipError_t fill64(double *dst, long long n, hipStream_t st)
+{
+    long long blocks = (n + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(mrf_fill_f64, dim3((unsigned)blocks), dim3(256), 0, st, dst, n, 0.0);
+    return hipGetLastError();
+}
+
 hipError_t broadcast(const float *src, float *dst, long long n, int copies, hipStream_t st)
 {
     long long blocks = (n + 255) / 256;
@@ -242,12 +250,12 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     char *ws = (char *)workspace;
     float *buf0 = (float *)ws;                       // ISGMR: grad m-hat   TRWP: grad m
     float *buf1 = (float *)(ws + msg_bytes(pr));     // ISGMR: S
-    float *gvslots = (float *)(ws + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
+    double *gvslots = (double *)(ws + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
 
     if (grad_w && fill(grad_w, (long long)R * N, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
     if (grad_V) {
         P.gV = gvslots;
-        if (fill(gvslots, kGradVSlots * L * L, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
+        if (fill64(gvslots, kGradVSlots * L * L, st) != hipSuccess) return MRF_ERR_HIP;
     }
 
     if (algo == MRF_ISGMR) {
@@ -295,7 +303,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     if (grad_V) {
         const long long n = (long long)L * L;
         hipLaunchKernelGGL(mrf_reduce_slots, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                           (const float *)gvslots, grad_V, n, kGradVSlots);
+                           (const double *)gvslots, grad_V, n, kGradVSlots);
         if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
     }
     return MRF_OK;

@@ -8,6 +8,11 @@
 // index scatter s(mu) = sum_{lambda : p(lambda) = mu} g(lambda) through a wavefront-private
 // LDS vector.  What the same direction passes on to node i-r stays in registers.
 //
+// Precision: tensors in memory are float; the chain a scanline carries from node to node
+// (message gradient, its label sum, the scatter sums) and the V-gradient accumulators are
+// kept in double, so that rounding does not build up along a scanline.  On this chip
+// double adds issue at the same rate as unpacked float adds.
+//
 // ISGMR sweeps all directions in one launch, so cross-direction sums are not formed here:
 // the sweep writes s per (direction, node) and mrf_isgmr_bwd_combine adds them up in a
 // fixed order.  TRWP sweeps one direction per launch; every (node, label) is touched by
@@ -31,7 +36,7 @@ struct MrfBwdParams {
     float *G;                              // TRWP : [R][N][L] grad m, updated in place
     float *gunary;                         // TRWP : [N][L] grad theta_i, updated in place
     float *gw;                             // [R][N] or NULL, accumulated over iterations
-    float *gV;                             // [slots][L][L] or NULL, one slot per wavefront
+    double *gV;                            // [slots][L][L] or NULL, one slot per wavefront
     float rho[MRF_MAXR];
 };
 
@@ -40,15 +45,15 @@ struct MrfBwdParams {
 template <int LP>
 __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
-    __shared__ float sbuf_all[MRF_BWD_WAVES][64 * LP];
+    __shared__ double sbuf_all[MRF_BWD_WAVES][64 * LP];
     const int L = P.g.L, R = P.g.R;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    float *sbuf = sbuf_all[wv];
+    double *sbuf = sbuf_all[wv];
     const long long slot = (long long)blockIdx.x * MRF_BWD_WAVES + wv;
     const long long nslots = (long long)gridDim.x * MRF_BWD_WAVES;
     const long long N = P.g.N;
     const bool trwp = P.algo != 0;
-    float *gVs = P.gV ? P.gV + (size_t)slot * L * L : nullptr;
+    double *gVs = P.gV ? P.gV + (size_t)slot * L * L : nullptr;
 
     for (long long sl = slot; sl < P.total_scanlines; sl += nslots) {
         int ri = 0;
@@ -63,7 +68,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
         mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
         const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
         const long long nstep = (long long)dh * P.g.W + dw;
-        const float rho = P.rho[r];
+        const double rho = (double)P.rho[r];
         const float *gin = trwp ? P.G + (size_t)r * N * L : P.gin + (size_t)r * P.gin_stride;
 
         // the last node of the scanline has no successor in direction r
@@ -76,23 +81,23 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             }
         }
 
-        float carry[LP];   // what node i+r of this direction passed back to node i
+        double carry[LP];   // what node i+r of this direction passed back to node i
 #pragma unroll
-        for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
+        for (int s = 0; s < LP; ++s) carry[s] = 0.0;
 
         for (int n = len - 1; n >= 1; --n) {
             const long long i = head + (long long)n * nstep;
             const long long j = i - nstep;
-            float g[LP];
+            double g[LP];
             int pv[LP];
-            float part = 0.0f;
+            double part = 0.0;
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 const int lam = lane + 64 * s;
-                g[s] = 0.0f;
+                g[s] = 0.0;
                 pv[s] = 0;
                 if (lam < L) {
-                    g[s] = gin[(size_t)i * L + lam] + carry[s];
+                    g[s] = (double)gin[(size_t)i * L + lam] + carry[s];
                     int pp = P.p[((size_t)r * N + i) * L + lam];
                     pv[s] = pp < L ? pp : L - 1;
                     if (trwp) P.G[((size_t)r * N + i) * L + lam] = 0.0f;   // zero-out (Alg. 4)
@@ -100,23 +105,23 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 part += g[s];
             }
             // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
-            const float tot = mrf_wave_sum(part);
+            const double tot = mrf_wave_sum_f64(part);
             int qv = P.q[(size_t)r * N + i];
             qv = qv < L ? qv : L - 1;
 #pragma unroll
             for (int s = 0; s < LP; ++s)
                 if (lane + 64 * s == qv) g[s] = g[s] - tot;
 
-            const float wgt = P.w ? P.w[(size_t)r * N + i] : P.w_scalar;
+            const double wgt = (double)(P.w ? P.w[(size_t)r * N + i] : P.w_scalar);
             if (P.gw) {
-                float acc = 0.0f;
+                double acc = 0.0;
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    if (lam < L) acc += g[s] * P.V[(size_t)pv[s] * L + lam];
+                    if (lam < L) acc += g[s] * (double)P.V[(size_t)pv[s] * L + lam];
                 }
-                acc = mrf_wave_sum(acc);
-                if (lane == 0) P.gw[(size_t)r * N + i] += acc;
+                acc = mrf_wave_sum_f64(acc);
+                if (lane == 0) P.gw[(size_t)r * N + i] = (float)((double)P.gw[(size_t)r * N + i] + acc);
             }
             if (gVs) {
 #pragma unroll
@@ -128,14 +133,14 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 
             // index scatter through LDS: s(mu) = sum over lambda with p(lambda) = mu
 #pragma unroll
-            for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0f;
+            for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0;
             mrf_wave_lds_fence();
 #pragma unroll
             for (int s = 0; s < LP; ++s)
                 if (lane + 64 * s < L)
-                    __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             mrf_wave_lds_fence();
-            float sv[LP];
+            double sv[LP];
 #pragma unroll
             for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
             mrf_wave_lds_fence();
@@ -144,23 +149,23 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    if (lam < L) P.S[((size_t)r * N + j) * L + lam] = sv[s];
+                    if (lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)sv[s];
                     carry[s] = sv[s];
                 }
             } else {
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    const float rs = rho * sv[s];
+                    const double rs = rho * sv[s];
                     if (lam < L) {
                         const size_t e = (size_t)j * L + lam;
-                        P.gunary[e] = P.gunary[e] + rs;
+                        P.gunary[e] = (float)((double)P.gunary[e] + rs);
                         for (int d = 0; d < R; ++d) {
                             if (d == r) continue;
                             float *gd = P.G + (size_t)d * N * L;
-                            float v = gd[e] + rs;
+                            double v = (double)gd[e] + rs;
                             if (d == rm) v = v - sv[s];
-                            gd[e] = v;
+                            gd[e] = (float)v;
                         }
                     }
                     carry[s] = rs;
@@ -195,28 +200,34 @@ __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombinePar
 {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < P.NL; e += stride) {
-        float tot = P.first ? P.gc[e] : P.gunary[e];
-        for (int r = 0; r < P.R; ++r) tot = tot + P.S[(size_t)r * P.NL + e];
-        P.gunary[e] = tot;
+        double tot = (double)(P.first ? P.gc[e] : P.gunary[e]);
+        for (int r = 0; r < P.R; ++r) tot = tot + (double)P.S[(size_t)r * P.NL + e];
+        P.gunary[e] = (float)tot;
         if (P.ghat) {
             for (int d = 0; d < P.R; ++d) {
-                float v = 0.0f;
+                double v = 0.0;
                 for (int r = 0; r < P.R; ++r)
-                    if (r != d && r != P.opp[d]) v = v + P.S[(size_t)r * P.NL + e];
-                P.ghat[(size_t)d * P.NL + e] = v;
+                    if (r != d && r != P.opp[d]) v = v + (double)P.S[(size_t)r * P.NL + e];
+                P.ghat[(size_t)d * P.NL + e] = (float)v;
             }
         }
     }
 }
 
 // dst[e] = sum over slots of src[slot][e], slots in ascending order
-__global__ void __launch_bounds__(256) mrf_reduce_slots(const float *src, float *dst, long long n, long long slots)
+__global__ void __launch_bounds__(256) mrf_reduce_slots(const double *src, float *dst, long long n, long long slots)
 {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n) return;
-    float v = 0.0f;
+    double v = 0.0;
     for (long long s = 0; s < slots; ++s) v = v + src[(size_t)s * n + e];
-    dst[e] = v;
+    dst[e] = (float)v;
+}
+
+__global__ void __launch_bounds__(256) mrf_fill_f64(double *dst, long long n, double val)
+{
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) dst[e] = val;
 }
 
 __global__ void __launch_bounds__(256) mrf_fill_f32(float *dst, long long n, float val)

@@ -69,6 +69,13 @@ __device__ inline float mrf_wave_sum(float v)
     return v;
 }
 
+__device__ inline double mrf_wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MRF_WAVE);
+    return v;
+}
+
 // Orders this wavefront's LDS writes before its later LDS reads by other lanes (lanes of
 // one wavefront run in lock step; only the compiler and the LDS queue need telling).
 __device__ inline void mrf_wave_lds_fence()
