@@ -140,6 +140,13 @@ int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
 /* Static text for a status code. */
 const char *mrf_strerror(int status);
 
+/* Profiling hook: while set (both non-NULL hipEvent_t handles), every forward or backward
+ * call records `start_event` on its stream just before its first scanline-sweep launch and
+ * `stop_event` just after its last one, so a caller can time the sweeps apart from the
+ * surrounding element-wise kernels.  Pass NULL, NULL to clear.  Process-global, not
+ * thread-safe; the caller owns the events. */
+int mrf_set_sweep_events(void *start_event, void *stop_event);
+
 /* Process-global tuning knobs for experiments; results never depend on them.
  *   knob 0: source labels per wavefront in the dense forward sweep (8, 16 or 32; 0 = heuristic)
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */

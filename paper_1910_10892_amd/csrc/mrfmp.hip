@@ -71,6 +71,12 @@ size_t gradv_bytes(const mrf_problem *pr)
 // ---- forward sweep dispatch -------------------------------------------------------------
 // tuning knobs (0 = heuristic)
 int g_tune_mch = 0;
+hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+
+inline void mark(hipEvent_t ev, hipStream_t st)
+{
+    if (g_ev_start && g_ev_stop) (void)hipEventRecord(ev, st);
+}
 
 template <int LP, int MCH>
 hipError_t launch_fwd(const MrfFwdParams &P, long long blocks, hipStream_t st)
@@ -130,6 +136,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
     float *final_m = nullptr;
 
+    mark(g_ev_start, st);
     if (algo == MRF_ISGMR) {
         // all directions of one iteration in one launch; messages ping-pong between two buffers
         P.r_first = 0; P.r_count = R;
@@ -163,6 +170,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
         }
         final_m = bufA;
     }
+    mark(g_ev_stop, st);
 
     MrfAggParams A;
     A.N = N; A.L = L; A.R = R;
@@ -258,6 +266,11 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         if (fill64(gvslots, kGradVSlots * L * L, st) != hipSuccess) return MRF_ERR_HIP;
     }
 
+    if (algo == MRF_TRWP) {
+        if (broadcast(grad_cost, buf0, NL, R, st) != hipSuccess) return MRF_ERR_HIP;
+        if (broadcast(grad_cost, grad_unary, NL, 1, st) != hipSuccess) return MRF_ERR_HIP;
+    }
+    mark(g_ev_start, st);
     if (algo == MRF_ISGMR) {
         P.r_first = 0; P.r_count = R;
         long long tot = 0;
@@ -286,8 +299,6 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     } else {
         P.G = buf0;
         P.gunary = grad_unary;
-        if (broadcast(grad_cost, buf0, NL, R, st) != hipSuccess) return MRF_ERR_HIP;
-        if (broadcast(grad_cost, grad_unary, NL, 1, st) != hipSuccess) return MRF_ERR_HIP;
         for (int k = K - 1; k >= 0; --k) {
             for (int r = R - 1; r >= 0; --r) {      // reverse of the forward direction order
                 P.r_first = r; P.r_count = 1;
@@ -300,6 +311,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
             }
         }
     }
+    mark(g_ev_stop, st);
     if (grad_V) {
         const long long n = (long long)L * L;
         hipLaunchKernelGGL(mrf_reduce_slots, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
@@ -388,6 +400,13 @@ const char *mrf_strerror(int status)
 }
 
 const char *mrf_version(void) { return "0.1.0"; }
+
+int mrf_set_sweep_events(void *start_event, void *stop_event)
+{
+    g_ev_start = (hipEvent_t)start_event;
+    g_ev_stop = (hipEvent_t)stop_event;
+    return MRF_OK;
+}
 
 int mrf_tune(int knob, int value)
 {

@@ -75,6 +75,8 @@ def load_library():
     lib.mrf_strerror.restype = ctypes.c_char_p
     lib.mrf_strerror.argtypes = [ci]
     lib.mrf_version.restype = ctypes.c_char_p
+    lib.mrf_set_sweep_events.restype = ci
+    lib.mrf_set_sweep_events.argtypes = [vp, vp]
     lib.mrf_tune.restype = ci
     lib.mrf_tune.argtypes = [ci, ci]
     _lib = lib
@@ -150,6 +152,13 @@ def mrf_version() -> str:
 
 def mrf_tune(knob: int, value: int) -> int:
     return int(load_library().mrf_tune(int(knob), int(value)))
+
+
+def mrf_set_sweep_events(start_event, stop_event) -> int:
+    """start_event / stop_event: torch.cuda.Event(enable_timing=True) that have been recorded
+    once (so that their HIP handles exist), or None, None to clear."""
+    h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
+    return int(load_library().mrf_set_sweep_events(h(start_event), h(stop_event)))
 
 
 def mrf_validate(prob: MrfProblem, algo: int) -> int:
