@@ -78,39 +78,84 @@ inline void mark(hipEvent_t ev, hipStream_t st)
     if (g_ev_start && g_ev_stop) (void)hipEventRecord(ev, st);
 }
 
-template <int LP, int MCH>
-hipError_t launch_fwd(const MrfFwdParams &P, long long blocks, hipStream_t st)
+template <int LP, int MCH, int RMAX, int D>
+hipError_t launch_fwd(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
-    const int NW = P.NW;
-    const size_t lds = (size_t)NW * NW * MCH * sizeof(float) + (size_t)2 * NW * 64 * LP * (sizeof(float) + 1);
-    hipLaunchKernelGGL((mrf_fwd_sweep<LP, MCH>), dim3((unsigned)blocks), dim3(64 * NW), lds, st, P);
+    constexpr int NWMAX = (64 * LP + MCH - 1) / MCH;
+    const size_t lds = (size_t)NWMAX * NWMAX * MCH * sizeof(float) +
+                       (NWMAX > 1 ? (size_t)2 * NWMAX * 64 * LP * sizeof(float2) : 0);
+    if (algo == MRF_TRWP)
+        hipLaunchKernelGGL((mrf_fwd_sweep<LP, MCH, RMAX, D, true>), dim3((unsigned)blocks), dim3(64 * P.NW), lds, st, P);
+    else
+        hipLaunchKernelGGL((mrf_fwd_sweep<LP, MCH, RMAX, D, false>), dim3((unsigned)blocks), dim3(64 * P.NW), lds, st, P);
     return hipGetLastError();
 }
 
-int pick_mch(int L, int LP)
+// source labels per wavefront: small enough that the slice of V fits in registers, large
+// enough that at most 16 wavefronts share a node
+int pick_mch(int L, int LP, bool many_sources)
 {
-    int mch = g_tune_mch;
-    if (mch != 8 && mch != 16 && mch != 32) mch = (L <= 32) ? 32 : (L <= 64 ? 16 : 32);
-    while (mch < 32 && (L + mch - 1) / mch > 16) mch *= 2;       // at most 16 wavefronts
-    while (mch < 4 * LP) mch *= 2;                                // launch bound 64*(64*LP/MCH) <= 1024
-    if (LP == 3 && mch == 8) mch = 16;
-    return mch;
+    static const int allowed[4][5] = { {8, 16, 32, 0, 0}, {8, 12, 16, 24, 32}, {16, 24, 32, 48, 0}, {32, 0, 0, 0, 0} };
+    int want = g_tune_mch;
+    if (want <= 0) want = LP == 1 ? (L <= 32 ? 32 : 16) : (LP == 2 ? 24 : 32);
+    if (many_sources) want = (LP <= 2) ? (want < 16 ? 16 : (want == 24 || want == 12 ? 16 : want)) : 32;
+    int best = 0;
+    for (int i = 0; i < 5; ++i) {
+        const int m = allowed[LP - 1][i];
+        if (m == 0) continue;
+        if (many_sources && m != 16 && m != 32) continue;
+        if (best == 0 || mrf_iabs(m - want) < mrf_iabs(best - want)) best = m;
+    }
+    return best;
 }
 
-hipError_t dispatch_fwd(MrfFwdParams &P, long long blocks, hipStream_t st)
+hipError_t dispatch_fwd(MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
     const int L = P.g.L;
     const int LP = (L + 63) / 64;
-    const int mch = pick_mch(L, LP);
+    int max_src = 0;
+    for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
+        if (P.n_src[r] > max_src) max_src = P.n_src[r];
+    const int rmax = (max_src + 1 <= 4) ? 4 : ((max_src + 1 <= 8) ? 8 : 16);
+    const int mch = pick_mch(L, LP, rmax > 4);
     P.NW = (L + mch - 1) / mch;
-#define MRF_CASE(lp, m) if (LP == lp && mch == m) return launch_fwd<lp, m>(P, blocks, st);
+    // prefetch depth: as deep as the register file allows next to the slice of V
+#define MRF_CASE(lp, m) \
+    if (LP == lp && mch == m && rmax == 4) return launch_fwd<lp, m, 4, (lp <= 2 ? 4 : 2)>(P, algo, blocks, st);
+#define MRF_CASE_MANY(lp, m) \
+    if (LP == lp && mch == m && rmax == 8) return launch_fwd<lp, m, 8, (lp <= 2 ? 2 : 1)>(P, algo, blocks, st); \
+    if (LP == lp && mch == m && rmax == 16) return launch_fwd<lp, m, 16, 1>(P, algo, blocks, st);
     MRF_CASE(1, 8) MRF_CASE(1, 16) MRF_CASE(1, 32)
-    MRF_CASE(2, 8) MRF_CASE(2, 16) MRF_CASE(2, 32)
-    MRF_CASE(3, 16) MRF_CASE(3, 32)
-    MRF_CASE(4, 16) MRF_CASE(4, 32)
+    MRF_CASE(2, 8) MRF_CASE(2, 12) MRF_CASE(2, 16) MRF_CASE(2, 24) MRF_CASE(2, 32)
+    MRF_CASE(3, 16) MRF_CASE(3, 24) MRF_CASE(3, 32) MRF_CASE(3, 48)
+    MRF_CASE(4, 32)
+    MRF_CASE_MANY(1, 16) MRF_CASE_MANY(1, 32) MRF_CASE_MANY(2, 16) MRF_CASE_MANY(2, 32)
+    MRF_CASE_MANY(3, 32) MRF_CASE_MANY(4, 32)
 #undef MRF_CASE
+#undef MRF_CASE_MANY
     return hipErrorInvalidValue;
 }
+
+// Which message arrays enter h at the previous node, in the order they are summed, for the
+// sweep of direction r.  live: bit d set if array d holds data (else it is all zero and is
+// skipped: adding 0 changes nothing).
+void fill_sources(MrfFwdParams &P, int algo, int r, unsigned live)
+{
+    const int R = P.g.R, rm = P.g.opp[r];
+    int n = 0, npre = 0, rmslot = -1;
+    for (int d = 0; d < R; ++d) {
+        if (d == r || !((live >> d) & 1u)) continue;
+        if (algo == MRF_ISGMR && d == rm) continue;       // Eq. isgmr excludes r and r-
+        if (algo == MRF_TRWP && d < r) ++npre;            // Eq. trwp sums all d in index order
+        if (d == rm) rmslot = n;
+        P.src_dir[r][n++] = (signed char)d;
+    }
+    P.n_pre[r] = (signed char)npre;
+    P.n_src[r] = (signed char)n;
+    P.rm_slot[r] = (signed char)rmslot;
+}
+
+hipError_t fill(float *dst, long long n, float v, hipStream_t st);
 
 int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
                 float *messages, void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -127,12 +172,19 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     fill_geom(pr, P.g);
     const long long N = P.g.N;
     const int R = pr->R, L = pr->L, K = pr->K;
-    P.algo = algo;
-    P.unary = pr->unary; P.V = pr->pairwise; P.w = pr->edge_weight; P.w_scalar = pr->edge_weight_scalar;
+    P.unary = pr->unary; P.V = pr->pairwise;
     for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP) ? pr->rho[r] : 1.0f;
 
-    float *bufA = (float *)workspace;
-    float *bufB = (float *)((char *)workspace + msg_bytes(pr));
+    // workspace: [scalars 256 B][messages A][messages B (ISGMR only)]
+    float *scal = (float *)workspace;
+    float *bufA = (float *)((char *)workspace + kAlign);
+    float *bufB = (float *)((char *)workspace + kAlign + msg_bytes(pr));
+    if (pr->edge_weight) { P.w = pr->edge_weight; P.w_mul = 1; }
+    else {
+        // a scalar weight is read through the same vector loads as per-edge weights
+        if (fill(scal, 1, pr->edge_weight_scalar, st) != hipSuccess) return MRF_ERR_HIP;
+        P.w = scal; P.w_mul = 0;
+    }
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
     float *final_m = nullptr;
 
@@ -146,10 +198,10 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
         for (int k = 0; k < K; ++k) {
             P.m_in = (k & 1) ? bufB : bufA;      // written by iteration k-1 (unused when k = 0)
             P.m_out = (k & 1) ? bufA : bufB;
-            P.live_mask = k == 0 ? 0u : 0xffffffffu;
+            for (int r = 0; r < R; ++r) fill_sources(P, algo, r, k == 0 ? 0u : 0xffffffffu);
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
-            if (dispatch_fwd(P, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+            if (dispatch_fwd(P, algo, blocks, st) != hipSuccess) return MRF_ERR_HIP;
             final_m = P.m_out;
         }
     } else {
@@ -162,10 +214,10 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
                 const long long blocks = (long long)pr->B * P.g.nscan[r];
                 P.blk_begin[1] = blocks;
                 // in the first iteration the directions after r have not been written yet: they read as 0
-                P.live_mask = k == 0 ? ((1u << r) - 1u) : 0xffffffffu;
+                fill_sources(P, algo, r, k == 0 ? ((1u << r) - 1u) : 0xffffffffu);
                 P.p = p + (size_t)k * pk;
                 P.q = q + (size_t)k * qk;
-                if (dispatch_fwd(P, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+                if (dispatch_fwd(P, algo, blocks, st) != hipSuccess) return MRF_ERR_HIP;
             }
         }
         final_m = bufA;
@@ -328,7 +380,7 @@ extern "C" {
 size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward)
 {
     if (check_problem(prob, algo, false) != MRF_OK) return 0;
-    if (!backward) return (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob);
+    if (!backward) return kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob);
     return (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob) + gradv_bytes(prob);
 }
 

@@ -54,26 +54,59 @@ __host__ __device__ inline void mrf_geom_head(int H, int W, int dh, int dw, long
 }
 
 #ifdef __HIPCC__
-// ---- wavefront helpers ---------------------------------------------------------------
+// ---- wavefront helpers (gfx950: 64 lanes, DPP row = 16 lanes) -------------------------
+// DPP controls: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141,
+// row_mirror = 0x140.  After the four steps every lane holds the reduction of its row.
+template <int CTRL>
+__device__ inline float mrf_dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+
+template <int CTRL>
+__device__ inline double mrf_dpp_f64(double v)
+{
+    const long long b = __builtin_bit_cast(long long, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffLL), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+    return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+}
+
+__device__ inline float mrf_readlane_f32(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+__device__ inline double mrf_readlane_f64(double v, int lane)
+{
+    const long long b = __builtin_bit_cast(long long, v);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffLL), lane);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+    return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+}
+
+// minimum over the 64 lanes, returned to every lane (wave-uniform)
 __device__ inline float mrf_wave_min(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, MRF_WAVE));
-    return v;
+    v = fminf(v, mrf_dpp_f32<0xB1>(v));
+    v = fminf(v, mrf_dpp_f32<0x4E>(v));
+    v = fminf(v, mrf_dpp_f32<0x141>(v));
+    v = fminf(v, mrf_dpp_f32<0x140>(v));
+    const float r0 = mrf_readlane_f32(v, 0), r1 = mrf_readlane_f32(v, 16);
+    const float r2 = mrf_readlane_f32(v, 32), r3 = mrf_readlane_f32(v, 48);
+    return fminf(fminf(r0, r1), fminf(r2, r3));
 }
 
-__device__ inline float mrf_wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MRF_WAVE);
-    return v;
-}
-
+// sum over the 64 lanes in a fixed tree order, returned to every lane
 __device__ inline double mrf_wave_sum_f64(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MRF_WAVE);
-    return v;
+    v += mrf_dpp_f64<0xB1>(v);
+    v += mrf_dpp_f64<0x4E>(v);
+    v += mrf_dpp_f64<0x141>(v);
+    v += mrf_dpp_f64<0x140>(v);
+    const double r0 = mrf_readlane_f64(v, 0), r1 = mrf_readlane_f64(v, 16);
+    const double r2 = mrf_readlane_f64(v, 32), r3 = mrf_readlane_f64(v, 48);
+    return (r0 + r1) + (r2 + r3);
 }
 
 // Orders this wavefront's LDS writes before its later LDS reads by other lanes (lanes of
@@ -83,5 +116,14 @@ __device__ inline void mrf_wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads issued as prefetch stay in
+// flight across it (a full __syncthreads would wait for them).
+__device__ inline void mrf_block_sync_lds()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 #endif

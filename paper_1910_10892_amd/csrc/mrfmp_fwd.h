@@ -9,37 +9,57 @@
 // Partial minima meet in LDS once per node (one workgroup barrier per node); every
 // wavefront then finishes the node redundantly (merge in ascending mu, argmin over
 // lambda, reparametrisation), so no second barrier is needed.
+//
+// The node-to-node dependence makes a sweep latency bound, so everything that does not
+// depend on the previous node (unary, other directions' messages, edge weight) is loaded
+// a group of D nodes ahead into a second register set, unconditionally (clamped
+// addresses), so that a load is first waited for at least D node steps after its issue.
 #pragma once
 
 #include "mrfmp_device.h"
 
 struct MrfFwdParams {
     MrfGeom g;
-    int algo;                              // 0 = ISGMR, 1 = TRWP
     int r_first, r_count;                  // directions swept by this launch
     long long blk_begin[MRF_MAXR + 1];     // prefix sums of B*nscan over those directions
-    unsigned live_mask;                    // bit d: message array d holds data (else reads as 0)
-    const float *unary, *V, *w;
-    float w_scalar;
+    const float *unary, *V;
+    const float *w;                        // [R][N] edge weights, or one float when w_mul == 0
+    int w_mul;                             // 1: per-edge weights, 0: the scalar at w[0]
     const float *m_in;                     // [R][N][L] messages read
     float *m_out;                          // [R][N][L] messages written (TRWP: same array)
     uint8_t *p, *q;                        // [R][N][L], [R][N] of this iteration
     float rho[MRF_MAXR];
+    // per swept direction r: the message arrays that enter h, in summation order.  The first
+    // n_pre[r] are added before this direction's own running message, the rest after it.
+    signed char src_dir[MRF_MAXR][MRF_MAXR];
+    signed char n_pre[MRF_MAXR], n_src[MRF_MAXR];
+    signed char rm_slot[MRF_MAXR];         // position of r^- in src_dir[r], or -1 (term absent / still 0)
     int NW;                                // wavefronts per workgroup = ceil(L / MCH)
 };
 
-template <int LP, int MCH>
-__global__ void __launch_bounds__(64 * (64 * LP / MCH))
+// A zero the compiler cannot see through: keeps wave-uniform addresses in vector loads, so
+// that they queue behind the other prefetches instead of going through the scalar cache.
+__device__ inline int mrf_opaque_zero()
+{
+    int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// LP: labels per lane; MCH: source labels per wavefront; RMAX: bound on 1 + n_src;
+// D: prefetch distance in nodes; TRWP: Eq. trwp (else Eq. isgmr)
+template <int LP, int MCH, int RMAX, int D, bool TRWP>
+__global__ void __launch_bounds__(64 * ((64 * LP + MCH - 1) / MCH))
 mrf_fwd_sweep(const MrfFwdParams P)
 {
     extern __shared__ __align__(16) unsigned char mrf_smem[];
-    const int L = P.g.L, NW = P.NW, R = P.g.R;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int LPAD = NW * MCH;
+    constexpr int NWMAX = (64 * LP + MCH - 1) / MCH;
+    constexpr int LPAD = NWMAX * MCH;
     constexpr int SLOTS = 64 * LP;
-    float *hbuf = reinterpret_cast<float *>(mrf_smem) + wv * LPAD;      // private to this wavefront
-    float *pval = reinterpret_cast<float *>(mrf_smem) + NW * LPAD;      // [2][NW][SLOTS]
-    uint8_t *pidx = reinterpret_cast<uint8_t *>(pval + 2 * NW * SLOTS); // [2][NW][SLOTS]
+    const int L = P.g.L, NW = P.NW;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    float *hbuf = reinterpret_cast<float *>(mrf_smem) + wv * LPAD;          // private to this wavefront
+    float2 *part = reinterpret_cast<float2 *>(reinterpret_cast<float *>(mrf_smem) + NWMAX * LPAD);  // [2][NWMAX][SLOTS]
 
     // workgroup -> (direction r, image b, scanline t)
     const long long blk = blockIdx.x;
@@ -50,14 +70,32 @@ mrf_fwd_sweep(const MrfFwdParams P)
     const int nsc = P.g.nscan[r];
     const int b = (int)(local / nsc);
     const long long t = local - (long long)b * nsc;
-    const int dh = P.g.dh[r], dw = P.g.dw[r], rm = P.g.opp[r];
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
     int y0, x0, len;
     mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
     const long long N = P.g.N;
     const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
     const long long nstep = (long long)dh * P.g.W + dw;
-    const bool trwp = P.algo != 0;
     const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+
+    // Sources of h: slot 0 = unary, slot c >= 1 = message array src_dir[r][c-1].  Unused
+    // slots read the unary again and enter with factor 0: fma(0, x, v) = v exactly, and
+    // fma(1, x, v) = v + x exactly, so the sum below is the plain left-to-right sum of the
+    // live terms with this direction's running message inserted after the first n_pre.
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = (c <= n_src) ? 1.0f : 0.0f;
+        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
 
     // this wavefront's slice of V: rows mu0 .. mu0+MCH-1, columns = the lane's lambdas
     const int mu0 = wv * MCH;
@@ -69,8 +107,12 @@ mrf_fwd_sweep(const MrfFwdParams P)
             const int mu = mu0 + i, lam = lane + 64 * s;
             Vr[i][s] = (mu < L && lam < L) ? P.V[(size_t)mu * L + lam] : 0.0f;
         }
-    // padding of h beyond L can never win a strict '<'
+    // padding of h beyond L, and partial minima of absent wavefronts, can never win a strict '<'
     for (int i = L + lane; i < LPAD; i += 64) hbuf[i] = INFINITY;
+    if (NWMAX > 1) {
+        for (int i = threadIdx.x; i < 2 * NWMAX * SLOTS; i += blockDim.x) part[i] = make_float2(INFINITY, 0.0f);
+        __syncthreads();
+    }
 
     // first node of the scanline: message 0, p = q = 0
     if (wv == 0) {
@@ -85,133 +127,166 @@ mrf_fwd_sweep(const MrfFwdParams P)
         if (lane == 0) P.q[(size_t)r * N + head] = 0;
     }
 
-    float carry[LP];   // normalised message of this direction at the previous node
+    // Prefetch in groups of D nodes: while the D nodes of one group are processed from the
+    // registers `cur`, the inputs of the next group are in flight into `nxt`.
+    const int vzero = mrf_opaque_zero();
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len - 2;           // last node that is a predecessor
+    float cur[D][RMAX][LP], nxt[D][RMAX][LP];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, int nj) {   // inputs of the update nj -> nj+1
+        nj = nj < lastsrc ? nj : lastsrc;  // past the end: reload the last one, never used
+        const long long j = head + (long long)nj * nstep;
 #pragma unroll
-    for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
-    int buf = 0;
-
-    for (int n = 1; n < len; ++n) {
-        const long long j = head + (long long)(n - 1) * nstep;   // i - r
-        const long long i = j + nstep;
-
-        // ---- lambda-independent part h[mu] at node i-r (lane's labels act as mu here) ----
-        float a[LP];
-#pragma unroll
-        for (int s = 0; s < LP; ++s) {
-            const int lam = lane + 64 * s;
-            float v = 0.0f;
-            if (lam < L) {
-                v = P.unary[(size_t)j * L + lam];
-                if (!trwp) {
-                    // Eq. isgmr: theta_{i-r} + m-hat^r_{i-r} + sum_{d not in {r, r-}} m^d_{i-r}
-                    v = v + carry[s];
-                    for (int d = 0; d < R; ++d)
-                        if (d != r && d != rm && ((P.live_mask >> d) & 1u))
-                            v = v + P.m_in[((size_t)d * N + j) * L + lam];
-                } else {
-                    // Eq. trwp: rho (theta_{i-r} + sum_d m^d_{i-r}) - m^{r-}_{i-r}
-                    float mrm = 0.0f;
-                    for (int d = 0; d < R; ++d) {
-                        float md;
-                        if (d == r) md = carry[s];
-                        else if ((P.live_mask >> d) & 1u) md = P.m_in[((size_t)d * N + j) * L + lam];
-                        else md = 0.0f;
-                        v = v + md;
-                        if (d == rm) mrm = md;
-                    }
-                    v = rho * v;
-                    if (rm >= 0) v = v - mrm;
-                }
-            }
-            a[s] = v;
-        }
-#pragma unroll
-        for (int s = 0; s < LP; ++s) {
-            const int lam = lane + 64 * s;
-            if (lam < L) hbuf[lam] = a[s];
-        }
-        mrf_wave_lds_fence();
-
-        const float wgt = P.w ? P.w[(size_t)r * N + i] : P.w_scalar;
-
-        // ---- min-plus over this wavefront's mu slice, lowest mu on ties ----
-        float best[LP];
-        int bidx[LP];
-#pragma unroll
-        for (int s = 0; s < LP; ++s) { best[s] = INFINITY; bidx[s] = 0; }
-#pragma unroll
-        for (int i4 = 0; i4 < MCH; i4 += 4) {
-            const float4 hv = *reinterpret_cast<const float4 *>(&hbuf[mu0 + i4]);
-            const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int s = 0; s < LP; ++s) {
-                    const float dlt = __builtin_fmaf(wgt, Vr[i4 + c][s], hq[c]);
-                    if (dlt < best[s]) { best[s] = dlt; bidx[s] = i4 + c; }
-                }
-        }
-
-        float tv[LP];
-        int tp[LP];
-        if (NW > 1) {
-            float *pv = pval + (size_t)buf * NW * SLOTS;
-            uint8_t *pi = pidx + (size_t)buf * NW * SLOTS;
-#pragma unroll
-            for (int s = 0; s < LP; ++s) {
-                pv[wv * SLOTS + lane + 64 * s] = best[s];
-                pi[wv * SLOTS + lane + 64 * s] = (uint8_t)(mu0 + bidx[s]);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int s = 0; s < LP; ++s) { tv[s] = INFINITY; tp[s] = 0; }
-            for (int w2 = 0; w2 < NW; ++w2) {
-#pragma unroll
-                for (int s = 0; s < LP; ++s) {
-                    const float v = pv[w2 * SLOTS + lane + 64 * s];
-                    const int ix = pi[w2 * SLOTS + lane + 64 * s];
-                    if (v < tv[s]) { tv[s] = v; tp[s] = ix; }
-                }
-            }
-            buf ^= 1;
-        } else {
-#pragma unroll
-            for (int s = 0; s < LP; ++s) { tv[s] = best[s]; tp[s] = bidx[s]; }
-        }
-
-        // ---- q = lowest argmin over lambda, reparametrisation (Eq. isgmr-norm) ----
-        float mn = INFINITY;
-#pragma unroll
-        for (int s = 0; s < LP; ++s) {
-            if (lane + 64 * s >= L) tv[s] = INFINITY;
-            mn = fminf(mn, tv[s]);
-        }
-        mn = mrf_wave_min(mn);
-        int qidx = -1;
-        float tq = mn;
-#pragma unroll
-        for (int s = 0; s < LP; ++s) {
-            const unsigned long long bal = __ballot(tv[s] == mn);
-            if (qidx < 0 && bal != 0ull) {
-                const int ql = __ffsll((long long)bal) - 1;
-                qidx = 64 * s + ql;
-                tq = __shfl(tv[s], ql, MRF_WAVE);
-            }
-        }
-#pragma unroll
-        for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
-
-        // ---- outputs of node i (the wavefronts take turns) ----
-        if (wv == n % NW) {
+        for (int c = 0; c < RMAX; ++c)
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 const int lam = lane + 64 * s;
-                if (lam < L) {
-                    P.m_out[((size_t)r * N + i) * L + lam] = carry[s];
-                    P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
+                dst[c][s] = src[c][(size_t)j * L + (lam < L ? lam : 0)];
+            }
+        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+    };
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
+
+    float carry[LP];   // normalised message of this direction at the previous node
+#pragma unroll
+    for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
+    int buf = 0, turn = 0;
+
+    for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            // node index of i on the scanline; i-r is node n-1.  The last group may run past
+            // the end of the scanline: those steps recompute the last node and store nothing.
+            const int nn = n0 + u;
+            const bool past = nn >= len;
+            const int n = past ? len - 1 : nn;
+            const long long i = head + (long long)n * nstep;
+
+            // ---- lambda-independent part h[mu] at node i-r (lane's labels act as mu here) ----
+            float a[LP];
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                float v = cur[u][0][s];
+                float mrm = 0.0f;
+                if (TRWP) {
+                    // Eq. trwp: rho (theta_{i-r} + sum_d m^d_{i-r}) - m^{r-}_{i-r}
+#pragma unroll
+                    for (int c = 1; c < RMAX; ++c) {
+                        v = __builtin_fmaf(carry_at[c], carry[s], v);
+                        v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                        mrm = __builtin_fmaf(is_rm[c], cur[u][c][s], mrm);
+                    }
+                    v = __builtin_fmaf(carry_at[RMAX], carry[s], v);
+                    v = rho * v;
+                    v = v - mrm;
+                } else {
+                    // Eq. isgmr: theta_{i-r} + m-hat^r_{i-r} + sum_{d not in {r, r-}} m^d_{i-r}
+                    v = v + carry[s];
+#pragma unroll
+                    for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                }
+                a[s] = v;
+            }
+            const float wgt = wcur[u];
+
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const int lam = lane + 64 * s;
+                if (lam < L) hbuf[lam] = a[s];
+            }
+            mrf_wave_lds_fence();
+
+            // ---- min-plus over this wavefront's mu slice, lowest mu on ties ----
+            float best[LP];
+            int bidx[LP];
+#pragma unroll
+            for (int s = 0; s < LP; ++s) { best[s] = INFINITY; bidx[s] = 0; }
+#pragma unroll
+            for (int i4 = 0; i4 < MCH; i4 += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(&hbuf[mu0 + i4]);
+                const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const float dlt = __builtin_fmaf(wgt, Vr[i4 + c][s], hq[c]);
+                        if (dlt < best[s]) { best[s] = dlt; bidx[s] = i4 + c; }
+                    }
+            }
+
+            float tv[LP];
+            int tp[LP];
+            if (NWMAX > 1) {
+                float2 *pb = part + (size_t)buf * NWMAX * SLOTS;
+#pragma unroll
+                for (int s = 0; s < LP; ++s)
+                    pb[wv * SLOTS + lane + 64 * s] = make_float2(best[s], __int_as_float(mu0 + bidx[s]));
+                mrf_block_sync_lds();
+#pragma unroll
+                for (int s = 0; s < LP; ++s) { tv[s] = INFINITY; tp[s] = 0; }
+#pragma unroll
+                for (int w2 = 0; w2 < NWMAX; ++w2) {
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const float2 e = pb[w2 * SLOTS + lane + 64 * s];
+                        if (e.x < tv[s]) { tv[s] = e.x; tp[s] = __float_as_int(e.y); }
+                    }
+                }
+                buf ^= 1;
+            } else {
+#pragma unroll
+                for (int s = 0; s < LP; ++s) { tv[s] = best[s]; tp[s] = bidx[s]; }
+            }
+
+            // ---- q = lowest argmin over lambda, reparametrisation (Eq. isgmr-norm) ----
+            float mn = INFINITY;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                if (lane + 64 * s >= L) tv[s] = INFINITY;
+                mn = fminf(mn, tv[s]);
+            }
+            mn = mrf_wave_min(mn);
+            int qidx = -1;
+            float tq = mn;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const unsigned long long bal = __ballot(tv[s] == mn);
+                if (qidx < 0 && bal != 0ull) {
+                    const int ql = __ffsll((long long)bal) - 1;
+                    qidx = 64 * s + ql;
+                    tq = mrf_readlane_f32(tv[s], ql);
                 }
             }
-            if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
+
+            // ---- outputs of node i (the wavefronts take turns) ----
+            if (wv == turn && !past) {
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    if (lam < L) {
+                        P.m_out[((size_t)r * N + i) * L + lam] = carry[s];
+                        P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
+                    }
+                }
+                if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+            }
+            turn = (turn + 1 == NW) ? 0 : turn + 1;
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c)
+#pragma unroll
+                for (int s = 0; s < LP; ++s) cur[u][c][s] = nxt[u][c][s];
         }
     }
 }
