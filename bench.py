@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: 2, the metric's)")
     ap.add_argument("--algo", default=None, help="isgmr | trwp (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune-mch", type=int, default=0, help="experiment: source labels per wavefront (0 = heuristic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -77,6 +78,8 @@ def main():
     import paper_1910_10892_amd as mrf
 
     mrf.load_library()      # no fallback: raises if libmrfmp.so is missing
+    if args.tune_mch:
+        mrf.mrf_tune(0, args.tune_mch)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     pr = make_config(args.config, algo=args.algo)
     g = GpuProblem(pr, want_messages=False)

@@ -12,7 +12,7 @@ HEADERS = ["mrfmp_device.h", "mrfmp_fwd.h", "mrfmp_bwd.h", "../../include/mrfmp.
 # -ffp-contract=off: the only fused multiply-add is the explicit one of the message update,
 #   so that floating point decisions (argmins) match a plain C evaluation order.
 # packed-fp32 instructions are switched off for the test machines of machines.
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-munsafe-fp-atomics",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall"]
 
 

@@ -238,24 +238,43 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     return MRF_OK;
 }
 
-template <int LP>
-hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, hipStream_t st)
+template <int LP, int NS, int D>
+hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((mrf_bwd_sweep<LP>), dim3((unsigned)blocks), dim3(64 * MRF_BWD_WAVES), 0, st, P);
+    if (P.gw && P.v_mode == 0)
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true>), dim3((unsigned)blocks), dim3(64 * MRF_BWD_WAVES), lds, st, P);
+    else
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false>), dim3((unsigned)blocks), dim3(64 * MRF_BWD_WAVES), lds, st, P);
     return hipGetLastError();
 }
 
-hipError_t dispatch_bwd(const MrfBwdParams &P, hipStream_t st)
+hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
 {
+    const int L = P.g.L;
+    const int LP = (L + 63) / 64;
     long long blocks = (P.total_scanlines + MRF_BWD_WAVES - 1) / MRF_BWD_WAVES;
     if (P.gV && blocks > kGradVSlots / MRF_BWD_WAVES) blocks = kGradVSlots / MRF_BWD_WAVES;
-    const int LP = (P.g.L + 63) / 64;
-    switch (LP) {
-    case 1: return launch_bwd<1>(P, blocks, st);
-    case 2: return launch_bwd<2>(P, blocks, st);
-    case 3: return launch_bwd<3>(P, blocks, st);
-    default: return launch_bwd<4>(P, blocks, st);
+    // LDS: scatter vectors, optional private V-gradient accumulators, optional copy of V
+    P.gv_lds = (P.gV && L <= 32) ? 1 : 0;
+    P.v_mode = 0;
+    if (P.gw) {
+        if ((size_t)L * L * sizeof(float) <= 40 * 1024) P.v_mode = 1;
+        else if (pairwise_kind != MRF_PAIRWISE_DENSE) P.v_mode = 2;   // promise: V(mu,lambda) = V(0,|mu-lambda|)
     }
+    const size_t lds = sizeof(double) * ((size_t)MRF_BWD_WAVES * 64 * LP + (P.gv_lds ? (size_t)MRF_BWD_WAVES * L * L : 0)) +
+                       sizeof(float) * (P.v_mode == 1 ? (size_t)L * L : (P.v_mode == 2 ? (size_t)L : 0));
+    int need = 0;
+    for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
+        if (P.n_src[r] + (P.use_gc ? 1 : 0) > need) need = P.n_src[r] + (P.use_gc ? 1 : 0);
+    const int ns = need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 8 ? 8 : 16));
+#define MRF_BCASE(lp) \
+    if (LP == lp && ns == 1) return launch_bwd<lp, 1, 4>(P, blocks, lds, st); \
+    if (LP == lp && ns == 4) return launch_bwd<lp, 4, (lp <= 2 ? 4 : 2)>(P, blocks, lds, st); \
+    if (LP == lp && ns == 8) return launch_bwd<lp, 8, 2>(P, blocks, lds, st); \
+    if (LP == lp && ns == 16) return launch_bwd<lp, 16, 1>(P, blocks, lds, st);
+    MRF_BCASE(1) MRF_BCASE(2) MRF_BCASE(3) MRF_BCASE(4)
+#undef MRF_BCASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t fill(float *dst, long long n, float v, hipStream_t st)
@@ -272,14 +291,6 @@ hipError_t fill64(double *dst, long long n, hipStream_t st)
     long long blocks = (n + 255) / 256;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(mrf_fill_f64, dim3((unsigned)blocks), dim3(256), 0, st, dst, n, 0.0);
-    return hipGetLastError();
-}
-
-hipError_t broadcast(const float *src, float *dst, long long n, int copies, hipStream_t st)
-{
-    long long blocks = (n + 255) / 256;
-    if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL(mrf_broadcast_f32, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, n, copies);
     return hipGetLastError();
 }
 
@@ -301,16 +312,24 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     const long long N = P.g.N;
     const int R = pr->R, L = pr->L, K = pr->K;
     const long long NL = N * L;
-    P.algo = algo;
-    P.V = pr->pairwise; P.w = pr->edge_weight; P.w_scalar = pr->edge_weight_scalar;
-    for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP) ? pr->rho[r] : 1.0f;
+    P.V = pr->pairwise;
     P.gw = grad_w;
+    P.gc = grad_cost;
+    P.gunary = grad_unary;
+    P.unary_dir = -1;
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
 
+    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots]
     char *ws = (char *)workspace;
-    float *buf0 = (float *)ws;                       // ISGMR: grad m-hat   TRWP: grad m
-    float *buf1 = (float *)(ws + msg_bytes(pr));     // ISGMR: S
-    double *gvslots = (double *)(ws + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
+    float *scal = (float *)ws;
+    float *buf0 = (float *)(ws + kAlign);                   // ISGMR: grad m-hat   TRWP: s per direction
+    float *buf1 = (float *)(ws + kAlign + msg_bytes(pr));   // ISGMR: s per direction
+    double *gvslots = (double *)(ws + kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
+    if (pr->edge_weight) { P.w = pr->edge_weight; P.w_mul = 1; }
+    else {
+        if (fill(scal, 1, pr->edge_weight_scalar, st) != hipSuccess) return MRF_ERR_HIP;
+        P.w = scal; P.w_mul = 0;
+    }
 
     if (grad_w && fill(grad_w, (long long)R * N, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
     if (grad_V) {
@@ -318,10 +337,6 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         if (fill64(gvslots, kGradVSlots * L * L, st) != hipSuccess) return MRF_ERR_HIP;
     }
 
-    if (algo == MRF_TRWP) {
-        if (broadcast(grad_cost, buf0, NL, R, st) != hipSuccess) return MRF_ERR_HIP;
-        if (broadcast(grad_cost, grad_unary, NL, 1, st) != hipSuccess) return MRF_ERR_HIP;
-    }
     mark(g_ev_start, st);
     if (algo == MRF_ISGMR) {
         P.r_first = 0; P.r_count = R;
@@ -330,6 +345,11 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         P.blk_begin[R] = tot;
         P.total_scanlines = tot;
         P.S = buf1;
+        for (int r = 0; r < R; ++r) {
+            // one source: grad m-hat^r itself
+            P.n_src[r] = 1; P.src_dir[r][0] = (signed char)r; P.coefG[r][0] = 1.0f; P.coefT[r][0] = 0.0f;
+            P.carry_scale[r] = 1.0f;
+        }
         MrfCombineParams C;
         memset(&C, 0, sizeof(C));
         C.NL = NL; C.R = R;
@@ -338,28 +358,43 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         long long cblocks = (NL + 255) / 256;
         if (cblocks > 32768) cblocks = 32768;
         for (int k = K - 1; k >= 0; --k) {
-            if (k == K - 1) { P.gin = grad_cost; P.gin_stride = 0; }   // back Eq. isgmr-aggregation
-            else { P.gin = buf0; P.gin_stride = NL; }
+            if (k == K - 1) { P.src_base = grad_cost; P.src_stride = 0; }   // back Eq. isgmr-aggregation
+            else { P.src_base = buf0; P.src_stride = NL; }
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
-            if (dispatch_bwd(P, st) != hipSuccess) return MRF_ERR_HIP;
+            if (dispatch_bwd(P, pr->pairwise_kind, st) != hipSuccess) return MRF_ERR_HIP;
             C.first = (k == K - 1);
             C.ghat = (k > 0) ? buf0 : nullptr;
             hipLaunchKernelGGL(mrf_isgmr_bwd_combine, dim3((unsigned)cblocks), dim3(256), 0, st, C);
             if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
         }
     } else {
-        P.G = buf0;
-        P.gunary = grad_unary;
+        P.S = buf0;
+        P.src_base = buf0; P.src_stride = NL;
+        P.unary_dir = 0;
         for (int k = K - 1; k >= 0; --k) {
-            for (int r = R - 1; r >= 0; --r) {      // reverse of the forward direction order
-                P.r_first = r; P.r_count = 1;
+            for (int d = R - 1; d >= 0; --d) {      // reverse of the forward direction order
+                P.r_first = d; P.r_count = 1;
                 P.blk_begin[0] = 0;
-                P.total_scanlines = (long long)pr->B * P.g.nscan[r];
+                P.total_scanlines = (long long)pr->B * P.g.nscan[d];
                 P.blk_begin[1] = P.total_scanlines;
+                // directions that swept since the last sweep of d: all others, except that in the
+                // first processed iteration only those after d have swept at all
+                int n = 0;
+                for (int r = 0; r < R; ++r) {
+                    if (r == d || (k == K - 1 && r < d)) continue;
+                    P.src_dir[d][n] = (signed char)r;
+                    P.coefG[d][n] = pr->rho[r] - (r == P.g.opp[d] ? 1.0f : 0.0f);
+                    P.coefT[d][n] = pr->rho[r];
+                    ++n;
+                }
+                P.n_src[d] = (signed char)n;
+                P.carry_scale[d] = pr->rho[d];
+                P.use_gc = (k == K - 1);
+                P.unary_init = (k == K - 1);
                 P.p = p + (size_t)k * pk;
                 P.q = q + (size_t)k * qk;
-                if (dispatch_bwd(P, st) != hipSuccess) return MRF_ERR_HIP;
+                if (dispatch_bwd(P, pr->pairwise_kind, st) != hipSuccess) return MRF_ERR_HIP;
             }
         }
     }
@@ -381,7 +416,7 @@ size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward)
 {
     if (check_problem(prob, algo, false) != MRF_OK) return 0;
     if (!backward) return kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob);
-    return (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob) + gradv_bytes(prob);
+    return kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob) + gradv_bytes(prob);
 }
 
 int mrf_validate(const mrf_problem *prob, int algo) { return check_problem(prob, algo, true); }

@@ -1,59 +1,92 @@
 // Backward passes of ISGMR (Alg. 3) and TRWP (Alg. 4): replay of the stored indices p, q
 // in reverse scanline order.
 //
-// One wavefront walks one scanline from its last node back to the node after its first;
-// lanes own labels (lambda = lane + 64*s).  Per node: reparametrisation backward through q
+// One wavefront walks one scanline from its last node back to its first; lanes own labels
+// (lambda = lane + 64*s).  Per node: reparametrisation backward through q
 // (Eq. supp-isgmr-back-norm), edge-weight gradient (Eq. supp-gradient-edge), V gradient
 // (Eq. supp-gradient-smoothness) into an accumulator private to the wavefront, and the
 // index scatter s(mu) = sum_{lambda : p(lambda) = mu} g(lambda) through a wavefront-private
-// LDS vector.  What the same direction passes on to node i-r stays in registers.
+// LDS vector.  What the same direction passes on to node i-r stays in registers; nothing
+// the sweep reads from memory depends on the previous node, so all of it is prefetched a
+// group of D nodes ahead.
+//
+// A sweep never read-modify-writes message gradients.  It stores s per (direction, node)
+// and later sweeps rebuild the gradient of a message from those stores:
+//   ISGMR  all directions of an iteration run in one launch; mrf_isgmr_bwd_combine then forms
+//          grad theta_i += sum_r s^r_i and grad m^d_i = sum_{r not in {d,d-}} s^r_i.
+//   TRWP   directions run one after the other (reverse forward order).  Between two sweeps
+//          of direction d every other direction r sweeps exactly once and adds
+//          rho_r s^r_i (minus s^r_i if r = d-) to grad m^d_i (Alg. 4 lines 10-11), after
+//          which grad m^d is reset; so the sweep of d reads the latest s^r of the other
+//          directions and sums them with those coefficients (plus grad c in the first
+//          processed iteration).  The sweep of direction 0 also owns grad theta_i.
 //
 // Precision: tensors in memory are float; the chain a scanline carries from node to node
 // (message gradient, its label sum, the scatter sums) and the V-gradient accumulators are
 // kept in double, so that rounding does not build up along a scanline.  On this chip
 // double adds issue at the same rate as unpacked float adds.
-//
-// ISGMR sweeps all directions in one launch, so cross-direction sums are not formed here:
-// the sweep writes s per (direction, node) and mrf_isgmr_bwd_combine adds them up in a
-// fixed order.  TRWP sweeps one direction per launch; every (node, label) is touched by
-// exactly one wavefront of the launch, so its read-modify-writes need no atomics.
 #pragma once
 
 #include "mrfmp_device.h"
 
 struct MrfBwdParams {
     MrfGeom g;
-    int algo;                              // 0 = ISGMR, 1 = TRWP
     int r_first, r_count;
     long long blk_begin[MRF_MAXR + 1];     // prefix sums of B*nscan over the launch's directions
     long long total_scanlines;
-    const float *V, *w;
-    float w_scalar;
+    const float *V;
+    const float *w;                        // [R][N] edge weights, or one float when w_mul == 0
+    int w_mul;
     const uint8_t *p, *q;                  // [R][N][L], [R][N] of this iteration
-    const float *gin;                      // ISGMR: grad m-hat, direction r at gin + r*gin_stride
-    long long gin_stride;                  //        (0 when every direction starts from grad c)
-    float *S;                              // ISGMR: [R][N][L] per-direction scatter result
-    float *G;                              // TRWP : [R][N][L] grad m, updated in place
-    float *gunary;                         // TRWP : [N][L] grad theta_i, updated in place
+    // incoming message gradient of direction d at node i = sum_c coefG[d][c] * src_c[i], where
+    // src_c = src_base + src_dir[d][c] * src_stride for c < n_src[d]; slot n_src[d] is grad c
+    // when use_gc is set
+    const float *src_base;
+    long long src_stride;
+    signed char src_dir[MRF_MAXR][MRF_MAXR];
+    signed char n_src[MRF_MAXR];
+    float coefG[MRF_MAXR][MRF_MAXR];
+    float coefT[MRF_MAXR][MRF_MAXR];       // coefficients of the same sources in grad theta_i
+    const float *gc;
+    int use_gc;
+    float *S;                              // [R][N][L] out: s of direction d at node i-d
+    float *gunary;                         // [N][L]
+    int unary_dir;                         // direction whose sweep forms grad theta_i, or -1
+    int unary_init;                        // grad theta_i is assigned (first iteration) / accumulated
     float *gw;                             // [R][N] or NULL, accumulated over iterations
     double *gV;                            // [slots][L][L] or NULL, one slot per wavefront
-    float rho[MRF_MAXR];
+    int gv_lds;                            // accumulate grad V in LDS and flush once per wavefront
+    int v_mode;                            // V for grad w: 0 global, 1 copy in LDS, 2 first row in LDS
+    float carry_scale[MRF_MAXR];           // rho_d (TRWP) or 1 (ISGMR)
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
 
-template <int LP>
+// LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
+// gradient is gathered from global memory (it fits neither LDS layout)
+template <int LP, int NS, int D, bool VG>
 __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
-    __shared__ double sbuf_all[MRF_BWD_WAVES][64 * LP];
-    const int L = P.g.L, R = P.g.R;
+    extern __shared__ __align__(16) unsigned char mrf_bsmem[];
+    const int L = P.g.L;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    double *sbuf = sbuf_all[wv];
+    double *sbuf = reinterpret_cast<double *>(mrf_bsmem) + wv * 64 * LP;
+    double *gvl = reinterpret_cast<double *>(mrf_bsmem) + MRF_BWD_WAVES * 64 * LP + (P.gv_lds ? wv * L * L : 0);
+    float *vl = reinterpret_cast<float *>(reinterpret_cast<double *>(mrf_bsmem) + MRF_BWD_WAVES * 64 * LP +
+                                          (P.gv_lds ? MRF_BWD_WAVES * L * L : 0));
     const long long slot = (long long)blockIdx.x * MRF_BWD_WAVES + wv;
     const long long nslots = (long long)gridDim.x * MRF_BWD_WAVES;
     const long long N = P.g.N;
-    const bool trwp = P.algo != 0;
     double *gVs = P.gV ? P.gV + (size_t)slot * L * L : nullptr;
+    const int vzero = mrf_opaque_zero();
+
+    if (P.v_mode == 1)
+        for (int e = threadIdx.x; e < L * L; e += blockDim.x) vl[e] = P.V[e];
+    else if (P.v_mode == 2)
+        for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
+    if (gVs && P.gv_lds)
+        for (int e = lane; e < L * L; e += 64) gvl[e] = 0.0;
+    __syncthreads();
 
     for (long long sl = slot; sl < P.total_scanlines; sl += nslots) {
         int ri = 0;
@@ -63,16 +96,33 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
         const int nsc = P.g.nscan[r];
         const int b = (int)(local / nsc);
         const long long t = local - (long long)b * nsc;
-        const int dh = P.g.dh[r], dw = P.g.dw[r], rm = P.g.opp[r];
+        const int dh = P.g.dh[r], dw = P.g.dw[r];
         int y0, x0, len;
         mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
         const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
         const long long nstep = (long long)dh * P.g.W + dw;
-        const double rho = (double)P.rho[r];
-        const float *gin = trwp ? P.G + (size_t)r * N * L : P.gin + (size_t)r * P.gin_stride;
+        const double cscale = (double)P.carry_scale[r];
+        const bool own_unary = (r == P.unary_dir);
+        const bool unary_old = own_unary && !P.unary_init;
+        const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+        const uint8_t *pbase = P.p + (size_t)r * N * L;
+        const uint8_t *qbase = P.q + (size_t)r * N;
+
+        // source slots; unused ones re-read grad c / the first source with coefficient 0
+        const float *src[NS];
+        double cG[NS], cT[NS];
+        const int nsrc = P.n_src[r];
+#pragma unroll
+        for (int c = 0; c < NS; ++c) {
+            const bool live = c < nsrc;
+            const bool isgc = (c == nsrc) && P.use_gc;
+            src[c] = live ? P.src_base + (size_t)P.src_dir[r][c] * P.src_stride : P.gc;
+            cG[c] = live ? (double)P.coefG[r][c] : (isgc ? 1.0 : 0.0);
+            cT[c] = live ? (double)P.coefT[r][c] : (isgc ? 1.0 : 0.0);
+        }
 
         // the last node of the scanline has no successor in direction r
-        if (!trwp) {
+        {
             const long long last = head + (long long)(len - 1) * nstep;
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
@@ -81,105 +131,153 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             }
         }
 
+        // prefetch registers: step tt handles node len-1-tt (clamped at the first node)
+        float cur[D][NS][LP], nxt[D][NS][LP];
+        float ucur[D][LP], unxt[D][LP];       // old grad theta_i (only read when accumulating)
+        int pcur[D][LP], pnxt[D][LP];
+        int qcur[D], qnxt[D];
+        float wcur[D], wnxt[D];
+        auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, float &wdst, int tt) {
+            int n = len - 1 - tt;
+            n = n > 0 ? n : 0;
+            const long long i = head + (long long)n * nstep;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const int lam = lane + 64 * s;
+                const int lc = lam < L ? lam : 0;
+#pragma unroll
+                for (int c = 0; c < NS; ++c) dst[c][s] = src[c][(size_t)i * L + lc];
+                udst[s] = P.gunary[(size_t)i * L + lc];
+                pdst[s] = pbase[(size_t)i * L + lc];
+            }
+            qdst = qbase[(size_t)i + vzero];
+            wdst = wbase[(size_t)(i * P.w_mul) + vzero];
+        };
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
+
         double carry[LP];   // what node i+r of this direction passed back to node i
 #pragma unroll
         for (int s = 0; s < LP; ++s) carry[s] = 0.0;
 
-        for (int n = len - 1; n >= 1; --n) {
-            const long long i = head + (long long)n * nstep;
-            const long long j = i - nstep;
-            double g[LP];
-            int pv[LP];
-            double part = 0.0;
+        for (int t0 = 0; t0 < len; t0 += D) {
 #pragma unroll
-            for (int s = 0; s < LP; ++s) {
-                const int lam = lane + 64 * s;
-                g[s] = 0.0;
-                pv[s] = 0;
-                if (lam < L) {
-                    g[s] = (double)gin[(size_t)i * L + lam] + carry[s];
-                    int pp = P.p[((size_t)r * N + i) * L + lam];
-                    pv[s] = pp < L ? pp : L - 1;
-                    if (trwp) P.G[((size_t)r * N + i) * L + lam] = 0.0f;   // zero-out (Alg. 4)
+            for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], t0 + D + u);
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                // Steps past the first node (last group only) and the first node itself run the
+                // same instructions with their stores switched off, so that the loop body has no
+                // branches around the prefetched registers.
+                const int tt = t0 + u;
+                const bool past = tt >= len;
+                const int n = past ? 0 : len - 1 - tt;
+                const bool update = !past && n > 0;      // node i has a predecessor: replay its update
+                const long long i = head + (long long)n * nstep;
+                const long long j = i - nstep;
+                double g[LP];
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    double acc = carry[s], accT = carry[s];
+#pragma unroll
+                    for (int c = 0; c < NS; ++c) {
+                        acc += cG[c] * (double)cur[u][c][s];
+                        accT += cT[c] * (double)cur[u][c][s];
+                    }
+                    g[s] = (lane + 64 * s < L) ? acc : 0.0;
+                    // grad theta_i: everything every direction passed back to node i
+                    accT += unary_old ? (double)ucur[u][s] : 0.0;   // (the buffer may hold anything at first)
+                    if (own_unary && !past && lane + 64 * s < L)
+                        P.gunary[(size_t)i * L + lane + 64 * s] = (float)accT;
                 }
-                part += g[s];
-            }
-            // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
-            const double tot = mrf_wave_sum_f64(part);
-            int qv = P.q[(size_t)r * N + i];
-            qv = qv < L ? qv : L - 1;
+                int pv[LP];
+                double part = 0.0;
 #pragma unroll
-            for (int s = 0; s < LP; ++s)
-                if (lane + 64 * s == qv) g[s] = g[s] - tot;
+                for (int s = 0; s < LP; ++s) {
+                    pv[s] = pcur[u][s] < L ? pcur[u][s] : L - 1;
+                    part += g[s];
+                }
+                // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
+                const double tot = mrf_wave_sum_f64(part);
+                const int qv = qcur[u] < L ? qcur[u] : L - 1;
+#pragma unroll
+                for (int s = 0; s < LP; ++s)
+                    if (lane + 64 * s == qv) g[s] = g[s] - tot;
 
-            const double wgt = (double)(P.w ? P.w[(size_t)r * N + i] : P.w_scalar);
-            if (P.gw) {
-                double acc = 0.0;
+                // index scatter through LDS: s(mu) = sum over lambda with p(lambda) = mu
+#pragma unroll
+                for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0;
+                mrf_wave_lds_fence();
+#pragma unroll
+                for (int s = 0; s < LP; ++s)
+                    if (lane + 64 * s < L)
+                        __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                mrf_wave_lds_fence();
+                double sv[LP];
+#pragma unroll
+                for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
+                mrf_wave_lds_fence();
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    if (lam < L) acc += g[s] * (double)P.V[(size_t)pv[s] * L + lam];
+                    if (update && lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)sv[s];
+                    carry[s] = cscale * sv[s];
                 }
-                acc = mrf_wave_sum_f64(acc);
-                if (lane == 0) P.gw[(size_t)r * N + i] = (float)((double)P.gw[(size_t)r * N + i] + acc);
-            }
-            if (gVs) {
-#pragma unroll
-                for (int s = 0; s < LP; ++s) {
-                    const int lam = lane + 64 * s;
-                    if (lam < L) gVs[(size_t)pv[s] * L + lam] += wgt * g[s];
-                }
-            }
 
-            // index scatter through LDS: s(mu) = sum over lambda with p(lambda) = mu
+                // pairwise gradients (off the node-to-node chain)
+                const double wgt = (double)wcur[u];
+                if (P.gw) {
+                    double acc = 0.0;
 #pragma unroll
-            for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0;
-            mrf_wave_lds_fence();
-#pragma unroll
-            for (int s = 0; s < LP; ++s)
-                if (lane + 64 * s < L)
-                    __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            mrf_wave_lds_fence();
-            double sv[LP];
-#pragma unroll
-            for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
-            mrf_wave_lds_fence();
-
-            if (!trwp) {
-#pragma unroll
-                for (int s = 0; s < LP; ++s) {
-                    const int lam = lane + 64 * s;
-                    if (lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)sv[s];
-                    carry[s] = sv[s];
-                }
-            } else {
-#pragma unroll
-                for (int s = 0; s < LP; ++s) {
-                    const int lam = lane + 64 * s;
-                    const double rs = rho * sv[s];
-                    if (lam < L) {
-                        const size_t e = (size_t)j * L + lam;
-                        P.gunary[e] = (float)((double)P.gunary[e] + rs);
-                        for (int d = 0; d < R; ++d) {
-                            if (d == r) continue;
-                            float *gd = P.G + (size_t)d * N * L;
-                            double v = (double)gd[e] + rs;
-                            if (d == rm) v = v - sv[s];
-                            gd[e] = (float)v;
+                    for (int s = 0; s < LP; ++s) {
+                        const int lam = lane + 64 * s;
+                        if (lam < L) {
+                            float vv;
+                            if (VG) {
+                                vv = P.V[(size_t)pv[s] * L + lam];
+                            } else {
+                                const int dist = pv[s] > lam ? pv[s] - lam : lam - pv[s];
+                                vv = vl[P.v_mode == 1 ? pv[s] * L + lam : dist];
+                            }
+                            acc += g[s] * (double)vv;
                         }
                     }
-                    carry[s] = rs;
+                    acc = mrf_wave_sum_f64(acc);
+                    // one writer per entry and launch: a no-return atomic is a plain accumulate
+                    // that does not make the wavefront wait for the old value
+                    if (update && lane == 0)
+                        __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (gVs) {
+                    // lane lambda owns column lambda of the wavefront's private accumulator
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const int lam = lane + 64 * s;
+                        if (update && lam < L) {
+                            if (P.gv_lds) gvl[pv[s] * L + lam] += wgt * g[s];
+                            else __hip_atomic_fetch_add(&gVs[(size_t)pv[s] * L + lam], wgt * g[s],
+                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                qcur[u] = qnxt[u];
+                wcur[u] = wnxt[u];
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    ucur[u][s] = unxt[u][s];
+                    pcur[u][s] = pnxt[u][s];
+#pragma unroll
+                    for (int c = 0; c < NS; ++c) cur[u][c][s] = nxt[u][c][s];
                 }
             }
         }
-        if (trwp) {
-            // gradient that reached the first node belongs to a constant message: dropped
-#pragma unroll
-            for (int s = 0; s < LP; ++s) {
-                const int lam = lane + 64 * s;
-                if (lam < L) P.G[((size_t)r * N + head) * L + lam] = 0.0f;
-            }
-        }
+    }
+    if (gVs && P.gv_lds) {
+        mrf_wave_lds_fence();
+        for (int e = lane; e < L * L; e += 64) gVs[e] += gvl[e];
     }
 }
 
@@ -234,15 +332,4 @@ __global__ void __launch_bounds__(256) mrf_fill_f32(float *dst, long long n, flo
 {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) dst[e] = val;
-}
-
-// dst[c][e] = src[e] for c < copies  (back Eq. isgmr-aggregation: every direction's message
-// gradient and the unary gradient start from grad c)
-__global__ void __launch_bounds__(256) mrf_broadcast_f32(const float *src, float *dst, long long n, int copies)
-{
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) {
-        const float v = src[e];
-        for (int c = 0; c < copies; ++c) dst[(size_t)c * n + e] = v;
-    }
 }

@@ -118,6 +118,15 @@ __device__ inline void mrf_wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// A zero the compiler cannot see through: keeps wave-uniform addresses in vector loads, so
+// that they queue behind the other prefetches instead of going through the scalar cache.
+__device__ inline int mrf_opaque_zero()
+{
+    int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
 // Workgroup barrier that orders LDS traffic only: global loads issued as prefetch stay in
 // flight across it (a full __syncthreads would wait for them).
 __device__ inline void mrf_block_sync_lds()

@@ -37,15 +37,6 @@ struct MrfFwdParams {
     int NW;                                // wavefronts per workgroup = ceil(L / MCH)
 };
 
-// A zero the compiler cannot see through: keeps wave-uniform addresses in vector loads, so
-// that they queue behind the other prefetches instead of going through the scalar cache.
-__device__ inline int mrf_opaque_zero()
-{
-    int z;
-    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
-    return z;
-}
-
 // LP: labels per lane; MCH: source labels per wavefront; RMAX: bound on 1 + n_src;
 // D: prefetch distance in nodes; TRWP: Eq. trwp (else Eq. isgmr)
 template <int LP, int MCH, int RMAX, int D, bool TRWP>
