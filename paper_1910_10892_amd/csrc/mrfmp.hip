@@ -5,6 +5,7 @@
 #include "mrfmp_fwd.h"
 #include "mrfmp_bwd.h"
 
+#include <math.h>
 #include <string.h>
 
 namespace {
@@ -71,6 +72,7 @@ size_t gradv_bytes(const mrf_problem *pr)
 // ---- forward sweep dispatch -------------------------------------------------------------
 // tuning knobs (0 = heuristic)
 int g_tune_mch = 0;
+int g_tune_no_window = 0;
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 inline void mark(hipEvent_t ev, hipStream_t st)
@@ -109,8 +111,50 @@ int pick_mch(int L, int LP, bool many_sources)
     return best;
 }
 
-hipError_t dispatch_fwd(MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
+template <int LP, int RMAX, int D>
+hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
+#define MRF_W(twv) \
+    if (tw == twv) { \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, true, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, false, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2) MRF_W(8) MRF_W(16)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
+// Distance from which a truncated pairwise function is constant, or 0 if the window
+// kernel does not apply (dense kind, no truncation inside the label range, wide window).
+int window_width(const mrf_problem *pr)
+{
+    if (g_tune_no_window || pr->pairwise_kind == MRF_PAIRWISE_DENSE) return 0;
+    double t = pr->trunc;
+    if (pr->pairwise_kind == MRF_PAIRWISE_TRUNC_QUADRATIC) t = sqrt(t);
+    if (!(t > 0.0) || t > 16.0) return 0;
+    int ti = (int)ceil(t);
+    if (ti < 1) ti = 1;
+    if (ti >= pr->L) return 0;
+    return ti <= 2 ? 2 : (ti <= 8 ? 8 : 16);
+}
+
+hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
+{
+    if (tw > 0) {
+        const int LPw = (P.g.L + 63) / 64;
+        int ms = 0;
+        for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
+            if (P.n_src[r] > ms) ms = P.n_src[r];
+        if (ms + 1 <= 8) {
+            P.NW = 1;
+#define MRF_WCASE(lp) \
+            if (LPw == lp && ms + 1 <= 4) return launch_window<lp, 4, (lp <= 2 ? 4 : 2)>(P, algo, tw, blocks, st); \
+            if (LPw == lp) return launch_window<lp, 8, (lp <= 2 ? 2 : 1)>(P, algo, tw, blocks, st);
+            MRF_WCASE(1) MRF_WCASE(2) MRF_WCASE(3) MRF_WCASE(4)
+#undef MRF_WCASE
+        }
+    }
     const int L = P.g.L;
     const int LP = (L + 63) / 64;
     int max_src = 0;
@@ -187,6 +231,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     }
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
     float *final_m = nullptr;
+    const int tw = window_width(pr);
 
     mark(g_ev_start, st);
     if (algo == MRF_ISGMR) {
@@ -201,7 +246,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
             for (int r = 0; r < R; ++r) fill_sources(P, algo, r, k == 0 ? 0u : 0xffffffffu);
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
-            if (dispatch_fwd(P, algo, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+            if (dispatch_fwd(P, algo, tw, blocks, st) != hipSuccess) return MRF_ERR_HIP;
             final_m = P.m_out;
         }
     } else {
@@ -217,7 +262,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
                 fill_sources(P, algo, r, k == 0 ? ((1u << r) - 1u) : 0xffffffffu);
                 P.p = p + (size_t)k * pk;
                 P.q = q + (size_t)k * qk;
-                if (dispatch_fwd(P, algo, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+                if (dispatch_fwd(P, algo, tw, blocks, st) != hipSuccess) return MRF_ERR_HIP;
             }
         }
         final_m = bufA;
@@ -498,6 +543,7 @@ int mrf_set_sweep_events(void *start_event, void *stop_event)
 int mrf_tune(int knob, int value)
 {
     if (knob == 0) { g_tune_mch = value; return MRF_OK; }
+    if (knob == 1) { g_tune_no_window = value; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

@@ -324,3 +324,241 @@ __global__ void __launch_bounds__(256) mrf_aggregate(const MrfAggParams P)
         }
     }
 }
+
+// ---- fast path: V(mu, lambda) = f(|mu - lambda|) with f non-decreasing and constant (= fT)
+// from distance TW on (truncated linear / quadratic models, Sec. 5.1) ------------------------
+//
+// With a non-negative edge weight every candidate inside the window |mu - lambda| < TW is
+// <= g(mu) := fma(w, fT, h(mu)), and every candidate outside it equals g(mu).  Hence
+//     min_mu Delta(lambda, mu) = min(W(lambda), gmin),   W = min over the window, gmin = min_mu g,
+// and the lowest minimiser is  pW            if W <  gmin
+//                              mu_g          if W >  gmin   (mu_g = lowest argmin of g; it is
+//                                                            then provably outside the window)
+//                              min(pW, mu_g) if W == gmin.
+// Values and indices are bit-identical to the dense evaluation; the work per label drops
+// from L to 2 TW - 1 candidates.  One wavefront walks one scanline: no workgroup barrier.
+// A node with a negative weight falls back to the full loop over mu.
+template <int LP, int RMAX, int D, bool TRWP, int TW>
+__global__ void __launch_bounds__(64)
+mrf_fwd_sweep_window(const MrfFwdParams P)
+{
+    constexpr int HB = 64 * LP + 2 * TW;          // h with TW entries of padding on both sides
+    __shared__ float hpad[HB];
+    __shared__ float ftab[TW + 1];
+    const int L = P.g.L;
+    const int lane = threadIdx.x;
+
+    const long long blk = blockIdx.x;
+    int ri = 0;
+    while (ri + 1 < P.r_count && blk >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = blk - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long N = P.g.N;
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = (c <= n_src) ? 1.0f : 0.0f;
+        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+
+    // f(d) = V(0, d) for d < TW, fT = V(0, L-1) (the promise makes every farther entry equal it)
+    float f[TW];
+#pragma unroll
+    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1];
+    const float fT = P.V[L - 1];
+    if (lane <= TW) ftab[lane] = lane < TW ? P.V[lane < L ? lane : L - 1] : fT;
+    for (int i = lane; i < HB; i += 64) hpad[i] = INFINITY;     // padding never wins a strict '<'
+    __syncthreads();
+    float *hbuf = hpad + TW;
+
+#pragma unroll
+    for (int s = 0; s < LP; ++s) {
+        const int lam = lane + 64 * s;
+        if (lam < L) {
+            P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
+            P.p[((size_t)r * N + head) * L + lam] = 0;
+        }
+    }
+    if (lane == 0) P.q[(size_t)r * N + head] = 0;
+
+    const int vzero = mrf_opaque_zero();
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len - 2;
+    float cur[D][RMAX][LP], nxt[D][RMAX][LP];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, int nj) {
+        nj = nj < lastsrc ? nj : lastsrc;
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c)
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const int lam = lane + 64 * s;
+                dst[c][s] = src[c][(size_t)j * L + (lam < L ? lam : 0)];
+            }
+        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+    };
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
+
+    float carry[LP];
+#pragma unroll
+    for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
+
+    for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int nn = n0 + u;
+            const bool past = nn >= len;
+            const int n = past ? len - 1 : nn;
+            const long long i = head + (long long)n * nstep;
+            const float wgt = wcur[u];
+
+            float a[LP], gfar[LP];
+            float gm = INFINITY;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                float v = cur[u][0][s];
+                float mrm = 0.0f;
+                if (TRWP) {
+#pragma unroll
+                    for (int c = 1; c < RMAX; ++c) {
+                        v = __builtin_fmaf(carry_at[c], carry[s], v);
+                        v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                        mrm = __builtin_fmaf(is_rm[c], cur[u][c][s], mrm);
+                    }
+                    v = __builtin_fmaf(carry_at[RMAX], carry[s], v);
+                    v = rho * v;
+                    v = v - mrm;
+                } else {
+                    v = v + carry[s];
+#pragma unroll
+                    for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                }
+                a[s] = v;
+                const int lam = lane + 64 * s;
+                if (lam < L) hbuf[lam] = v;
+                gfar[s] = lam < L ? __builtin_fmaf(wgt, fT, v) : INFINITY;
+                gm = fminf(gm, gfar[s]);
+            }
+            mrf_wave_lds_fence();
+
+            float tv[LP];
+            int tp[LP];
+            // (the weight is wave-uniform: take the branch on a scalar copy of its sign)
+            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+                // far field: lowest argmin of g over all mu
+                const float gmin = mrf_wave_min(gm);
+                int mug = 0;
+                bool found = false;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const unsigned long long bal = __ballot(gfar[s] == gmin);
+                    if (!found && bal != 0ull) { found = true; mug = 64 * s + __ffsll((long long)bal) - 1; }
+                }
+                // window |mu - lambda| < TW, ascending mu
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float dl[2 * TW - 1];
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o) {
+                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                        dl[o] = __builtin_fmaf(wgt, f[dist], hbuf[lam + o - (TW - 1)]);
+                    }
+                    float W = dl[0];
+#pragma unroll
+                    for (int o = 1; o < 2 * TW - 1; ++o) W = fminf(W, dl[o]);
+                    int po = 2 * TW - 2;
+#pragma unroll
+                    for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
+                    const int pW = lam + po - (TW - 1);
+                    const bool wlt = W < gmin, wgt_ = W > gmin;
+                    tv[s] = wlt ? W : gmin;
+                    const int tie = pW < mug ? pW : mug;
+                    tp[s] = wlt ? pW : (wgt_ ? mug : tie);
+                }
+            } else {
+                // negative weight: the ordering argument does not hold, evaluate every mu
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float best = INFINITY;
+                    int bi = 0;
+                    for (int mu = 0; mu < L; ++mu) {
+                        int dist = mu > lam ? mu - lam : lam - mu;
+                        dist = dist < TW ? dist : TW;
+                        const float dlt = __builtin_fmaf(wgt, ftab[dist], hbuf[mu]);
+                        if (dlt < best) { best = dlt; bi = mu; }
+                    }
+                    tv[s] = best;
+                    tp[s] = bi;
+                }
+            }
+            mrf_wave_lds_fence();
+
+            float mn = INFINITY;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                if (lane + 64 * s >= L) tv[s] = INFINITY;
+                mn = fminf(mn, tv[s]);
+            }
+            mn = mrf_wave_min(mn);
+            int qidx = -1;
+            float tq = mn;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const unsigned long long bal = __ballot(tv[s] == mn);
+                if (qidx < 0 && bal != 0ull) {
+                    const int ql = __ffsll((long long)bal) - 1;
+                    qidx = 64 * s + ql;
+                    tq = mrf_readlane_f32(tv[s], ql);
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
+
+            if (!past) {
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    if (lam < L) {
+                        P.m_out[((size_t)r * N + i) * L + lam] = carry[s];
+                        P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
+                    }
+                }
+                if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c)
+#pragma unroll
+                for (int s = 0; s < LP; ++s) cur[u][c][s] = nxt[u][c][s];
+        }
+    }
+}

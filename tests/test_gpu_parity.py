@@ -131,6 +131,56 @@ def test_wavefront_split_does_not_change_results(oracle, mch):
         mrf.mrf_tune(0, 0)
 
 
+def truncated_problem(seed, algo, H, W, L, dirs, K, kind, trunc, integer_valued, weights):
+    """Truncated linear (kind 1) / quadratic (kind 2) pairwise with the kind announced, so the
+    library may take its window path.  weights: 'pos' | 'zero_mix' | 'neg_mix'."""
+    from mrf_inputs import truncated_linear, truncated_quadratic
+    pr = random_problem(seed, algo, 1, H, W, L, dirs, K, integer_valued=integer_valued,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    scale = 1.0 if integer_valued else 0.37
+    pr.pairwise = truncated_linear(L, trunc, scale) if kind == 1 else truncated_quadratic(L, trunc, scale)
+    pr.pairwise_kind, pr.trunc, pr.scale = kind, float(trunc), float(scale)
+    rng = np.random.default_rng(seed + 1000)
+    if weights == "zero_mix":
+        pr.edge_weight = pr.edge_weight * (rng.random(pr.edge_weight.shape) > 0.3)
+    elif weights == "neg_mix":
+        pr.edge_weight = pr.edge_weight * np.where(rng.random(pr.edge_weight.shape) > 0.2, 1.0, -0.5)
+    pr.edge_weight = pr.edge_weight.astype(np.float32)
+    return pr
+
+
+WINDOW_CASES = [
+    # seed, algo, H, W, L, dirs, K, kind, trunc, integer_valued, weights
+    (41, "trwp", 6, 9, 96, DIRS4, 3, 1, 8.0, False, "pos"),
+    (42, "isgmr", 6, 9, 96, DIRS8, 2, 1, 8.0, True, "pos"),        # integer data: ties between window and far field
+    (43, "trwp", 5, 7, 40, DIRS4, 3, 1, 2.0, True, "zero_mix"),    # zero weights: every candidate ties
+    (44, "isgmr", 5, 7, 70, DIRS4, 2, 2, 200.0, False, "pos"),     # quadratic, window 15
+    (45, "trwp", 5, 7, 130, DIRS8, 2, 2, 30.0, True, "neg_mix"),   # negative weights take the full loop
+    (46, "isgmr", 4, 6, 200, DIRS4, 2, 1, 1.0, True, "pos"),       # Potts
+    (47, "trwp", 4, 6, 17, DIRS4, 2, 1, 16.0, False, "pos"),       # window almost as wide as the label range
+    (48, "trwp", 4, 6, 12, DIRS4, 2, 1, 20.0, False, "pos"),       # no truncation inside the range: dense kernel
+    (49, "isgmr", 5, 5, 256, DIRS4, 2, 2, 200.0, True, "zero_mix"),
+]
+
+
+@pytest.mark.parametrize("case", WINDOW_CASES, ids=lambda c: "seed%d" % c[0])
+def test_window_path_is_exact(oracle, case):
+    """Truncated models run through the window kernel; its results must equal the oracle's
+    and, bit for bit, those of the dense kernel on the same problem."""
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import run_gpu
+    print("case window", case[:5], case[7:], flush=True)
+    pr = truncated_problem(*case)
+    g = full_check(oracle, pr)
+    try:
+        assert mrf.mrf_tune(1, 1) == 0
+        d = run_gpu(pr)
+    finally:
+        mrf.mrf_tune(1, 0)
+    for name in ("p", "q", "labels", "cost", "messages"):
+        np.testing.assert_array_equal(getattr(g, name), getattr(d, name), err_msg=name)
+
+
 def test_optional_outputs_may_be_null(oracle):
     from gpu_harness import GpuProblem
     import torch
