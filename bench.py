@@ -21,13 +21,23 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
     if p not in sys.path:
         sys.path.insert(0, p)
 
-# peak of plain fp32 VALU issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
+# Peak of plain fp32 VALU issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s.
 VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9
-# one (lambda, mu) pair of the min-plus = 1 FMA + 1 compare + 2 selects = 4 VALU instructions,
-# counted as 5 flops (FMA = 2); none of them has a packed form that applies here
+# Dense sweep: one (lambda, mu) candidate = 1 FMA + 1 compare + 2 selects = 4 VALU
+# instructions, counted as 5 flops (FMA = 2).  None of them has a packed form that applies,
+# so the ceiling of this instruction mix is 5/4 flop per lane-instruction.
 FLOPS_PER_PAIR, INSTR_PER_PAIR = 5.0, 4.0
 ALU_PEAK_TFLOPS = VALU_LANE_OPS_PER_S * FLOPS_PER_PAIR / INSTR_PER_PAIR / 1e12
 HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by what
+# the same counters read for a copy of known size; filled in from profiles/*.md, keyed by
+# (workload, kernel).  None where not measured.
+MEASURED_TRAFFIC = {
+    # profiles/cfg2_trwp_stereo_kernels.md
+    ("cfg2_trwp_stereo_256x512_L96", "mrf_fwd_sweep_window"): 251.9e6,
+    ("cfg2_trwp_stereo_256x512_L96", "mrf_bwd_sweep"): 327.5e6,
+}
 
 
 def edges_per_direction(pr):
@@ -65,6 +75,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: 2, the metric's)")
     ap.add_argument("--algo", default=None, help="isgmr | trwp (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a 1 GiB device-to-device copy (calibration of HBM byte counters)")
     ap.add_argument("--tune-mch", type=int, default=0, help="experiment: source labels per wavefront (0 = heuristic)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -88,10 +100,22 @@ def main():
     B, H, W, L = pr.shape
     R, K = pr.R, pr.K
 
+    # grad_pairwise is asked for only where V is a free (dense) table, as in the segmentation
+    # configuration; truncated linear / quadratic V has no per-entry parameters to learn
+    want_V = pr.pairwise_kind == 0
+
     def step():
         g.forward()
-        g.backward()
+        g.backward(want_V=want_V)
 
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -114,7 +138,7 @@ def main():
         g.forward()
         torch.cuda.synchronize()
         fwd_ms.append(ev[0].elapsed_time(ev[1]))
-        g.backward()
+        g.backward(want_V=want_V)
         torch.cuda.synchronize()
         bwd_ms.append(ev[0].elapsed_time(ev[1]))
     mrf.mrf_set_sweep_events(None, None)
@@ -123,15 +147,33 @@ def main():
     n_fwd_launch = K * (R if pr.algo == "trwp" else 1)
     n_bwd_launch = n_fwd_launch
 
-    pairs = sum(E) * L * L * K                      # (lambda, mu) evaluations of one forward pass
-    fwd_tflops = pairs * FLOPS_PER_PAIR / (fwd_sweeps_ms * 1e-3) / 1e12
-    bwd_bytes = sum(E) * K * (9 * L + 8 * L / R + 9)  # algorithmic bytes of one backward pass
+    # Algorithmic work.  Forward: per message update (node, direction, label, iteration) the
+    # sweep reads the unary and the other directions' messages (4 B each), writes the message
+    # (4 B) and p (1 B), plus q and the edge weight once per node.  Backward: p (1 B), incoming
+    # gradient (4 B) and outgoing share (4 B) per label, grad theta read-modify-write once per node
+    # and iteration (8 B / R per direction), q + weight + weight gradient (9 B) per node.
+    window = mrf.mrf_forward_window(g.prob, g.algo)
+    opp = sum(1 for d in pr.dirs.tolist() if [-d[0], -d[1]] in pr.dirs.tolist())
+    n_in = R if pr.algo == "trwp" else (R - 1 if opp == R else R)   # label vectors read per update
+    fwd_bytes = sum(E) * K * (L * (4 * n_in + 5) + 5)
+    bwd_bytes = sum(E) * K * (9 * L + 8 * L / R + 9)
+    fwd_gbs = fwd_bytes / (fwd_sweeps_ms * 1e-3) / 1e9
     bwd_gbs = bwd_bytes / (bwd_sweeps_ms * 1e-3) / 1e9
-    roof_fwd = {"kernel": "mrf_fwd_sweep", "bound": "alu", "achieved": fwd_tflops, "peak": ALU_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": fwd_tflops / ALU_PEAK_TFLOPS, "traffic": None,
-                "launches_per_step": n_fwd_launch, "avg_launch_ms": fwd_sweeps_ms / n_fwd_launch}
+    traffic = lambda k: MEASURED_TRAFFIC.get((pr.name, k))
+    if window > 0:
+        # the window sweep evaluates 2*window-1 candidates per label instead of L: bandwidth bound
+        roof_fwd = {"kernel": "mrf_fwd_sweep_window", "bound": "hbm", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": traffic("mrf_fwd_sweep_window"),
+                    "launches_per_step": n_fwd_launch, "avg_launch_ms": fwd_sweeps_ms / n_fwd_launch,
+                    "window": window}
+    else:
+        pairs = sum(E) * L * L * K                      # (lambda, mu) candidates of one forward pass
+        fwd_tflops = pairs * FLOPS_PER_PAIR / (fwd_sweeps_ms * 1e-3) / 1e12
+        roof_fwd = {"kernel": "mrf_fwd_sweep", "bound": "alu", "achieved": fwd_tflops, "peak": ALU_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": fwd_tflops / ALU_PEAK_TFLOPS, "traffic": traffic("mrf_fwd_sweep"),
+                    "launches_per_step": n_fwd_launch, "avg_launch_ms": fwd_sweeps_ms / n_fwd_launch}
     roof_bwd = {"kernel": "mrf_bwd_sweep", "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS, "traffic": None,
+                "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS, "traffic": traffic("mrf_bwd_sweep"),
                 "launches_per_step": n_bwd_launch, "avg_launch_ms": bwd_sweeps_ms / n_bwd_launch}
     dominant, other = (roof_fwd, roof_bwd) if fwd_sweeps_ms >= bwd_sweeps_ms else (roof_bwd, roof_fwd)
 
@@ -144,7 +186,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": pr.name, "algorithm": pr.algo, "grid": [B, H, W], "labels": L, "directions": R,
                    "iterations": K, "pairwise": ["dense", "truncated_linear", "truncated_quadratic"][pr.pairwise_kind],
-                   "message_updates_per_pass": updates},
+                   "message_updates_per_pass": updates,
+                   "gradients": ["unary", "edge_weight"] + (["pairwise"] if want_V else [])},
         "roofline": dominant,
         "roofline_other": other,
         "forward_sweeps_ms": fwd_sweeps_ms, "backward_sweeps_ms": bwd_sweeps_ms,

@@ -95,6 +95,12 @@ size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward);
 /* Checks a problem description the way the entry points do; no GPU work. */
 int mrf_validate(const mrf_problem *prob, int algo);
 
+/* Which forward kernel the problem's pairwise_kind selects: 0 = the dense O(L^2) sweep,
+ * w > 0 = the window sweep that evaluates 2w - 1 source labels per label (truncated models
+ * whose truncation distance is at most 16 and below L).  Results are identical either way.
+ * Negative mrf_status for an invalid problem.  Host arithmetic. */
+int mrf_forward_window(const mrf_problem *prob, int algo);
+
 /* Forward propagation of ISGMR (Alg. 1; update Eq. isgmr, reparametrisation
  * Eq. isgmr-norm, final costs Eq. isgmr-aggregation, labelling Eq. disp).
  *   cost      DEVICE out, required

@@ -466,6 +466,14 @@ size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward)
 
 int mrf_validate(const mrf_problem *prob, int algo) { return check_problem(prob, algo, true); }
 
+int mrf_forward_window(const mrf_problem *prob, int algo)
+{
+    const int rc = check_problem(prob, algo, false);
+    if (rc != MRF_OK) return rc;
+    if (prob->R > 8) return 0;
+    return window_width(prob);
+}
+
 int mrf_isgmr_forward(const mrf_problem *prob, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
                       float *messages, void *workspace, size_t workspace_bytes, void *hip_stream)
 {

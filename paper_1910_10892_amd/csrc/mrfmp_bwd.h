@@ -104,6 +104,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
         const double cscale = (double)P.carry_scale[r];
         const bool own_unary = (r == P.unary_dir);
         const bool unary_old = own_unary && !P.unary_init;
+        const size_t umul = unary_old ? 1 : 0;
         const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
         const uint8_t *pbase = P.p + (size_t)r * N * L;
         const uint8_t *qbase = P.q + (size_t)r * N;
@@ -147,7 +148,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 const int lc = lam < L ? lam : 0;
 #pragma unroll
                 for (int c = 0; c < NS; ++c) dst[c][s] = src[c][(size_t)i * L + lc];
-                udst[s] = P.gunary[(size_t)i * L + lc];
+                udst[s] = P.gunary[((size_t)i * L + lc) * umul];   // one cached word unless it is needed
                 pdst[s] = pbase[(size_t)i * L + lc];
             }
             qdst = qbase[(size_t)i + vzero];

@@ -60,6 +60,8 @@ def load_library():
     lib.mrf_workspace_bytes.argtypes = [P, ci, ci]
     lib.mrf_validate.restype = ci
     lib.mrf_validate.argtypes = [P, ci]
+    lib.mrf_forward_window.restype = ci
+    lib.mrf_forward_window.argtypes = [P, ci]
     for name in ("mrf_isgmr_forward", "mrf_trwp_forward"):
         f = getattr(lib, name)
         f.restype = ci
@@ -164,6 +166,11 @@ def mrf_set_sweep_events(start_event, stop_event) -> int:
 def mrf_validate(prob: MrfProblem, algo: int) -> int:
     c = prob.c_struct()
     return int(load_library().mrf_validate(ctypes.byref(c), int(algo)))
+
+
+def mrf_forward_window(prob: MrfProblem, algo: int) -> int:
+    c = prob.c_struct()
+    return int(load_library().mrf_forward_window(ctypes.byref(c), int(algo)))
 
 
 def mrf_workspace_bytes(prob: MrfProblem, algo: int, backward: bool) -> int:
