@@ -384,6 +384,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
 #pragma unroll
     for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1];
     const float fT = P.V[L - 1];
+    const bool f0zero = (f[0] == 0.0f);
     if (lane <= TW) ftab[lane] = lane < TW ? P.V[lane < L ? lane : L - 1] : fT;
     for (int i = lane; i < HB; i += 64) hpad[i] = INFINITY;     // padding never wins a strict '<'
     __syncthreads();
@@ -437,7 +438,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
             const float wgt = wcur[u];
 
             float a[LP], gfar[LP];
-            float gm = INFINITY;
+            float hm = INFINITY;
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 float v = cur[u][0][s];
@@ -457,20 +458,27 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
 #pragma unroll
                     for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
                 }
-                a[s] = v;
                 const int lam = lane + 64 * s;
                 if (lam < L) hbuf[lam] = v;
+                a[s] = lam < L ? v : INFINITY;
                 gfar[s] = lam < L ? __builtin_fmaf(wgt, fT, v) : INFINITY;
-                gm = fminf(gm, gfar[s]);
+                hm = fminf(hm, a[s]);
             }
             mrf_wave_lds_fence();
 
             float tv[LP];
             int tp[LP];
+            int qidx = -1;
+            float tq;
             // (the weight is wave-uniform: take the branch on a scalar copy of its sign)
             if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
-                // far field: lowest argmin of g over all mu
-                const float gmin = mrf_wave_min(gm);
+                // One reduction serves the whole node.  g is a non-decreasing function of h, so
+                // gmin = fma(w, fT, hmin).  If moreover f(0) = 0, every candidate is >= its h(mu)
+                // >= hmin and the candidate (lambda = mu = argmin h) equals hmin, so the minimum
+                // over lambda of the new message is hmin itself: q is the lowest label that
+                // attains it and no second reduction is needed.
+                const float hmin = mrf_wave_min(hm);
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
                 int mug = 0;
                 bool found = false;
 #pragma unroll
@@ -496,9 +504,17 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                     for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
                     const int pW = lam + po - (TW - 1);
                     const bool wlt = W < gmin, wgt_ = W > gmin;
-                    tv[s] = wlt ? W : gmin;
+                    tv[s] = (lam < L) ? (wlt ? W : gmin) : INFINITY;
                     const int tie = pW < mug ? pW : mug;
                     tp[s] = wlt ? pW : (wgt_ ? mug : tie);
+                }
+                if (f0zero) {
+                    tq = hmin;
+                } else {
+                    float mn = INFINITY;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                    tq = mrf_wave_min(mn);
                 }
             } else {
                 // negative weight: the ordering argument does not hold, evaluate every mu
@@ -513,29 +529,21 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                         const float dlt = __builtin_fmaf(wgt, ftab[dist], hbuf[mu]);
                         if (dlt < best) { best = dlt; bi = mu; }
                     }
-                    tv[s] = best;
+                    tv[s] = (lam < L) ? best : INFINITY;
                     tp[s] = bi;
                 }
+                float mn = INFINITY;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                tq = mrf_wave_min(mn);
             }
             mrf_wave_lds_fence();
 
-            float mn = INFINITY;
+            // q = lowest label attaining the minimum; reparametrisation (Eq. isgmr-norm)
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
-                if (lane + 64 * s >= L) tv[s] = INFINITY;
-                mn = fminf(mn, tv[s]);
-            }
-            mn = mrf_wave_min(mn);
-            int qidx = -1;
-            float tq = mn;
-#pragma unroll
-            for (int s = 0; s < LP; ++s) {
-                const unsigned long long bal = __ballot(tv[s] == mn);
-                if (qidx < 0 && bal != 0ull) {
-                    const int ql = __ffsll((long long)bal) - 1;
-                    qidx = 64 * s + ql;
-                    tq = mrf_readlane_f32(tv[s], ql);
-                }
+                const unsigned long long bal = __ballot(tv[s] == tq);
+                if (qidx < 0 && bal != 0ull) qidx = 64 * s + __ffsll((long long)bal) - 1;
             }
 #pragma unroll
             for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
