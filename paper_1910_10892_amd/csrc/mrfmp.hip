@@ -11,7 +11,9 @@
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr long long kGradVSlots = 1024;   // wavefront-private V-gradient accumulators
+// wavefront-private V-gradient accumulators: many small ones (flushed from LDS once per
+// wavefront) for few labels, fewer large ones (updated in place) otherwise
+inline long long grad_slots(int L) { return L <= 32 ? 16384 : 1024; }
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -66,7 +68,7 @@ size_t msg_bytes(const mrf_problem *pr)
 
 size_t gradv_bytes(const mrf_problem *pr)
 {
-    return align_up((size_t)kGradVSlots * pr->L * pr->L * sizeof(double));
+    return align_up((size_t)grad_slots(pr->L) * pr->L * pr->L * sizeof(double));
 }
 
 // ---- forward sweep dispatch -------------------------------------------------------------
@@ -298,7 +300,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     const int L = P.g.L;
     const int LP = (L + 63) / 64;
     long long blocks = (P.total_scanlines + MRF_BWD_WAVES - 1) / MRF_BWD_WAVES;
-    if (P.gV && blocks > kGradVSlots / MRF_BWD_WAVES) blocks = kGradVSlots / MRF_BWD_WAVES;
+    if (P.gV && blocks > grad_slots(L) / MRF_BWD_WAVES) blocks = grad_slots(L) / MRF_BWD_WAVES;
     // LDS: scatter vectors, optional private V-gradient accumulators, optional copy of V
     P.gv_lds = (P.gV && L <= 32) ? 1 : 0;
     P.v_mode = 0;
@@ -379,7 +381,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     if (grad_w && fill(grad_w, (long long)R * N, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
     if (grad_V) {
         P.gV = gvslots;
-        if (fill64(gvslots, kGradVSlots * L * L, st) != hipSuccess) return MRF_ERR_HIP;
+        if (fill64(gvslots, grad_slots(L) * L * L, st) != hipSuccess) return MRF_ERR_HIP;
     }
 
     mark(g_ev_start, st);
@@ -446,8 +448,12 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     mark(g_ev_stop, st);
     if (grad_V) {
         const long long n = (long long)L * L;
-        hipLaunchKernelGGL(mrf_reduce_slots, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                           (const double *)gvslots, grad_V, n, kGradVSlots);
+        const long long slots = grad_slots(L), chunk = 128;
+        const unsigned eb = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(mrf_reduce_slot_chunks, dim3(eb, (unsigned)((slots + chunk - 1) / chunk)), dim3(256), 0, st,
+                           gvslots, n, slots, chunk);
+        if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+        hipLaunchKernelGGL(mrf_reduce_slot_heads, dim3(eb), dim3(256), 0, st, (const double *)gvslots, grad_V, n, slots, chunk);
         if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
     }
     return MRF_OK;

@@ -299,27 +299,52 @@ __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombinePar
 {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < P.NL; e += stride) {
-        double tot = (double)(P.first ? P.gc[e] : P.gunary[e]);
-        for (int r = 0; r < P.R; ++r) tot = tot + (double)P.S[(size_t)r * P.NL + e];
-        P.gunary[e] = (float)tot;
+        // every s^r_i is read once; sums are formed in double, where removing the two excluded
+        // directions from the total loses nothing that float storage would keep
+        double sv[MRF_MAXR];
+        double tot = 0.0;
+#pragma unroll
+        for (int r = 0; r < MRF_MAXR; ++r) {
+            sv[r] = (r < P.R) ? (double)P.S[(size_t)r * P.NL + e] : 0.0;
+            tot += sv[r];
+        }
+        const double base = (double)(P.first ? P.gc[e] : P.gunary[e]);
+        P.gunary[e] = (float)(base + tot);
         if (P.ghat) {
-            for (int d = 0; d < P.R; ++d) {
-                double v = 0.0;
-                for (int r = 0; r < P.R; ++r)
-                    if (r != d && r != P.opp[d]) v = v + (double)P.S[(size_t)r * P.NL + e];
-                P.ghat[(size_t)d * P.NL + e] = (float)v;
+#pragma unroll
+            for (int d = 0; d < MRF_MAXR; ++d) {
+                if (d < P.R) {
+                    double v = tot - sv[d];
+#pragma unroll
+                    for (int r = 0; r < MRF_MAXR; ++r)
+                        if (r == P.opp[d]) v -= sv[r];
+                    P.ghat[(size_t)d * P.NL + e] = (float)v;
+                }
             }
         }
     }
 }
 
-// dst[e] = sum over slots of src[slot][e], slots in ascending order
-__global__ void __launch_bounds__(256) mrf_reduce_slots(const double *src, float *dst, long long n, long long slots)
+// Reduction of the wavefront-private V-gradient accumulators in a fixed order, two levels:
+// first every chunk of `chunk` consecutive slots is summed into its first slot, then the
+// chunk heads are summed into the output.
+__global__ void __launch_bounds__(256) mrf_reduce_slot_chunks(double *buf, long long n, long long slots, long long chunk)
+{
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    const long long first = (long long)blockIdx.y * chunk;
+    const long long last = first + chunk < slots ? first + chunk : slots;
+    double v = 0.0;
+    for (long long s = first; s < last; ++s) v = v + buf[(size_t)s * n + e];
+    buf[(size_t)first * n + e] = v;
+}
+
+__global__ void __launch_bounds__(256) mrf_reduce_slot_heads(const double *buf, float *dst, long long n, long long slots, long long chunk)
 {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n) return;
     double v = 0.0;
-    for (long long s = 0; s < slots; ++s) v = v + src[(size_t)s * n + e];
+    for (long long s = 0; s < slots; s += chunk) v = v + buf[(size_t)s * n + e];
     dst[e] = (float)v;
 }
 
