@@ -156,6 +156,8 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
 /* Process-global tuning knobs for experiments; results never depend on them.
  *   knob 0: source labels per wavefront in the dense forward sweep (8, 12, 16, 24, 32, 48; 0 = heuristic)
  *   knob 1: non-zero = ignore pairwise_kind and always run the dense forward sweep
+ *   knob 2: window sweep layout: 0 = by launch size, 1 = one wavefront per scanline,
+ *           2 = one wavefront per 64 labels whenever L > 64
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

@@ -75,6 +75,7 @@ size_t gradv_bytes(const mrf_problem *pr)
 // tuning knobs (0 = heuristic)
 int g_tune_mch = 0;
 int g_tune_no_window = 0;
+int g_tune_split = 0;      // 0 auto, 1 never, 2 whenever L > 64
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 inline void mark(hipEvent_t ev, hipStream_t st)
@@ -127,6 +128,21 @@ hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long bloc
     return hipErrorInvalidValue;
 }
 
+template <int RMAX, int D>
+hipError_t launch_window_split(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
+{
+    const unsigned threads = 64u * (unsigned)((P.g.L + 63) / 64);
+#define MRF_W(twv) \
+    if (tw == twv) { \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_split<RMAX, D, true, twv>), dim3((unsigned)blocks), dim3(threads), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_window_split<RMAX, D, false, twv>), dim3((unsigned)blocks), dim3(threads), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2) MRF_W(8) MRF_W(16)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
 // Distance from which a truncated pairwise function is constant, or 0 if the window
 // kernel does not apply (dense kind, no truncation inside the label range, wide window).
 int window_width(const mrf_problem *pr)
@@ -148,6 +164,14 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         int ms = 0;
         for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
             if (P.n_src[r] > ms) ms = P.n_src[r];
+        // few scanlines in the launch and many labels: spread each node step over one
+        // wavefront per 64 labels
+        const bool split = LPw > 1 && g_tune_split != 1 && (g_tune_split == 2 || (LPw >= 3 && blocks * LPw <= 4096));
+        if (ms + 1 <= 8 && split) {
+            P.NW = LPw;
+            if (ms + 1 <= 4) return launch_window_split<4, 4>(P, algo, tw, blocks, st);
+            return launch_window_split<8, 2>(P, algo, tw, blocks, st);
+        }
         if (ms + 1 <= 8) {
             P.NW = 1;
 #define MRF_WCASE(lp) \
@@ -558,6 +582,7 @@ int mrf_tune(int knob, int value)
 {
     if (knob == 0) { g_tune_mch = value; return MRF_OK; }
     if (knob == 1) { g_tune_no_window = value; return MRF_OK; }
+    if (knob == 2) { g_tune_split = value; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

@@ -159,7 +159,8 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 
         double carry[LP];   // what node i+r of this direction passed back to node i
 #pragma unroll
-        for (int s = 0; s < LP; ++s) carry[s] = 0.0;
+        for (int s = 0; s < LP; ++s) { carry[s] = 0.0; sbuf[lane + 64 * s] = 0.0; }
+        mrf_wave_lds_fence();
 
         for (int t0 = 0; t0 < len; t0 += D) {
 #pragma unroll
@@ -178,17 +179,21 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 double g[LP];
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
-                    double acc = carry[s], accT = carry[s];
+                    double acc = carry[s];
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) {
-                        acc += cG[c] * (double)cur[u][c][s];
-                        accT += cT[c] * (double)cur[u][c][s];
-                    }
+                    for (int c = 0; c < NS; ++c) acc += cG[c] * (double)cur[u][c][s];
                     g[s] = (lane + 64 * s < L) ? acc : 0.0;
+                }
+                if (own_unary) {
                     // grad theta_i: everything every direction passed back to node i
-                    accT += unary_old ? (double)ucur[u][s] : 0.0;   // (the buffer may hold anything at first)
-                    if (own_unary && !past && lane + 64 * s < L)
-                        P.gunary[(size_t)i * L + lane + 64 * s] = (float)accT;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        double accT = carry[s];
+#pragma unroll
+                        for (int c = 0; c < NS; ++c) accT += cT[c] * (double)cur[u][c][s];
+                        accT += unary_old ? (double)ucur[u][s] : 0.0;   // (the buffer may hold anything at first)
+                        if (!past && lane + 64 * s < L) P.gunary[(size_t)i * L + lane + 64 * s] = (float)accT;
+                    }
                 }
                 int pv[LP];
                 double part = 0.0;
@@ -205,9 +210,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     if (lane + 64 * s == qv) g[s] = g[s] - tot;
 
                 // index scatter through LDS: s(mu) = sum over lambda with p(lambda) = mu
-#pragma unroll
-                for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0;
-                mrf_wave_lds_fence();
+                // (sbuf was cleared right after the previous step read it)
 #pragma unroll
                 for (int s = 0; s < LP; ++s)
                     if (lane + 64 * s < L)
@@ -217,6 +220,8 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 #pragma unroll
                 for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
                 mrf_wave_lds_fence();
+#pragma unroll
+                for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0;
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;

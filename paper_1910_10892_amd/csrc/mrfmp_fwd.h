@@ -570,3 +570,231 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
         }
     }
 }
+
+// ---- window sweep, one label per lane, ceil(L/64) wavefronts per scanline ------------------
+//
+// Same arithmetic as mrf_fwd_sweep_window, laid out for launches with few scanlines (TRWP
+// sweeps one direction at a time): a lone wavefront issues one instruction every four
+// cycles, so the node step is spread over NWV wavefronts that each own 64 labels.  They
+// meet once per node: every wavefront publishes its slice of h and its local minimum of h,
+// then (after one LDS-only barrier) knows hmin, finds the lowest argmin of g by looking at
+// all slices, evaluates its own windows and normalises by hmin without further exchange.
+// q is assembled from per-wavefront candidates one node later, after the next barrier.
+// Nodes where the single-reduction argument does not apply (negative weight, f(0) != 0)
+// take a second barrier.
+template <int RMAX, int D, bool TRWP, int TW>
+__global__ void __launch_bounds__(256)
+mrf_fwd_sweep_window_split(const MrfFwdParams P)
+{
+    constexpr int HB = 256 + 2 * TW;
+    __shared__ float hpad[2][HB];
+    __shared__ float ftab[TW + 1];
+    __shared__ __align__(16) float hmslot[2][4];     // local minima of h
+    __shared__ __align__(16) float tmslot[2][4];     // local minima of the new message (general path)
+    __shared__ __align__(16) int qslot[2][4];        // local candidates for q
+    const int L = P.g.L;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int NWV = blockDim.x >> 6;
+    const int lam = wv * 64 + lane;
+    const bool valid = lam < L;
+    const int lamc = valid ? lam : 0;
+
+    const long long blk = blockIdx.x;
+    int ri = 0;
+    while (ri + 1 < P.r_count && blk >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = blk - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long N = P.g.N;
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = (c <= n_src) ? 1.0f : 0.0f;
+        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+
+    float f[TW];
+#pragma unroll
+    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1];
+    const float fT = P.V[L - 1];
+    const bool f0zero = (f[0] == 0.0f);
+    if (threadIdx.x <= TW) ftab[threadIdx.x] = (int)threadIdx.x < TW ? P.V[(int)threadIdx.x < L ? threadIdx.x : L - 1] : fT;
+    for (int i = threadIdx.x; i < 2 * HB; i += blockDim.x) (&hpad[0][0])[i] = INFINITY;
+    if (threadIdx.x < 8) {
+        (&hmslot[0][0])[threadIdx.x] = INFINITY;
+        (&tmslot[0][0])[threadIdx.x] = INFINITY;
+        (&qslot[0][0])[threadIdx.x] = -1;
+    }
+    __syncthreads();
+
+    if (valid) {
+        P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
+        P.p[((size_t)r * N + head) * L + lam] = 0;
+    }
+    if (threadIdx.x == 0) P.q[(size_t)r * N + head] = 0;
+
+    const int vzero = mrf_opaque_zero();
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len - 2;
+    float cur[D][RMAX], nxt[D][RMAX];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX], float &wdst, int nj) {
+        nj = nj < lastsrc ? nj : lastsrc;
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][(size_t)j * L + lamc];
+        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+    };
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
+
+    float carry = 0.0f;
+    int par = 0, qpar = 0;
+    long long qnode = -1;      // node whose q is still to be stored (wavefront 0), candidates in qslot[qpar]
+
+    for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int nn = n0 + u;
+            const bool past = nn >= len;
+            const int n = past ? len - 1 : nn;
+            const long long i = head + (long long)n * nstep;
+            const float wgt = wcur[u];
+            float *hb = &hpad[par][TW];
+
+            float v = cur[u][0];
+            if (TRWP) {
+                float mrm = 0.0f;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) {
+                    v = __builtin_fmaf(carry_at[c], carry, v);
+                    v = __builtin_fmaf(use[c], cur[u][c], v);
+                    mrm = __builtin_fmaf(is_rm[c], cur[u][c], mrm);
+                }
+                v = __builtin_fmaf(carry_at[RMAX], carry, v);
+                v = rho * v;
+                v = v - mrm;
+            } else {
+                v = v + carry;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+            }
+            if (valid) hb[lam] = v;
+            const float hloc = mrf_wave_min(valid ? v : INFINITY);
+            if (lane == 0) hmslot[par][wv] = hloc;
+            mrf_block_sync_lds();
+
+            // q of the previous node: first wavefront that had a candidate
+            if (wv == 0 && qnode >= 0) {
+                const int4 qc = *reinterpret_cast<const int4 *>(&qslot[qpar][0]);
+                const int qv = qc.x >= 0 ? qc.x : (qc.y >= 0 ? qc.y : (qc.z >= 0 ? qc.z : qc.w));
+                if (lane == 0) P.q[(size_t)r * N + qnode] = (uint8_t)qv;
+            }
+
+            const float4 hm4 = *reinterpret_cast<const float4 *>(&hmslot[par][0]);
+            const float hmin = fminf(fminf(hm4.x, hm4.y), fminf(hm4.z, hm4.w));
+            const bool wpos = __builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0;
+            float tv;
+            int tp;
+            if (wpos) {
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
+                // lowest argmin of g over all labels: look at every wavefront's slice of h
+                int mug = 0;
+                bool found = false;
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) {
+                    if (w2 < NWV) {
+                        const float g2 = __builtin_fmaf(wgt, fT, hb[w2 * 64 + lane]);   // padding is +inf
+                        const unsigned long long bal = __ballot(g2 == gmin);
+                        if (!found && bal != 0ull) { found = true; mug = 64 * w2 + __ffsll((long long)bal) - 1; }
+                    }
+                }
+                float dl[2 * TW - 1];
+#pragma unroll
+                for (int o = 0; o < 2 * TW - 1; ++o) {
+                    const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                    dl[o] = __builtin_fmaf(wgt, f[dist], hb[lam + o - (TW - 1)]);
+                }
+                float W = dl[0];
+#pragma unroll
+                for (int o = 1; o < 2 * TW - 1; ++o) W = fminf(W, dl[o]);
+                int po = 2 * TW - 2;
+#pragma unroll
+                for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
+                const int pW = lam + po - (TW - 1);
+                const bool wlt = W < gmin, wgt_ = W > gmin;
+                tv = valid ? (wlt ? W : gmin) : INFINITY;
+                const int tie = pW < mug ? pW : mug;
+                tp = wlt ? pW : (wgt_ ? mug : tie);
+            } else {
+                float best = INFINITY;
+                int bi = 0;
+                for (int mu = 0; mu < L; ++mu) {
+                    int dist = mu > lam ? mu - lam : lam - mu;
+                    dist = dist < TW ? dist : TW;
+                    const float dlt = __builtin_fmaf(wgt, ftab[dist], hb[mu]);
+                    if (dlt < best) { best = dlt; bi = mu; }
+                }
+                tv = valid ? best : INFINITY;
+                tp = bi;
+            }
+            float tq = hmin;
+            if (!(wpos && f0zero)) {
+                // general case: the minimum of the new message needs its own exchange
+                const float tloc = mrf_wave_min(tv);
+                if (lane == 0) tmslot[par][wv] = tloc;
+                mrf_block_sync_lds();
+                const float4 t4 = *reinterpret_cast<const float4 *>(&tmslot[par][0]);
+                tq = fminf(fminf(t4.x, t4.y), fminf(t4.z, t4.w));
+            }
+            const unsigned long long qb = __ballot(tv == tq);
+            carry = tv - tq;
+
+            // steps past the end of the scanline (last group only) leave no trace
+            if (!past) {
+                if (lane == 0) qslot[par][wv] = qb != 0ull ? wv * 64 + __ffsll((long long)qb) - 1 : -1;
+                if (valid) {
+                    P.m_out[((size_t)r * N + i) * L + lam] = carry;
+                    P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp;
+                }
+                qnode = i;
+                qpar = par;
+            }
+            par ^= 1;
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c) cur[u][c] = nxt[u][c];
+        }
+    }
+    // q of the last node
+    __syncthreads();
+    if (wv == 0 && qnode >= 0) {
+        const int4 qc = *reinterpret_cast<const int4 *>(&qslot[qpar][0]);
+        const int qv = qc.x >= 0 ? qc.x : (qc.y >= 0 ? qc.y : (qc.z >= 0 ? qc.z : qc.w));
+        if (lane == 0) P.q[(size_t)r * N + qnode] = (uint8_t)qv;
+    }
+}

@@ -171,14 +171,19 @@ def test_window_path_is_exact(oracle, case):
     from gpu_harness import run_gpu
     print("case window", case[:5], case[7:], flush=True)
     pr = truncated_problem(*case)
-    g = full_check(oracle, pr)
     try:
-        assert mrf.mrf_tune(1, 1) == 0
+        assert mrf.mrf_tune(2, 1) == 0          # one wavefront per scanline
+        g = full_check(oracle, pr)
+        assert mrf.mrf_tune(2, 2) == 0          # one wavefront per 64 labels
+        g2 = full_check(oracle, pr)
+        assert mrf.mrf_tune(1, 1) == 0          # dense sweep
         d = run_gpu(pr)
     finally:
         mrf.mrf_tune(1, 0)
+        mrf.mrf_tune(2, 0)
     for name in ("p", "q", "labels", "cost", "messages"):
         np.testing.assert_array_equal(getattr(g, name), getattr(d, name), err_msg=name)
+        np.testing.assert_array_equal(getattr(g2, name), getattr(d, name), err_msg=name)
 
 
 def test_optional_outputs_may_be_null(oracle):
