@@ -312,10 +312,13 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
 template <int LP, int NS, int D>
 hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
+    const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_WAVES);
     if (P.gw && P.v_mode == 0)
-        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true>), dim3((unsigned)blocks), dim3(64 * MRF_BWD_WAVES), lds, st, P);
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false>), grid, block, lds, st, P);
+    else if (P.hot_label)
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true>), grid, block, lds, st, P);
     else
-        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false>), dim3((unsigned)blocks), dim3(64 * MRF_BWD_WAVES), lds, st, P);
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, false>), grid, block, lds, st, P);
     return hipGetLastError();
 }
 
@@ -327,6 +330,9 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     if (P.gV && blocks > grad_slots(L) / MRF_BWD_WAVES) blocks = grad_slots(L) / MRF_BWD_WAVES;
     // LDS: scatter vectors, optional private V-gradient accumulators, optional copy of V
     P.gv_lds = (P.gV && L <= 32) ? 1 : 0;
+    // truncated models scatter most labels to one target; pre-reducing it pays when LDS
+    // conflicts, not instruction issue, bound the step
+    P.hot_label = (pairwise_kind != MRF_PAIRWISE_DENSE && (L > 128 || P.total_scanlines > 1024)) ? 1 : 0;
     P.v_mode = 0;
     if (P.gw) {
         if ((size_t)L * L * sizeof(float) <= 40 * 1024) P.v_mode = 1;

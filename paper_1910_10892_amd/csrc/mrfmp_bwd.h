@@ -57,14 +57,16 @@ struct MrfBwdParams {
     double *gV;                            // [slots][L][L] or NULL, one slot per wavefront
     int gv_lds;                            // accumulate grad V in LDS and flush once per wavefront
     int v_mode;                            // V for grad w: 0 global, 1 copy in LDS, 2 first row in LDS
+    int hot_label;                         // pre-reduce the most popular scatter target (truncated models)
     float carry_scale[MRF_MAXR];           // rho_d (TRWP) or 1 (ISGMR)
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
 
 // LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
-// gradient is gathered from global memory (it fits neither LDS layout)
-template <int LP, int NS, int D, bool VG>
+// gradient is gathered from global memory (it fits neither LDS layout), HOT: pre-reduce the
+// most popular scatter target
+template <int LP, int NS, int D, bool VG, bool HOT>
 __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
@@ -202,9 +204,44 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     pv[s] = pcur[u][s] < L ? pcur[u][s] : L - 1;
                     part += g[s];
                 }
+                // Truncated models send most labels to one source label (the far-field minimiser),
+                // which would serialise the LDS adds below.  Guess that label from p at the first
+                // and at the last label (one of the two is far from it), take the commoner of the
+                // two, and sum its lanes with a DPP tree instead.
+                // (Only worth its instructions when the launch is not latency bound or L is large.)
+                int hot = -1;
+                double hpart = 0.0;
+                if (HOT) {
+                    const int c0 = __builtin_amdgcn_readlane(pv[0], 0);
+                    int c1 = c0;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s)
+                        if (((L - 1) >> 6) == s) c1 = __builtin_amdgcn_readlane(pv[s], (L - 1) & 63);
+                    int n0 = 0, n1 = 0;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const bool vld = lane + 64 * s < L;
+                        n0 += __popcll(__ballot(vld && pv[s] == c0));
+                        n1 += __popcll(__ballot(vld && pv[s] == c1));
+                    }
+                    hot = n1 > n0 ? c1 : c0;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s)
+                        if (lane + 64 * s < L && pv[s] == hot) hpart += g[s];
+                }
                 // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
                 const double tot = mrf_wave_sum_f64(part);
-                const int qv = qcur[u] < L ? qcur[u] : L - 1;
+                double hsum = 0.0;
+                int qv = __builtin_amdgcn_readfirstlane(qcur[u]);
+                qv = qv < L ? qv : L - 1;
+                if (HOT) {
+                    hsum = mrf_wave_sum_f64(hpart);
+                    int pq = 0;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s)
+                        if ((qv >> 6) == s) pq = __builtin_amdgcn_readlane(pv[s], qv & 63);
+                    if (pq == hot) hsum -= tot;
+                }
 #pragma unroll
                 for (int s = 0; s < LP; ++s)
                     if (lane + 64 * s == qv) g[s] = g[s] - tot;
@@ -213,12 +250,15 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 // (sbuf was cleared right after the previous step read it)
 #pragma unroll
                 for (int s = 0; s < LP; ++s)
-                    if (lane + 64 * s < L)
+                    if (lane + 64 * s < L && pv[s] != hot)
                         __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 mrf_wave_lds_fence();
                 double sv[LP];
 #pragma unroll
-                for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
+                for (int s = 0; s < LP; ++s) {
+                    sv[s] = sbuf[lane + 64 * s];
+                    if (lane + 64 * s == hot) sv[s] += hsum;
+                }
                 mrf_wave_lds_fence();
 #pragma unroll
                 for (int s = 0; s < LP; ++s) sbuf[lane + 64 * s] = 0.0;
