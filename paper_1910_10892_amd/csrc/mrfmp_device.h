@@ -85,13 +85,29 @@ __device__ inline double mrf_readlane_f64(double v, int lane)
     return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
 }
 
+// Plain hardware minimum.  Inputs here are never NaN; fminf() would first canonicalise
+// every operand that comes from memory (one extra instruction each).
+__device__ inline float mrf_min(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+__device__ inline float mrf_min3(float a, float b, float c)
+{
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // minimum over the 64 lanes, returned to every lane (wave-uniform)
 __device__ inline float mrf_wave_min(float v)
 {
-    v = fminf(v, mrf_dpp_f32<0xB1>(v));
-    v = fminf(v, mrf_dpp_f32<0x4E>(v));
-    v = fminf(v, mrf_dpp_f32<0x141>(v));
-    v = fminf(v, mrf_dpp_f32<0x140>(v));
+    v = mrf_min(v, mrf_dpp_f32<0xB1>(v));
+    v = mrf_min(v, mrf_dpp_f32<0x4E>(v));
+    v = mrf_min(v, mrf_dpp_f32<0x141>(v));
+    v = mrf_min(v, mrf_dpp_f32<0x140>(v));
     const float r0 = mrf_readlane_f32(v, 0), r1 = mrf_readlane_f32(v, 16);
     const float r2 = mrf_readlane_f32(v, 32), r3 = mrf_readlane_f32(v, 48);
     return fminf(fminf(r0, r1), fminf(r2, r3));
@@ -123,6 +139,16 @@ __device__ inline void mrf_wave_lds_fence()
 __device__ inline int mrf_opaque_zero()
 {
     int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// The same for floats: adding it to a wave-uniform value keeps that value in a vector
+// register.  Kernels with many uniform constants (flags, small tables) otherwise run out of
+// scalar registers and pay a v_readlane for every use of a spilled one.
+__device__ inline float mrf_opaque_zero_f()
+{
+    float z;
     asm volatile("v_mov_b32 %0, 0" : "=v"(z));
     return z;
 }

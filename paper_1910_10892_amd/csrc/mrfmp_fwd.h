@@ -76,17 +76,18 @@ mrf_fwd_sweep(const MrfFwdParams P)
     // live terms with this direction's running message inserted after the first n_pre.
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    const float vz = mrf_opaque_zero_f();     // keeps the flags below in vector registers
     src[0] = P.unary;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
         src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
-        use[c] = (c <= n_src) ? 1.0f : 0.0f;
-        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+        use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
+        is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
 #pragma unroll
-    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = ((c == n_pre + 1) ? 1.0f : 0.0f) + vz;
 
     // this wavefront's slice of V: rows mu0 .. mu0+MCH-1, columns = the lane's lambdas
     const int mu0 = wv * MCH;
@@ -255,7 +256,7 @@ mrf_fwd_sweep(const MrfFwdParams P)
                 }
             }
 #pragma unroll
-            for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
+            for (int s = 0; s < LP; ++s) carry[s] = (lane + 64 * s < L) ? tv[s] - tq : 0.0f;
 
             // ---- outputs of node i (the wavefronts take turns) ----
             if (wv == turn && !past) {
@@ -367,24 +368,25 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
 
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    const float vz = mrf_opaque_zero_f();     // keeps the flags below in vector registers
     src[0] = P.unary;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
         src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
-        use[c] = (c <= n_src) ? 1.0f : 0.0f;
-        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+        use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
+        is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
 #pragma unroll
-    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = ((c == n_pre + 1) ? 1.0f : 0.0f) + vz;
 
     // f(d) = V(0, d) for d < TW, fT = V(0, L-1) (the promise makes every farther entry equal it)
     float f[TW];
 #pragma unroll
-    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1];
-    const float fT = P.V[L - 1];
-    const bool f0zero = (f[0] == 0.0f);
+    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1] + vz;
+    const float fT = P.V[L - 1] + vz;
+    const bool f0zero = (P.V[0] == 0.0f);
     if (lane <= TW) ftab[lane] = lane < TW ? P.V[lane < L ? lane : L - 1] : fT;
     for (int i = lane; i < HB; i += 64) hpad[i] = INFINITY;     // padding never wins a strict '<'
     __syncthreads();
@@ -462,7 +464,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                 if (lam < L) hbuf[lam] = v;
                 a[s] = lam < L ? v : INFINITY;
                 gfar[s] = lam < L ? __builtin_fmaf(wgt, fT, v) : INFINITY;
-                hm = fminf(hm, a[s]);
+                hm = mrf_min(hm, a[s]);
             }
             mrf_wave_lds_fence();
 
@@ -498,7 +500,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                     }
                     float W = dl[0];
 #pragma unroll
-                    for (int o = 1; o < 2 * TW - 1; ++o) W = fminf(W, dl[o]);
+                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
                     int po = 2 * TW - 2;
 #pragma unroll
                     for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
@@ -546,7 +548,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                 if (qidx < 0 && bal != 0ull) qidx = 64 * s + __ffsll((long long)bal) - 1;
             }
 #pragma unroll
-            for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
+            for (int s = 0; s < LP; ++s) carry[s] = (lane + 64 * s < L) ? tv[s] - tq : 0.0f;
 
             if (!past) {
 #pragma unroll
@@ -618,23 +620,24 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
 
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    const float vz = mrf_opaque_zero_f();     // keeps the flags below in vector registers
     src[0] = P.unary;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
         src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
-        use[c] = (c <= n_src) ? 1.0f : 0.0f;
-        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+        use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
+        is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
 #pragma unroll
-    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = ((c == n_pre + 1) ? 1.0f : 0.0f) + vz;
 
     float f[TW];
 #pragma unroll
-    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1];
-    const float fT = P.V[L - 1];
-    const bool f0zero = (f[0] == 0.0f);
+    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1] + vz;
+    const float fT = P.V[L - 1] + vz;
+    const bool f0zero = (P.V[0] == 0.0f);
     if (threadIdx.x <= TW) ftab[threadIdx.x] = (int)threadIdx.x < TW ? P.V[(int)threadIdx.x < L ? threadIdx.x : L - 1] : fT;
     for (int i = threadIdx.x; i < 2 * HB; i += blockDim.x) (&hpad[0][0])[i] = INFINITY;
     if (threadIdx.x < 8) {
@@ -738,7 +741,7 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
                 }
                 float W = dl[0];
 #pragma unroll
-                for (int o = 1; o < 2 * TW - 1; ++o) W = fminf(W, dl[o]);
+                for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
                 int po = 2 * TW - 2;
 #pragma unroll
                 for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
@@ -769,7 +772,7 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
                 tq = fminf(fminf(t4.x, t4.y), fminf(t4.z, t4.w));
             }
             const unsigned long long qb = __ballot(tv == tq);
-            carry = tv - tq;
+            carry = valid ? tv - tq : 0.0f;
 
             // steps past the end of the scanline (last group only) leave no trace
             if (!past) {
