@@ -322,6 +322,17 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
     return hipGetLastError();
 }
 
+template <int NS, int D>
+hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
+{
+    const dim3 grid((unsigned)blocks), block(64u * (unsigned)((P.g.L + 63) / 64));
+    if (P.gw && P.v_mode == 0)
+        hipLaunchKernelGGL((mrf_bwd_sweep_split<NS, D, true>), grid, block, lds, st, P);
+    else
+        hipLaunchKernelGGL((mrf_bwd_sweep_split<NS, D, false>), grid, block, lds, st, P);
+    return hipGetLastError();
+}
+
 hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
 {
     const int L = P.g.L;
@@ -344,6 +355,18 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
         if (P.n_src[r] + (P.use_gc ? 1 : 0) > need) need = P.n_src[r] + (P.use_gc ? 1 : 0);
     const int ns = need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 8 ? 8 : 16));
+    // few scanlines and many labels: one wavefront per 64 labels
+    const bool split = LP >= 3 && g_tune_split != 1 && ns <= 8 &&
+                       (g_tune_split == 2 || P.total_scanlines * LP <= 4096);
+    if (split) {
+        long long sblocks = P.total_scanlines;
+        if (P.gV && sblocks > grad_slots(L)) sblocks = grad_slots(L);
+        const size_t slds = sizeof(float) * (P.v_mode == 1 ? (size_t)L * L : (P.v_mode == 2 ? (size_t)L : 0));
+        P.gv_lds = 0;
+        if (ns == 1) return launch_bwd_split<1, 4>(P, sblocks, slds, st);
+        if (ns == 4) return launch_bwd_split<4, 4>(P, sblocks, slds, st);
+        return launch_bwd_split<8, 2>(P, sblocks, slds, st);
+    }
 #define MRF_BCASE(lp) \
     if (LP == lp && ns == 1) return launch_bwd<lp, 1, 4>(P, blocks, lds, st); \
     if (LP == lp && ns == 4) return launch_bwd<lp, 4, (lp <= 2 ? 4 : 2)>(P, blocks, lds, st); \

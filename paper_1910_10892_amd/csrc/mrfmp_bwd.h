@@ -327,6 +327,197 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
     }
 }
 
+// ---- index replay, one label per lane, ceil(L/64) wavefronts per scanline --------------------
+//
+// Same arithmetic as mrf_bwd_sweep for launches with few scanlines and many labels (a lone
+// wavefront with 3-4 labels per lane is bound by instruction issue).  Every wavefront owns 64
+// labels: it scatters their g into its own copy of the target vector and publishes their sum;
+// after one LDS-only barrier each wavefront adds the copies for its own 64 targets in
+// wavefront order (fixed order: reproducible), applies the reparametrisation correction
+// (the target p(q) loses the label sum) and carries on.  Copies alternate between two sets so
+// that one barrier per node is enough; the edge-weight gradient is assembled one node later.
+template <int NS, int D, bool VG>
+__global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
+{
+    extern __shared__ __align__(16) unsigned char mrf_bsmem[];
+    __shared__ double cp[2][4][256];
+    __shared__ double psum[2][4];
+    __shared__ double gwp[2][4];
+    __shared__ int pqs[2];
+    float *vl = reinterpret_cast<float *>(mrf_bsmem);
+    const int L = P.g.L;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int NWV = blockDim.x >> 6;
+    const int lam = wv * 64 + lane;
+    const bool valid = lam < L;
+    const int lc = valid ? lam : 0;
+    const long long N = P.g.N;
+    double *gVs = P.gV ? P.gV + (size_t)blockIdx.x * L * L : nullptr;
+    const int vzero = mrf_opaque_zero();
+
+    if (P.v_mode == 1)
+        for (int e = threadIdx.x; e < L * L; e += blockDim.x) vl[e] = P.V[e];
+    else if (P.v_mode == 2)
+        for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
+    if (threadIdx.x < 8) { (&psum[0][0])[threadIdx.x] = 0.0; (&gwp[0][0])[threadIdx.x] = 0.0; }
+
+    for (long long sl = blockIdx.x; sl < P.total_scanlines; sl += gridDim.x) {
+        int ri = 0;
+        while (ri + 1 < P.r_count && sl >= P.blk_begin[ri + 1]) ++ri;
+        const int r = P.r_first + ri;
+        const long long local = sl - P.blk_begin[ri];
+        const int nsc = P.g.nscan[r];
+        const int b = (int)(local / nsc);
+        const long long t = local - (long long)b * nsc;
+        const int dh = P.g.dh[r], dw = P.g.dw[r];
+        int y0, x0, len;
+        mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+        const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+        const long long nstep = (long long)dh * P.g.W + dw;
+        const double cscale = (double)P.carry_scale[r];
+        const bool own_unary = (r == P.unary_dir);
+        const bool unary_old = own_unary && !P.unary_init;
+        const size_t umul = unary_old ? 1 : 0;
+        const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+        const uint8_t *pbase = P.p + (size_t)r * N * L;
+        const uint8_t *qbase = P.q + (size_t)r * N;
+
+        const float *src[NS];
+        double cG[NS], cT[NS];
+        const int nsrc = P.n_src[r];
+#pragma unroll
+        for (int c = 0; c < NS; ++c) {
+            const bool live = c < nsrc;
+            const bool isgc = (c == nsrc) && P.use_gc;
+            src[c] = live ? P.src_base + (size_t)P.src_dir[r][c] * P.src_stride : P.gc;
+            cG[c] = live ? (double)P.coefG[r][c] : (isgc ? 1.0 : 0.0);
+            cT[c] = live ? (double)P.coefT[r][c] : (isgc ? 1.0 : 0.0);
+        }
+
+        __syncthreads();                       // previous scanline completely done with the copies
+        for (int e = lane; e < 256; e += 64) { cp[0][wv][e] = 0.0; cp[1][wv][e] = 0.0; }
+        int pv_prev = 0;                       // where this lane scattered in the previous step
+        if (valid) P.S[((size_t)r * N + head + (long long)(len - 1) * nstep) * L + lam] = 0.0f;
+
+        float cur[D][NS], nxt[D][NS];
+        float ucur[D], unxt[D];
+        int pcur[D], pnxt[D], qcur[D], qnxt[D];
+        float wcur[D], wnxt[D];
+        auto prefetch = [&](float (&dst)[NS], float &udst, int &pdst, int &qdst, float &wdst, int tt) {
+            int n = len - 1 - tt;
+            n = n > 0 ? n : 0;
+            const long long i = head + (long long)n * nstep;
+#pragma unroll
+            for (int c = 0; c < NS; ++c) dst[c] = src[c][(size_t)i * L + lc];
+            udst = P.gunary[((size_t)i * L + lc) * umul];
+            pdst = pbase[(size_t)i * L + lc];
+            qdst = qbase[(size_t)i + vzero];
+            wdst = wbase[(size_t)(i * P.w_mul) + vzero];
+        };
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
+
+        double carry = 0.0;
+        int par = 0;
+        long long gw_node = -1;     // node whose edge-weight gradient parts sit in gwp[par ^ 1]
+
+        for (int t0 = 0; t0 < len; t0 += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], t0 + D + u);
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int tt = t0 + u;
+                const bool past = tt >= len;
+                const int n = past ? 0 : len - 1 - tt;
+                const bool update = !past && n > 0;
+                const long long i = head + (long long)n * nstep;
+                const long long j = i - nstep;
+
+                double g = carry;
+#pragma unroll
+                for (int c = 0; c < NS; ++c) g += cG[c] * (double)cur[u][c];
+                g = valid ? g : 0.0;
+                if (own_unary) {
+                    double accT = carry;
+#pragma unroll
+                    for (int c = 0; c < NS; ++c) accT += cT[c] * (double)cur[u][c];
+                    accT += unary_old ? (double)ucur[u] : 0.0;
+                    if (!past && valid) P.gunary[(size_t)i * L + lam] = (float)accT;
+                }
+                const int pv = pcur[u] < L ? pcur[u] : L - 1;
+                int qv = __builtin_amdgcn_readfirstlane(qcur[u]);
+                qv = qv < L ? qv : L - 1;
+
+                if (valid) __hip_atomic_fetch_add(&cp[par][wv][pv], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                const double part = mrf_wave_sum_f64(g);
+                if (lane == 0) psum[par][wv] = part;
+                if (lam == qv) pqs[par] = pv;
+                mrf_block_sync_lds();
+
+                // edge-weight gradient of the previous node: parts in wavefront order
+                if (P.gw && wv == 0 && lane == 0 && gw_node >= 0) {
+                    const double a = ((gwp[par ^ 1][0] + gwp[par ^ 1][1]) + gwp[par ^ 1][2]) + gwp[par ^ 1][3];
+                    __hip_atomic_fetch_add(&P.gw[(size_t)r * N + gw_node], (float)a, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                }
+                // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda); the target p(q) loses the sum
+                const double tot = ((psum[par][0] + psum[par][1]) + psum[par][2]) + psum[par][3];
+                const int pq = pqs[par];
+                double sv = 0.0;
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2)
+                    if (w2 < NWV) sv += cp[par][w2][lam];
+                if (lam == pq) sv -= tot;
+                const double gn = (lam == qv) ? g - tot : g;
+                if (update && valid) P.S[((size_t)r * N + j) * L + lam] = (float)sv;
+                carry = cscale * sv;
+                // own copy of the other set: its readers are past the barrier, clear what was touched
+                cp[par ^ 1][wv][pv_prev] = 0.0;
+                pv_prev = pv;
+
+                const double wgt = (double)wcur[u];
+                if (P.gw) {
+                    double acc = 0.0;
+                    if (valid) {
+                        float vv;
+                        if (VG) {
+                            vv = P.V[(size_t)pv * L + lam];
+                        } else {
+                            const int dist = pv > lam ? pv - lam : lam - pv;
+                            vv = vl[P.v_mode == 1 ? pv * L + lam : dist];
+                        }
+                        acc = gn * (double)vv;
+                    }
+                    acc = mrf_wave_sum_f64(acc);
+                    if (lane == 0) gwp[par][wv] = acc;
+                    gw_node = update ? i : -1;
+                }
+                if (gVs && update && valid)
+                    __hip_atomic_fetch_add(&gVs[(size_t)pv * L + lam], wgt * gn, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                par ^= 1;
+            }
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                qcur[u] = qnxt[u];
+                wcur[u] = wnxt[u];
+                ucur[u] = unxt[u];
+                pcur[u] = pnxt[u];
+#pragma unroll
+                for (int c = 0; c < NS; ++c) cur[u][c] = nxt[u][c];
+            }
+        }
+        if (P.gw) {
+            __syncthreads();
+            if (wv == 0 && lane == 0 && gw_node >= 0) {
+                const double a = ((gwp[par ^ 1][0] + gwp[par ^ 1][1]) + gwp[par ^ 1][2]) + gwp[par ^ 1][3];
+                __hip_atomic_fetch_add(&P.gw[(size_t)r * N + gw_node], (float)a, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
 // ISGMR, after the sweeps of iteration k: grad theta_i += sum_r s^r_i, and the gradient of
 // m^d (= m-hat^d of iteration k-1) is sum over r not in {d, d-} of s^r_i.
 struct MrfCombineParams {

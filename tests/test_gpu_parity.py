@@ -186,6 +186,31 @@ def test_window_path_is_exact(oracle, case):
         np.testing.assert_array_equal(getattr(g2, name), getattr(d, name), err_msg=name)
 
 
+@pytest.mark.parametrize("case", [
+    (61, "trwp", 1, 6, 7, 200, DIRS4, 3, False, True),
+    (62, "isgmr", 1, 5, 6, 256, DIRS8, 2, True, True),
+    (63, "trwp", 2, 4, 5, 130, DIRS8, 2, False, False),
+    (64, "isgmr", 1, 7, 5, 192, DIRS4, 2, False, True),
+], ids=lambda c: "seed%d" % c[0])
+def test_multi_wavefront_backward_layout(oracle, case):
+    """Backward sweeps with one wavefront per 64 labels (chosen for launches with few scanlines
+    and many labels) against the oracle, and identical to the one-wavefront layout."""
+    import paper_1910_10892_amd as mrf
+    print("case split backward", case[:8], flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv, pe = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=pe,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    try:
+        assert mrf.mrf_tune(2, 1) == 0
+        a = full_check(oracle, pr)
+        assert mrf.mrf_tune(2, 2) == 0
+        b = full_check(oracle, pr)
+    finally:
+        mrf.mrf_tune(2, 0)
+    for name in ("grad_unary", "grad_edge_weight", "grad_pairwise"):
+        np.testing.assert_allclose(getattr(a, name), getattr(b, name), rtol=1e-5, atol=1e-4, err_msg=name)
+
+
 def test_optional_outputs_may_be_null(oracle):
     from gpu_harness import GpuProblem
     import torch
