@@ -76,6 +76,7 @@ size_t gradv_bytes(const mrf_problem *pr)
 int g_tune_mch = 0;
 int g_tune_no_window = 0;
 int g_tune_split = 0;      // 0 auto, 1 never, 2 whenever L > 64
+int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 inline void mark(hipEvent_t ev, hipStream_t st)
@@ -157,8 +158,33 @@ int window_width(const mrf_problem *pr)
     return ti <= 2 ? 2 : (ti <= 8 ? 8 : 16);
 }
 
+template <int SEG>
+hipError_t launch_packed(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
+{
+    const unsigned blocks = (unsigned)((scanlines + 64 / SEG - 1) / (64 / SEG));
+#define MRF_P(rm, d) \
+    if (rmax == rm) { \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, rm, d, true>), dim3(blocks), dim3(64), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, rm, d, false>), dim3(blocks), dim3(64), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_P(4, 4) MRF_P(8, 2) MRF_P(16, 1)
+#undef MRF_P
+    return hipErrorInvalidValue;
+}
+
 hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
+    // few labels: several scanlines per wavefront (dense evaluation), unless the launch is so
+    // small that it is latency bound and a truncated model can use the shorter window step
+    if (P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
+        int ms = 0;
+        for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
+            if (P.n_src[r] > ms) ms = P.n_src[r];
+        const int rmax = (ms + 1 <= 4) ? 4 : ((ms + 1 <= 8) ? 8 : 16);
+        P.NW = 1;
+        return P.g.L <= 16 ? launch_packed<16>(P, algo, rmax, blocks, st) : launch_packed<32>(P, algo, rmax, blocks, st);
+    }
     if (tw > 0) {
         const int LPw = (P.g.L + 63) / 64;
         int ms = 0;
@@ -612,6 +638,7 @@ int mrf_tune(int knob, int value)
     if (knob == 0) { g_tune_mch = value; return MRF_OK; }
     if (knob == 1) { g_tune_no_window = value; return MRF_OK; }
     if (knob == 2) { g_tune_split = value; return MRF_OK; }
+    if (knob == 3) { g_tune_pack = value; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

@@ -801,3 +801,186 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
         if (lane == 0) P.q[(size_t)r * N + qnode] = (uint8_t)qv;
     }
 }
+
+// ---- dense sweep for few labels: several scanlines per wavefront ----------------------------
+//
+// For L <= 32 a wavefront with one scanline leaves most lanes idle.  Here a wavefront is cut
+// into 64/SEG segments of SEG lanes (SEG = 16 or 32 >= L); each segment walks its own
+// scanline, possibly of another direction and length than its neighbours, so everything
+// that is wave-uniform in the other kernels (node addresses, weight, source flags) is
+// per-lane here.  V(.,lambda) sits in SEG registers per lane, h is exchanged through a
+// per-segment LDS row, the minimum over labels is a DPP row reduction (plus one swizzle
+// for 32-lane segments) and q comes from the segment's slice of a ballot.
+template <int SEG>
+__device__ inline float mrf_segment_min(float v)
+{
+    v = mrf_min(v, mrf_dpp_f32<0xB1>(v));
+    v = mrf_min(v, mrf_dpp_f32<0x4E>(v));
+    v = mrf_min(v, mrf_dpp_f32<0x141>(v));
+    v = mrf_min(v, mrf_dpp_f32<0x140>(v));
+    if (SEG == 32)   // partner row inside the 32-lane group: swizzle, xor lane id with 16
+        v = mrf_min(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));
+    return v;
+}
+
+template <int SEG, int RMAX, int D, bool TRWP>
+__global__ void __launch_bounds__(64)
+mrf_fwd_sweep_packed(const MrfFwdParams P)
+{
+    constexpr int NSEG = 64 / SEG;
+    constexpr int SEGP = SEG + 4;                 // row stride: keeps the segments on different banks
+    __shared__ __align__(16) float hseg[NSEG][SEGP];
+    const int L = P.g.L;
+    const int lane = threadIdx.x;
+    const int seg = lane / SEG, lam = lane % SEG;
+    const bool valid = lam < L;
+    const int lamc = valid ? lam : 0;
+    const long long N = P.g.N;
+    const long long total = P.blk_begin[P.r_count];
+    const long long sl = (long long)blockIdx.x * NSEG + seg;
+    const bool act_seg = sl < total;
+
+    // per-lane description of the segment's scanline
+    int r = P.r_first, nsc = 1, dh = 0, dw = 1, n_pre = 0, n_src = 0, rm_slot = -1;
+    long long local = 0;
+    float rho = 1.0f;
+    int sdir[RMAX];
+#pragma unroll
+    for (int c = 0; c < RMAX; ++c) sdir[c] = 0;
+    for (int ri = 0; ri < P.r_count; ++ri) {
+        const int rr = P.r_first + ri;
+        const bool mine = act_seg && sl >= P.blk_begin[ri] && sl < P.blk_begin[ri + 1];
+        if (mine) {
+            r = rr; local = sl - P.blk_begin[ri]; nsc = P.g.nscan[rr]; dh = P.g.dh[rr]; dw = P.g.dw[rr];
+            rho = P.rho[rr]; n_pre = P.n_pre[rr]; n_src = P.n_src[rr]; rm_slot = P.rm_slot[rr];
+#pragma unroll
+            for (int c = 0; c + 1 < RMAX; ++c) sdir[c] = P.src_dir[rr][c];
+        }
+    }
+    int y0 = 0, x0 = 0, len = 1;
+    long long head = 0;
+    if (act_seg) {
+        const int b = (int)(local / nsc);
+        const long long t = local - (long long)b * nsc;
+        mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+        head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    }
+    const long long nstep = (long long)dh * P.g.W + dw;
+
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)sdir[c - 1] * N * L : P.unary;
+        use[c] = (c <= n_src) ? 1.0f : 0.0f;
+        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+
+    float Vr[SEG];
+#pragma unroll
+    for (int mu = 0; mu < SEG; ++mu) Vr[mu] = (mu < L && valid) ? P.V[(size_t)mu * L + lam] : 0.0f;
+    hseg[seg][lam] = INFINITY;                    // entries mu >= L stay +inf: they never win
+    if (lam < 4) hseg[seg][SEG + lam] = INFINITY;
+    __syncthreads();
+
+    if (act_seg && valid) {
+        P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
+        P.p[((size_t)r * N + head) * L + lam] = 0;
+        if (lam == 0) P.q[(size_t)r * N + head] = 0;
+    }
+
+    // longest scanline of the wavefront bounds the loop
+    int maxlen = 1;
+#pragma unroll
+    for (int sg = 0; sg < NSEG; ++sg) {
+        const int l2 = __builtin_amdgcn_readlane(len, sg * SEG);
+        maxlen = l2 > maxlen ? l2 : maxlen;
+    }
+
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len >= 2 ? len - 2 : 0;
+    float cur[D][RMAX], nxt[D][RMAX];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX], float &wdst, int nj) {
+        nj = nj < lastsrc ? nj : lastsrc;          // past the end: reload the last one, never used
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][(size_t)j * L + lamc];
+        const long long iw = len >= 2 ? j + nstep : j;
+        wdst = wbase[(size_t)(iw * P.w_mul)];
+    };
+#pragma unroll
+    for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+
+    float carry = 0.0f;
+    for (int n0 = 1; n0 < maxlen; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int nn = n0 + u;
+            const bool act = act_seg && nn < len;       // this segment still has a node to update
+            const long long i = head + (long long)nn * nstep;
+            const float wgt = wcur[u];
+
+            float v = cur[u][0];
+            if (TRWP) {
+                float mrm = 0.0f;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) {
+                    v = __builtin_fmaf(carry_at[c], carry, v);
+                    v = __builtin_fmaf(use[c], cur[u][c], v);
+                    mrm = __builtin_fmaf(is_rm[c], cur[u][c], mrm);
+                }
+                v = __builtin_fmaf(carry_at[RMAX], carry, v);
+                v = rho * v;
+                v = v - mrm;
+            } else {
+                v = v + carry;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+            }
+            if (valid) hseg[seg][lam] = v;
+            mrf_wave_lds_fence();
+
+            float best = INFINITY;
+            int bidx = 0;
+#pragma unroll
+            for (int m4 = 0; m4 < SEG; m4 += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(&hseg[seg][m4]);
+                const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float dlt = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
+                    if (dlt < best) { best = dlt; bidx = m4 + c; }
+                }
+            }
+            mrf_wave_lds_fence();
+
+            const float tv = valid ? best : INFINITY;
+            const float tq = mrf_segment_min<SEG>(tv);
+            const unsigned long long bal = __ballot(tv == tq);
+            const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
+            const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
+            const int qidx = __ffs((int)mine) - 1;
+            carry = valid ? tv - tq : 0.0f;
+
+            if (act && valid) {
+                P.m_out[((size_t)r * N + i) * L + lam] = carry;
+                P.p[((size_t)r * N + i) * L + lam] = (uint8_t)bidx;
+                if (lam == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c) cur[u][c] = nxt[u][c];
+        }
+    }
+}

@@ -211,6 +211,35 @@ def test_multi_wavefront_backward_layout(oracle, case):
         np.testing.assert_allclose(getattr(a, name), getattr(b, name), rtol=1e-5, atol=1e-4, err_msg=name)
 
 
+PACK_CASES = [
+    (71, "isgmr", 2, 9, 11, 21, DIRS4, 3, False, True),
+    (72, "trwp", 1, 7, 13, 16, DIRS8, 2, True, True),
+    (73, "isgmr", 1, 6, 10, 5, DIRS16, 2, False, True),     # 16 directions: scanlines of very different length
+    (74, "trwp", 3, 5, 6, 32, DIRS4, 2, False, False),
+    (75, "isgmr", 1, 8, 3, 17, DIRS8, 2, True, True),
+    (76, "trwp", 1, 3, 9, 1, DIRS4, 2, False, True),
+]
+
+
+@pytest.mark.parametrize("case", PACK_CASES, ids=lambda c: "seed%d" % c[0])
+def test_packed_scanlines_layout(oracle, case):
+    """For L <= 32 several scanlines share a wavefront; results must not depend on it."""
+    import paper_1910_10892_amd as mrf
+    print("case packed", case[:8], flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv, pe = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=pe,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    try:
+        assert mrf.mrf_tune(3, 1) == 0
+        a = full_check(oracle, pr)
+        assert mrf.mrf_tune(3, 2) == 0
+        b = full_check(oracle, pr)
+    finally:
+        mrf.mrf_tune(3, 0)
+    for name in ("p", "q", "labels", "cost", "messages"):
+        np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
+
+
 def test_optional_outputs_may_be_null(oracle):
     from gpu_harness import GpuProblem
     import torch
