@@ -359,6 +359,22 @@ hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds,
     return hipGetLastError();
 }
 
+template <int SEG>
+hipError_t launch_bwd_packed(const MrfBwdParams &P, int ns, hipStream_t st)
+{
+    constexpr int NSEG = 64 / SEG;
+    const int L = P.g.L;
+    long long blocks = (P.total_scanlines + NSEG - 1) / NSEG;
+    if (P.gV && blocks > grad_slots(L) / NSEG) blocks = grad_slots(L) / NSEG;
+    const size_t lds = sizeof(double) * (64 + (P.gV ? (size_t)NSEG * L * L : 0)) + sizeof(float) * (size_t)L * L;
+    const dim3 grid((unsigned)blocks), block(64);
+    if (ns == 1) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 1, 4>), grid, block, lds, st, P);
+    else if (ns == 4) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 4, 4>), grid, block, lds, st, P);
+    else if (ns == 8) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 8, 2>), grid, block, lds, st, P);
+    else hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 16, 1>), grid, block, lds, st, P);
+    return hipGetLastError();
+}
+
 hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
 {
     const int L = P.g.L;
@@ -381,6 +397,9 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
         if (P.n_src[r] + (P.use_gc ? 1 : 0) > need) need = P.n_src[r] + (P.use_gc ? 1 : 0);
     const int ns = need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 8 ? 8 : 16));
+    // few labels: several scanlines per wavefront
+    if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256))
+        return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     // few scanlines and many labels: one wavefront per 64 labels
     const bool split = LP >= 3 && g_tune_split != 1 && ns <= 8 &&
                        (g_tune_split == 2 || P.total_scanlines * LP <= 4096);

@@ -518,6 +518,191 @@ __global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
     }
 }
 
+// ---- index replay for few labels: several scanlines per wavefront ---------------------------
+//
+// Counterpart of mrf_fwd_sweep_packed: the wavefront is cut into 64/SEG segments of SEG >= L
+// lanes, each replaying its own scanline (any direction, any length).  Label sums are DPP
+// row sums (plus one swizzle for 32-lane segments), the scatter vector and the V-gradient
+// accumulator are per segment in LDS.
+template <int SEG>
+__device__ inline double mrf_segment_sum_f64(double v)
+{
+    v += mrf_dpp_f64<0xB1>(v);
+    v += mrf_dpp_f64<0x4E>(v);
+    v += mrf_dpp_f64<0x141>(v);
+    v += mrf_dpp_f64<0x140>(v);
+    if (SEG == 32) {
+        const long long b = __builtin_bit_cast(long long, v);
+        const int lo = __builtin_amdgcn_ds_swizzle((int)(b & 0xffffffffLL), 0x401F);
+        const int hi = __builtin_amdgcn_ds_swizzle((int)(b >> 32), 0x401F);
+        v += __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+    }
+    return v;
+}
+
+template <int SEG, int NS, int D>
+__global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
+{
+    constexpr int NSEG = 64 / SEG;
+    extern __shared__ __align__(16) unsigned char mrf_bsmem[];
+    const int L = P.g.L;
+    const int lane = threadIdx.x;
+    const int seg = lane / SEG, lam = lane % SEG;
+    const bool valid = lam < L;
+    const int lc = valid ? lam : 0;
+    const long long N = P.g.N;
+    double *sbuf = reinterpret_cast<double *>(mrf_bsmem) + seg * SEG;                       // [NSEG][SEG]
+    double *gvl = reinterpret_cast<double *>(mrf_bsmem) + NSEG * SEG + (P.gV ? seg * L * L : 0);  // [NSEG][L*L]
+    float *vl = reinterpret_cast<float *>(reinterpret_cast<double *>(mrf_bsmem) + NSEG * SEG + (P.gV ? NSEG * L * L : 0));
+    double *gVs = P.gV ? P.gV + ((size_t)blockIdx.x * NSEG + seg) * L * L : nullptr;
+
+    for (int e = lane; e < L * L; e += 64) vl[e] = P.V[e];
+    if (gVs)
+        for (int e = lam; e < L * L; e += SEG) gvl[e] = 0.0;
+    sbuf[lam] = 0.0;
+    __syncthreads();
+
+    const long long npacks = (P.total_scanlines + NSEG - 1) / NSEG;
+    for (long long pk = blockIdx.x; pk < npacks; pk += gridDim.x) {
+        const long long sl = pk * NSEG + seg;
+        const bool act_seg = sl < P.total_scanlines;
+
+        int r = P.r_first, nsc = 1, dh = 0, dw = 1, nsrc = 0;
+        long long local = 0;
+        float cscale_f = 1.0f;
+        int sdir[NS];
+        float cGf[NS], cTf[NS];
+#pragma unroll
+        for (int c = 0; c < NS; ++c) { sdir[c] = 0; cGf[c] = 0.0f; cTf[c] = 0.0f; }
+        for (int ri = 0; ri < P.r_count; ++ri) {
+            const int rr = P.r_first + ri;
+            const bool mine = act_seg && sl >= P.blk_begin[ri] && sl < P.blk_begin[ri + 1];
+            if (mine) {
+                r = rr; local = sl - P.blk_begin[ri]; nsc = P.g.nscan[rr]; dh = P.g.dh[rr]; dw = P.g.dw[rr];
+                cscale_f = P.carry_scale[rr]; nsrc = P.n_src[rr];
+#pragma unroll
+                for (int c = 0; c < NS; ++c) { sdir[c] = P.src_dir[rr][c]; cGf[c] = P.coefG[rr][c]; cTf[c] = P.coefT[rr][c]; }
+            }
+        }
+        int y0 = 0, x0 = 0, len = 1;
+        long long head = 0;
+        if (act_seg) {
+            const int b = (int)(local / nsc);
+            const long long t = local - (long long)b * nsc;
+            mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+            head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+        }
+        const long long nstep = (long long)dh * P.g.W + dw;
+        const double cscale = (double)cscale_f;
+        const bool own_unary = act_seg && (r == P.unary_dir);
+        const bool unary_old = own_unary && !P.unary_init;
+        const size_t umul = unary_old ? 1 : 0;
+        const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+        const uint8_t *pbase = P.p + (size_t)r * N * L;
+        const uint8_t *qbase = P.q + (size_t)r * N;
+
+        const float *src[NS];
+        double cG[NS], cT[NS];
+#pragma unroll
+        for (int c = 0; c < NS; ++c) {
+            const bool live = c < nsrc;
+            const bool isgc = (c == nsrc) && P.use_gc;
+            src[c] = live ? P.src_base + (size_t)sdir[c] * P.src_stride : P.gc;
+            cG[c] = live ? (double)cGf[c] : (isgc ? 1.0 : 0.0);
+            cT[c] = live ? (double)cTf[c] : (isgc ? 1.0 : 0.0);
+        }
+        if (act_seg && valid) P.S[((size_t)r * N + head + (long long)(len - 1) * nstep) * L + lam] = 0.0f;
+
+        int maxlen = 1;
+#pragma unroll
+        for (int sg = 0; sg < NSEG; ++sg) {
+            const int l2 = __builtin_amdgcn_readlane(len, sg * SEG);
+            maxlen = l2 > maxlen ? l2 : maxlen;
+        }
+
+        float cur[D][NS], nxt[D][NS];
+        float ucur[D], unxt[D];
+        int pcur[D], pnxt[D], qcur[D], qnxt[D];
+        float wcur[D], wnxt[D];
+        auto prefetch = [&](float (&dst)[NS], float &udst, int &pdst, int &qdst, float &wdst, int tt) {
+            int n = len - 1 - tt;
+            n = n > 0 ? n : 0;
+            const long long i = head + (long long)n * nstep;
+#pragma unroll
+            for (int c = 0; c < NS; ++c) dst[c] = src[c][(size_t)i * L + lc];
+            udst = P.gunary[((size_t)i * L + lc) * umul];
+            pdst = pbase[(size_t)i * L + lc];
+            qdst = qbase[(size_t)i];
+            wdst = wbase[(size_t)(i * P.w_mul)];
+        };
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
+
+        double carry = 0.0;
+        for (int t0 = 0; t0 < maxlen; t0 += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], t0 + D + u);
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int tt = t0 + u;
+                const bool past = !act_seg || tt >= len;
+                const int n = past ? 0 : len - 1 - tt;
+                const bool update = !past && n > 0;
+                const long long i = head + (long long)n * nstep;
+                const long long j = i - nstep;
+
+                double g = carry;
+#pragma unroll
+                for (int c = 0; c < NS; ++c) g += cG[c] * (double)cur[u][c];
+                g = valid ? g : 0.0;
+                {
+                    double accT = carry;
+#pragma unroll
+                    for (int c = 0; c < NS; ++c) accT += cT[c] * (double)cur[u][c];
+                    accT += unary_old ? (double)ucur[u] : 0.0;
+                    if (own_unary && !past && valid) P.gunary[(size_t)i * L + lam] = (float)accT;
+                }
+                const int pv = pcur[u] < L ? pcur[u] : L - 1;
+                const int qv = qcur[u] < L ? qcur[u] : L - 1;
+                // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
+                const double tot = mrf_segment_sum_f64<SEG>(g);
+                if (lam == qv) g = g - tot;
+
+                if (valid) __hip_atomic_fetch_add(&sbuf[pv], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                mrf_wave_lds_fence();
+                const double sv = sbuf[lam];
+                mrf_wave_lds_fence();
+                sbuf[lam] = 0.0;
+                if (update && valid) P.S[((size_t)r * N + j) * L + lam] = (float)sv;
+                carry = cscale * sv;
+
+                const double wgt = (double)wcur[u];
+                if (P.gw) {
+                    double acc = valid ? g * (double)vl[pv * L + lc] : 0.0;
+                    acc = mrf_segment_sum_f64<SEG>(acc);
+                    if (update && lam == 0)
+                        __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (gVs && update && valid) gvl[pv * L + lam] += wgt * g;
+            }
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                qcur[u] = qnxt[u];
+                wcur[u] = wnxt[u];
+                ucur[u] = unxt[u];
+                pcur[u] = pnxt[u];
+#pragma unroll
+                for (int c = 0; c < NS; ++c) cur[u][c] = nxt[u][c];
+            }
+        }
+    }
+    if (gVs) {
+        mrf_wave_lds_fence();
+        for (int e = lam; e < L * L; e += SEG) gVs[e] += gvl[e];
+    }
+}
+
 // ISGMR, after the sweeps of iteration k: grad theta_i += sum_r s^r_i, and the gradient of
 // m^d (= m-hat^d of iteration k-1) is sum over r not in {d, d-} of s^r_i.
 struct MrfCombineParams {
