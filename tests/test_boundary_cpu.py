@@ -72,6 +72,20 @@ def test_validation_codes_without_gpu():
         assert mrf.mrf_strerror(code) != "unknown status"
 
 
+def test_forward_kernel_choice_is_host_arithmetic():
+    """Truncation distance -> window width (0 = dense sweep); no GPU involved."""
+    lib = mrf.load_library()
+    W = lambda **kw: lib.mrf_forward_window(ctypes.byref(_cprob(**kw)), 0)
+    assert W(L=16, pairwise_kind=1, trunc=4.0) == 8
+    assert W(L=96, pairwise_kind=1, trunc=8.0) == 8
+    assert W(L=192, pairwise_kind=1, trunc=2.0) == 2
+    assert W(L=256, pairwise_kind=2, trunc=200.0) == 16      # ceil(sqrt(200)) = 15
+    assert W(L=21, pairwise_kind=0) == 0
+    assert W(L=12, pairwise_kind=1, trunc=20.0) == 0          # never truncates inside the label range
+    assert W(L=200, pairwise_kind=1, trunc=40.0) == 0         # window wider than the kernel supports
+    assert W(L=0, pairwise_kind=1, trunc=4.0) == -3
+
+
 def test_entry_points_reject_before_any_gpu_work():
     """NULL outputs / short workspaces are reported before a kernel launch is attempted, so
     this runs on a machine without a GPU."""

@@ -287,6 +287,21 @@ def test_workspace_too_small_is_an_error_not_a_fault():
     assert ei.value.status == -6
 
 
+@pytest.mark.parametrize("index,crop,algo", [
+    (2, None, "isgmr"),            # stereo shape, all four directions in one launch
+    (3, (96, 312), "isgmr"),       # driving-stereo recipe, 1/16 of the area, L = 192, 8 directions
+    (4, (64, 64), "trwp"),         # denoising recipe, 1/16 of the area, L = 256
+    (5, None, "isgmr"),            # segmentation shape at full size (batch 4, 512 x 512, L = 21)
+    (5, None, "trwp"),
+])
+def test_large_configs(oracle, index, crop, algo):
+    """The other benchmark shapes at full size where the oracle finishes in seconds on all host
+    threads, else on a centred fraction of the grid with every other parameter unchanged."""
+    print("case large config", index, crop, algo, flush=True)
+    pr = make_config(index, crop=crop, algo=algo)
+    full_check(oracle, pr, threads=True)
+
+
 def test_full_size_stereo_config_trwp(oracle):
     """The configuration the bench times (TRWP, 256x512, L = 96, K = 5), whole grid, in the
     launch configuration the bench uses; oracle forward on all host threads (bit-identical
