@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 1 GiB device-to-device copy (calibration of HBM byte counters)")
     ap.add_argument("--tune-mch", type=int, default=0, help="experiment: source labels per wavefront (0 = heuristic)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
+                    help="experiment: set a kernel-choice knob of mrf_tune (results never depend on them)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -92,6 +94,9 @@ def main():
     mrf.load_library()      # no fallback: raises if libmrfmp.so is missing
     if args.tune_mch:
         mrf.mrf_tune(0, args.tune_mch)
+    for kv in args.tune:
+        knob, value = kv.split("=")
+        mrf.mrf_tune(int(knob), int(value))
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     pr = make_config(args.config, algo=args.algo)
     g = GpuProblem(pr, want_messages=False)

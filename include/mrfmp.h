@@ -159,6 +159,9 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 2: window sweep layout: 0 = by launch size, 1 = one wavefront per scanline,
  *           2 = one wavefront per 64 labels whenever L > 64
  *   knob 3: several scanlines per wavefront for L <= 32: 0 = by launch shape, 1 = never, 2 = always
+ *   knob 4: window sweep with separate value and index wavefronts: 0 = by launch size, 1 = never,
+ *           2 = whenever the window sweep applies (knob 2 = 2 takes precedence for L > 64)
+ *   knob 5: index wavefronts per scanline in that sweep: 0 = by launch size, 1, 2
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

@@ -77,6 +77,8 @@ int g_tune_mch = 0;
 int g_tune_no_window = 0;
 int g_tune_split = 0;      // 0 auto, 1 never, 2 whenever L > 64
 int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
+int g_tune_duo = 0;        // 0 auto, 1 never, 2 whenever the window applies
+int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 inline void mark(hipEvent_t ev, hipStream_t st)
@@ -122,6 +124,20 @@ hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long bloc
     if (tw == twv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, true, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
         else hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, false, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2) MRF_W(8) MRF_W(16)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
+template <int LP, int RMAX, int D, int NI>
+hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
+{
+#define MRF_W(twv) \
+    if (tw == twv) { \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, true, twv, NI>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, false, twv, NI>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
         return hipGetLastError(); \
     }
     MRF_W(2) MRF_W(8) MRF_W(16)
@@ -192,11 +208,28 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
             if (P.n_src[r] > ms) ms = P.n_src[r];
         // few scanlines in the launch and many labels: spread each node step over one
         // wavefront per 64 labels
-        const bool split = LPw > 1 && g_tune_split != 1 && (g_tune_split == 2 || (LPw >= 3 && blocks * LPw <= 4096));
+        // (wide windows over many labels only: otherwise the value/index pair below is faster)
+        const bool split = LPw > 1 && g_tune_split != 1 &&
+                           (g_tune_split == 2 || (LPw >= 3 && tw >= 8 && blocks * LPw <= 4096));
         if (ms + 1 <= 8 && split) {
             P.NW = LPw;
             if (ms + 1 <= 4) return launch_window_split<4, 4>(P, algo, tw, blocks, st);
             return launch_window_split<8, 2>(P, algo, tw, blocks, st);
+        }
+        // few scanlines: a second wavefront per scanline takes the argmin tables and the
+        // stores off the dependency chain
+        const bool duo = g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= 4096);
+        if (ms + 1 <= 8 && duo) {
+            P.NW = 1;
+            // two index wavefronts while the launch is far from filling the machine
+            const int ni = g_tune_duo_ni ? g_tune_duo_ni : (blocks <= 1536 ? 2 : 1);
+#define MRF_WCASE(lp) \
+            if (LPw == lp && ms + 1 <= 4 && ni == 2) return launch_window_duo<lp, 4, (lp <= 2 ? 4 : 2), 2>(P, algo, tw, blocks, st); \
+            if (LPw == lp && ms + 1 <= 4) return launch_window_duo<lp, 4, (lp <= 2 ? 4 : 2), 1>(P, algo, tw, blocks, st); \
+            if (LPw == lp && ni == 2) return launch_window_duo<lp, 8, (lp <= 2 ? 2 : 1), 2>(P, algo, tw, blocks, st); \
+            if (LPw == lp) return launch_window_duo<lp, 8, (lp <= 2 ? 2 : 1), 1>(P, algo, tw, blocks, st);
+            MRF_WCASE(1) MRF_WCASE(2) MRF_WCASE(3) MRF_WCASE(4)
+#undef MRF_WCASE
         }
         if (ms + 1 <= 8) {
             P.NW = 1;
@@ -402,7 +435,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     // few scanlines and many labels: one wavefront per 64 labels
     const bool split = LP >= 3 && g_tune_split != 1 && ns <= 8 &&
-                       (g_tune_split == 2 || P.total_scanlines * LP <= 4096);
+                       (g_tune_split == 2 || (P.total_scanlines < 1024 && P.total_scanlines * LP <= 4096));
     if (split) {
         long long sblocks = P.total_scanlines;
         if (P.gV && sblocks > grad_slots(L)) sblocks = grad_slots(L);
@@ -658,6 +691,8 @@ int mrf_tune(int knob, int value)
     if (knob == 1) { g_tune_no_window = value; return MRF_OK; }
     if (knob == 2) { g_tune_split = value; return MRF_OK; }
     if (knob == 3) { g_tune_pack = value; return MRF_OK; }
+    if (knob == 4) { g_tune_duo = value; return MRF_OK; }
+    if (knob == 5) { g_tune_duo_ni = (value == 1 || value == 2) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

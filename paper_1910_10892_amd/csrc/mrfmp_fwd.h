@@ -573,6 +573,346 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
     }
 }
 
+// ---- window sweep with an index wavefront ----------------------------------------------------
+//
+// Same arithmetic as mrf_fwd_sweep_window, for launches with few scanlines.  Only the VALUES
+// of the new message are on the node-to-node dependency chain; the argmin tables p and q and
+// every store are not.  Two wavefronts share a scanline: the value wavefront forms h, its
+// minimum and the new message and passes h, hmin and the weight through a ring in LDS; the
+// index wavefronts follow a little behind, repeat the window evaluation with the index
+// bookkeeping (Alg. 1/2: p, q) and store m, p and q.  Both sides evaluate the same
+// expressions on the same h, so what is stored equals what the value wavefront carries.
+// The index work of a node does not depend on other nodes, so NI index wavefronts take the
+// nodes of a scanline in turn (it is somewhat more work per node than the value chain).
+// Nobody meets at a barrier: the producer only waits when the ring is full, a consumer when
+// its next node is not there yet, and every counter only grows, so all waits end.
+template <int LP, int RMAX, int D, bool TRWP, int TW, int NI>
+__global__ void __launch_bounds__(64 * (1 + NI))
+mrf_fwd_sweep_window_duo(const MrfFwdParams P)
+{
+    constexpr int HB = 64 * LP + 2 * TW;          // h with TW entries of padding on both sides
+    constexpr int NR = 8;                         // ring slots (a power of two, >= D)
+    static_assert(NR >= D && (NR & (NR - 1)) == 0 && NI <= 4, "ring depth");
+    constexpr int NT = 64 * (1 + NI);
+    __shared__ float ring[NR][HB];
+    __shared__ float ringw[NR], ringhm[NR];
+    __shared__ float ftab[TW + 1];
+    __shared__ int produced;                      // last step published
+    __shared__ __align__(16) int consumed[4];     // per index wavefront: last step finished
+    const int L = P.g.L;
+    const int lane = threadIdx.x & 63;
+    const bool index_wave = threadIdx.x >= 64;
+
+    const long long blk = blockIdx.x;
+    int ri = 0;
+    while (ri + 1 < P.r_count && blk >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = blk - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long N = P.g.N;
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const float vz = mrf_opaque_zero_f();     // keeps uniform constants in vector registers
+
+    // f(d) = V(0, d) for d < TW, fT = V(0, L-1) (the promise makes every farther entry equal it)
+    float f[TW];
+#pragma unroll
+    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1] + vz;
+    const float fT = P.V[L - 1] + vz;
+    const bool f0zero = (P.V[0] == 0.0f);
+    if ((int)threadIdx.x <= TW) ftab[threadIdx.x] = (int)threadIdx.x < TW ? P.V[(int)threadIdx.x < L ? threadIdx.x : L - 1] : fT;
+    // padding and the entries of labels >= L are never written again: they never win a strict '<'
+    for (int i = threadIdx.x; i < NR * HB; i += NT) (&ring[0][0])[i] = INFINITY;
+    if (threadIdx.x == 0) produced = 0;
+    // index wavefront j takes steps 1 + j, 1 + j + NI, ...; "finished" starts one turn before
+    if (threadIdx.x < 4) consumed[threadIdx.x] = (int)threadIdx.x + 1 - NI;
+    __syncthreads();
+
+    if (index_wave) {
+        // ---- p, q and all stores -----------------------------------------------------------
+        const int jw = (int)(threadIdx.x >> 6) - 1;
+        if (jw == 0) {
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const int lam = lane + 64 * s;
+                if (lam < L) {
+                    P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
+                    P.p[((size_t)r * N + head) * L + lam] = 0;
+                }
+            }
+            if (lane == 0) P.q[(size_t)r * N + head] = 0;
+        }
+
+        int seen = 0;
+        for (int n = 1 + jw; n < len; n += NI) {
+            while (seen < n) {
+                seen = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (seen < n) __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            const int slot = n & (NR - 1);
+            const float *hbuf = &ring[slot][TW];
+            const float wgt = ringw[slot];
+            const float hmin = ringhm[slot];
+            const long long i = head + (long long)n * nstep;
+
+            float tv[LP];
+            int tp[LP];
+            float tq;
+            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
+                int mug = 0;
+                bool found = false;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    const float gfar = lam < L ? __builtin_fmaf(wgt, fT, hbuf[lam]) : INFINITY;
+                    const unsigned long long bal = __ballot(gfar == gmin);
+                    if (!found && bal != 0ull) { found = true; mug = 64 * s + __ffsll((long long)bal) - 1; }
+                }
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float dl[2 * TW - 1];
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o) {
+                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                        dl[o] = __builtin_fmaf(wgt, f[dist], hbuf[lam + o - (TW - 1)]);
+                    }
+                    float W = dl[0];
+#pragma unroll
+                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
+                    int po = 2 * TW - 2;
+#pragma unroll
+                    for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
+                    const int pW = lam + po - (TW - 1);
+                    const bool wlt = W < gmin, wgt_ = W > gmin;
+                    tv[s] = (lam < L) ? (wlt ? W : gmin) : INFINITY;
+                    const int tie = pW < mug ? pW : mug;
+                    tp[s] = wlt ? pW : (wgt_ ? mug : tie);
+                }
+                if (f0zero) {
+                    tq = hmin;
+                } else {
+                    float mn = INFINITY;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                    tq = mrf_wave_min(mn);
+                }
+            } else {
+                // negative weight: the ordering argument does not hold, evaluate every mu
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float best = INFINITY;
+                    int bi = 0;
+                    for (int mu = 0; mu < L; ++mu) {
+                        int dist = mu > lam ? mu - lam : lam - mu;
+                        dist = dist < TW ? dist : TW;
+                        const float dlt = __builtin_fmaf(wgt, ftab[dist], hbuf[mu]);
+                        if (dlt < best) { best = dlt; bi = mu; }
+                    }
+                    tv[s] = (lam < L) ? best : INFINITY;
+                    tp[s] = bi;
+                }
+                float mn = INFINITY;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                tq = mrf_wave_min(mn);
+            }
+            // this slot has been read: hand it back
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            if (lane == 0) __hip_atomic_store(&consumed[jw], n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+
+            int qidx = -1;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const unsigned long long bal = __ballot(tv[s] == tq);
+                if (qidx < 0 && bal != 0ull) qidx = 64 * s + __ffsll((long long)bal) - 1;
+            }
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const int lam = lane + 64 * s;
+                if (lam < L) {
+                    P.m_out[((size_t)r * N + i) * L + lam] = tv[s] - tq;
+                    P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
+                }
+            }
+            if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+        }
+        return;
+    }
+
+    // ---- values: the dependency chain ------------------------------------------------------
+    const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
+        is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = ((c == n_pre + 1) ? 1.0f : 0.0f) + vz;
+
+    const int vzero = mrf_opaque_zero();
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len - 2;
+    float cur[D][RMAX][LP], nxt[D][RMAX][LP];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, int nj) {
+        nj = nj < lastsrc ? nj : lastsrc;
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c)
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                const int lam = lane + 64 * s;
+                dst[c][s] = src[c][(size_t)j * L + (lam < L ? lam : 0)];
+            }
+        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+    };
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
+
+    float carry[LP];
+#pragma unroll
+    for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
+    int freed = 0;          // every step <= freed is finished (a possibly stale, hence conservative, view)
+
+    for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int nn = n0 + u;
+            const bool past = nn >= len;
+            const float wgt = wcur[u];
+            const int slot = nn & (NR - 1);
+            float *hbuf = &ring[slot][TW];
+
+            // the slot was last used by step nn - NR (steps past the end publish nothing
+            // and write nothing)
+            while (!past && freed < nn - NR) {
+                int lo = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+#pragma unroll
+                for (int j = 1; j < NI; ++j) {
+                    const int cj = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(&consumed[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    lo = cj < lo ? cj : lo;
+                }
+                freed = lo + NI - 1;
+                if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+            float a[LP];
+            float hm = INFINITY;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                float v = cur[u][0][s];
+                float mrm = 0.0f;
+                if (TRWP) {
+#pragma unroll
+                    for (int c = 1; c < RMAX; ++c) {
+                        v = __builtin_fmaf(carry_at[c], carry[s], v);
+                        v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                        mrm = __builtin_fmaf(is_rm[c], cur[u][c][s], mrm);
+                    }
+                    v = __builtin_fmaf(carry_at[RMAX], carry[s], v);
+                    v = rho * v;
+                    v = v - mrm;
+                } else {
+                    v = v + carry[s];
+#pragma unroll
+                    for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                }
+                const int lam = lane + 64 * s;
+                if (lam < L && !past) hbuf[lam] = v;
+                a[s] = lam < L ? v : INFINITY;
+                hm = mrf_min(hm, a[s]);
+            }
+            const float hmin = mrf_wave_min(hm);
+            if (lane == 0 && !past) { ringw[slot] = wgt; ringhm[slot] = hmin; }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_wave_barrier();
+            if (lane == 0 && !past) __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+            // a past step re-reads the slot of an earlier step: its result is never used
+            float tv[LP];
+            float tq;
+            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float dl[2 * TW - 1];
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o) {
+                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                        const float hv = (o == TW - 1) ? a[s] : hbuf[lam + o - (TW - 1)];
+                        dl[o] = __builtin_fmaf(wgt, f[dist], hv);
+                    }
+                    float W = dl[0];
+#pragma unroll
+                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
+                    tv[s] = (lam < L) ? mrf_min(W, gmin) : INFINITY;
+                }
+                if (f0zero) {
+                    tq = hmin;
+                } else {
+                    float mn = INFINITY;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                    tq = mrf_wave_min(mn);
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float best = INFINITY;
+                    for (int mu = 0; mu < L; ++mu) {
+                        int dist = mu > lam ? mu - lam : lam - mu;
+                        dist = dist < TW ? dist : TW;
+                        const float dlt = __builtin_fmaf(wgt, ftab[dist], hbuf[mu]);
+                        if (dlt < best) best = dlt;
+                    }
+                    tv[s] = (lam < L) ? best : INFINITY;
+                }
+                float mn = INFINITY;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                tq = mrf_wave_min(mn);
+            }
+#pragma unroll
+            for (int s = 0; s < LP; ++s) carry[s] = (lane + 64 * s < L) ? tv[s] - tq : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c)
+#pragma unroll
+                for (int s = 0; s < LP; ++s) cur[u][c][s] = nxt[u][c][s];
+        }
+    }
+}
+
 // ---- window sweep, one label per lane, ceil(L/64) wavefronts per scanline ------------------
 //
 // Same arithmetic as mrf_fwd_sweep_window, laid out for launches with few scanlines (TRWP

@@ -160,6 +160,10 @@ WINDOW_CASES = [
     (47, "trwp", 4, 6, 17, DIRS4, 2, 1, 16.0, False, "pos"),       # window almost as wide as the label range
     (48, "trwp", 4, 6, 12, DIRS4, 2, 1, 20.0, False, "pos"),       # no truncation inside the range: dense kernel
     (49, "isgmr", 5, 5, 256, DIRS4, 2, 2, 200.0, True, "zero_mix"),
+    # scanlines several times longer than the ring between the value and index wavefronts
+    (50, "trwp", 3, 41, 96, DIRS4, 2, 1, 8.0, False, "pos"),
+    (51, "isgmr", 2, 37, 40, DIRS8, 2, 1, 2.0, True, "zero_mix"),
+    (52, "trwp", 2, 33, 70, DIRS4, 2, 2, 30.0, True, "neg_mix"),
 ]
 
 
@@ -171,19 +175,24 @@ def test_window_path_is_exact(oracle, case):
     from gpu_harness import run_gpu
     print("case window", case[:5], case[7:], flush=True)
     pr = truncated_problem(*case)
+    got = {}
     try:
-        assert mrf.mrf_tune(2, 1) == 0          # one wavefront per scanline
-        g = full_check(oracle, pr)
-        assert mrf.mrf_tune(2, 2) == 0          # one wavefront per 64 labels
-        g2 = full_check(oracle, pr)
-        assert mrf.mrf_tune(1, 1) == 0          # dense sweep
+        assert mrf.mrf_tune(2, 1) == 0 and mrf.mrf_tune(4, 1) == 0      # one wavefront per scanline
+        got["single"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(4, 2) == 0 and mrf.mrf_tune(5, 1) == 0      # value + one index wavefront
+        got["pair"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(5, 2) == 0                                  # value + two index wavefronts
+        got["trio"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(2, 2) == 0                                  # one wavefront per 64 labels
+        got["split"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(1, 1) == 0                                  # dense sweep
         d = run_gpu(pr)
     finally:
-        mrf.mrf_tune(1, 0)
-        mrf.mrf_tune(2, 0)
-    for name in ("p", "q", "labels", "cost", "messages"):
-        np.testing.assert_array_equal(getattr(g, name), getattr(d, name), err_msg=name)
-        np.testing.assert_array_equal(getattr(g2, name), getattr(d, name), err_msg=name)
+        for knob in (1, 2, 4, 5):
+            mrf.mrf_tune(knob, 0)
+    for layout, g in got.items():
+        for name in ("p", "q", "labels", "cost", "messages"):
+            np.testing.assert_array_equal(getattr(g, name), getattr(d, name), err_msg="%s %s" % (layout, name))
 
 
 @pytest.mark.parametrize("case", [
