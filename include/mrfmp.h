@@ -146,6 +146,11 @@ int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
 /* Static text for a status code. */
 const char *mrf_strerror(int status);
 
+/* After a call returned MRF_ERR_HIP: which runtime call or launch failed and the runtime's
+ * own text for the error ("" if none has failed yet).  Process-global, not thread-safe; the
+ * library owns the string. */
+const char *mrf_last_error_detail(void);
+
 /* Profiling hook: while set (both non-NULL hipEvent_t handles), every forward or backward
  * call records `start_event` on its stream just before its first scanline-sweep launch and
  * `stop_event` just after its last one, so a caller can time the sweeps apart from the

@@ -6,6 +6,7 @@
 #include "mrfmp_bwd.h"
 
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
 namespace {
@@ -79,7 +80,18 @@ int g_tune_split = 0;      // 0 auto, 1 never, 2 whenever L > 64
 int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
 int g_tune_duo = 0;        // 0 auto, 1 never, 2 whenever the window applies
 int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
+int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
+int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 3, 4
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+
+char g_error_detail[256] = "";
+
+// records which call failed and how, for mrf_last_error_detail
+int hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_error_detail, sizeof(g_error_detail), "%s: %s", what, hipGetErrorString(e));
+    return MRF_ERR_HIP;
+}
 
 inline void mark(hipEvent_t ev, hipStream_t st)
 {
@@ -311,7 +323,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     if (pr->edge_weight) { P.w = pr->edge_weight; P.w_mul = 1; }
     else {
         // a scalar weight is read through the same vector loads as per-edge weights
-        if (fill(scal, 1, pr->edge_weight_scalar, st) != hipSuccess) return MRF_ERR_HIP;
+        { const hipError_t e_ = fill(scal, 1, pr->edge_weight_scalar, st); if (e_ != hipSuccess) return hip_fail(e_, "fill"); }
         P.w = scal; P.w_mul = 0;
     }
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
@@ -331,7 +343,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
             for (int r = 0; r < R; ++r) fill_sources(P, algo, r, k == 0 ? 0u : 0xffffffffu);
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
-            if (dispatch_fwd(P, algo, tw, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+            { const hipError_t e_ = dispatch_fwd(P, algo, tw, blocks, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_fwd"); }
             final_m = P.m_out;
         }
     } else {
@@ -347,7 +359,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
                 fill_sources(P, algo, r, k == 0 ? ((1u << r) - 1u) : 0xffffffffu);
                 P.p = p + (size_t)k * pk;
                 P.q = q + (size_t)k * qk;
-                if (dispatch_fwd(P, algo, tw, blocks, st) != hipSuccess) return MRF_ERR_HIP;
+                { const hipError_t e_ = dispatch_fwd(P, algo, tw, blocks, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_fwd"); }
             }
         }
         final_m = bufA;
@@ -360,10 +372,10 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     long long ablocks = (N + 3) / 4;
     if (ablocks > 65536) ablocks = 65536;
     hipLaunchKernelGGL(mrf_aggregate, dim3((unsigned)ablocks), dim3(256), 0, st, A);
-    if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
     if (messages) {
-        if (hipMemcpyAsync(messages, final_m, pk * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
-            return MRF_ERR_HIP;
+        const hipError_t e_ = hipMemcpyAsync(messages, final_m, pk * sizeof(float), hipMemcpyDeviceToDevice, st);
+        if (e_ != hipSuccess) return hip_fail(e_, "hipMemcpyAsync");
     }
     return MRF_OK;
 }
@@ -390,6 +402,22 @@ hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds,
     else
         hipLaunchKernelGGL((mrf_bwd_sweep_split<NS, D, false>), grid, block, lds, st, P);
     return hipGetLastError();
+}
+
+template <int LP, int NS, int D>
+hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t st)
+{
+    const dim3 grid((unsigned)P.total_scanlines);
+    const size_t lds = vg ? 0 : sizeof(float) * (size_t)P.g.L;
+#define MRF_CH(n) \
+    if (ni == n) { \
+        if (vg) hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, true>), grid, dim3(64 * (1 + n)), lds, st, P); \
+        else hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_CH(2) MRF_CH(3) MRF_CH(4)
+#undef MRF_CH
+    return hipErrorInvalidValue;
 }
 
 template <int SEG>
@@ -433,6 +461,17 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     // few labels: several scanlines per wavefront
     if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256))
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
+    // few scanlines: the node-to-node chain on a wavefront of its own, helpers around it
+    if (LP <= 2 && !P.gV && ns <= 8 && g_tune_chain != 1 && (g_tune_chain == 2 || P.total_scanlines <= 1024)) {
+        const int ni = g_tune_chain_ni ? g_tune_chain_ni : 3;
+        const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
+#define MRF_CCASE(lp) \
+        if (LP == lp && ns == 1) return launch_bwd_chain<lp, 1, 2>(P, ni, vg, st); \
+        if (LP == lp && ns == 4) return launch_bwd_chain<lp, 4, 2>(P, ni, vg, st); \
+        if (LP == lp && ns == 8) return launch_bwd_chain<lp, 8, 1>(P, ni, vg, st);
+        MRF_CCASE(1) MRF_CCASE(2)
+#undef MRF_CCASE
+    }
     // few scanlines and many labels: one wavefront per 64 labels
     const bool split = LP >= 3 && g_tune_split != 1 && ns <= 8 &&
                        (g_tune_split == 2 || (P.total_scanlines < 1024 && P.total_scanlines * LP <= 4096));
@@ -505,14 +544,17 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     double *gvslots = (double *)(ws + kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
     if (pr->edge_weight) { P.w = pr->edge_weight; P.w_mul = 1; }
     else {
-        if (fill(scal, 1, pr->edge_weight_scalar, st) != hipSuccess) return MRF_ERR_HIP;
+        { const hipError_t e_ = fill(scal, 1, pr->edge_weight_scalar, st); if (e_ != hipSuccess) return hip_fail(e_, "fill"); }
         P.w = scal; P.w_mul = 0;
     }
 
-    if (grad_w && fill(grad_w, (long long)R * N, 0.0f, st) != hipSuccess) return MRF_ERR_HIP;
+    if (grad_w) {
+        const hipError_t e_ = fill(grad_w, (long long)R * N, 0.0f, st);
+        if (e_ != hipSuccess) return hip_fail(e_, "fill");
+    }
     if (grad_V) {
         P.gV = gvslots;
-        if (fill64(gvslots, grad_slots(L) * L * L, st) != hipSuccess) return MRF_ERR_HIP;
+        { const hipError_t e_ = fill64(gvslots, grad_slots(L) * L * L, st); if (e_ != hipSuccess) return hip_fail(e_, "fill64"); }
     }
 
     mark(g_ev_start, st);
@@ -540,11 +582,11 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
             else { P.src_base = buf0; P.src_stride = NL; }
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
-            if (dispatch_bwd(P, pr->pairwise_kind, st) != hipSuccess) return MRF_ERR_HIP;
+            { const hipError_t e_ = dispatch_bwd(P, pr->pairwise_kind, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_bwd"); }
             C.first = (k == K - 1);
             C.ghat = (k > 0) ? buf0 : nullptr;
             hipLaunchKernelGGL(mrf_isgmr_bwd_combine, dim3((unsigned)cblocks), dim3(256), 0, st, C);
-            if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+            { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
         }
     } else {
         P.S = buf0;
@@ -572,7 +614,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
                 P.unary_init = (k == K - 1);
                 P.p = p + (size_t)k * pk;
                 P.q = q + (size_t)k * qk;
-                if (dispatch_bwd(P, pr->pairwise_kind, st) != hipSuccess) return MRF_ERR_HIP;
+                { const hipError_t e_ = dispatch_bwd(P, pr->pairwise_kind, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_bwd"); }
             }
         }
     }
@@ -583,9 +625,9 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         const unsigned eb = (unsigned)((n + 255) / 256);
         hipLaunchKernelGGL(mrf_reduce_slot_chunks, dim3(eb, (unsigned)((slots + chunk - 1) / chunk)), dim3(256), 0, st,
                            gvslots, n, slots, chunk);
-        if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+        { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
         hipLaunchKernelGGL(mrf_reduce_slot_heads, dim3(eb), dim3(256), 0, st, (const double *)gvslots, grad_V, n, slots, chunk);
-        if (hipGetLastError() != hipSuccess) return MRF_ERR_HIP;
+        { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
     }
     return MRF_OK;
 }
@@ -676,6 +718,8 @@ const char *mrf_strerror(int status)
     }
 }
 
+const char *mrf_last_error_detail(void) { return g_error_detail; }
+
 const char *mrf_version(void) { return "0.1.0"; }
 
 int mrf_set_sweep_events(void *start_event, void *stop_event)
@@ -693,6 +737,8 @@ int mrf_tune(int knob, int value)
     if (knob == 3) { g_tune_pack = value; return MRF_OK; }
     if (knob == 4) { g_tune_duo = value; return MRF_OK; }
     if (knob == 5) { g_tune_duo_ni = (value == 1 || value == 2) ? value : 0; return MRF_OK; }
+    if (knob == 6) { g_tune_chain = value; return MRF_OK; }
+    if (knob == 7) { g_tune_chain_ni = (value >= 2 && value <= 4) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

@@ -327,6 +327,284 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
     }
 }
 
+// ---- index replay with the node-to-node chain on a wavefront of its own ----------------------
+//
+// For launches with few scanlines, where the time of a sweep is the length of a scanline
+// times the latency of one node step.  Of the work of a node only this depends on the
+// previous node: add what it passed back (carry) to the gradient arriving from elsewhere
+// (ext), subtract the label sum at q, scatter through p, scale.  The label sum itself does
+// not: the scattered vector of a node sums to zero (the reparametrisation took exactly its
+// sum off one entry, back Eq. isgmr-norm), hence so does the carry, and the label sum of
+// carry + ext is the label sum of ext up to rounding of the last place of a double.
+//
+// So a scanline gets 1 + NI wavefronts.  The helpers take the nodes in turn: they load,
+// form ext, its label sum, p and q and publish them through a ring in LDS (stage "pre");
+// the chain wavefront touches only LDS: a few adds, the scatter, one read, one publish;
+// the same helpers later pick up what the chain left for a node (incoming carry and
+// scattered vector) and do the rest: grad theta (Alg. 4 line 8), the stored s, the
+// edge-weight gradient (Eq. supp-gradient-edge) (stage "post").  A helper runs pre(t) then
+// post(t - NI), with a ring of 2 NI slots: every slot is free again exactly when its owner
+// comes round to it, so only two kinds of wait exist (chain on pre, post on chain), each on a
+// counter that only grows.
+//
+// Not for launches that also want the V gradient.
+template <int LP, int NS, int D, int NI, bool VG>
+__global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBwdParams P)
+{
+    constexpr int NR = 2 * NI;
+    constexpr int LL = 64 * LP;
+    static_assert(NI >= 1 && NI <= 4, "helpers per scanline");
+    extern __shared__ __align__(16) unsigned char mrf_bsmem[];
+    __shared__ double a_ext[NR][LL];      // pre -> chain, post
+    __shared__ double a_extT[NR][LL];     // pre -> post
+    __shared__ int a_p[NR][LL];
+    __shared__ double a_tot[NR];
+    __shared__ int a_q[NR];
+    __shared__ double b_cin[NR][LL];      // chain -> post: carry that entered the node
+    __shared__ double b_sv[NR][LL];       //                scattered vector that left it
+    __shared__ double sbuf[LL];
+    __shared__ __align__(16) int pre_done[4];     // per helper: last step published
+    __shared__ int chain_done;                    // last step the chain finished
+    float *vl = reinterpret_cast<float *>(mrf_bsmem);
+    const int L = P.g.L;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const long long N = P.g.N;
+
+    if (!VG)
+        for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
+    if (threadIdx.x < 4) pre_done[threadIdx.x] = (int)threadIdx.x - NI;
+    if (threadIdx.x == 0) chain_done = -1;
+    for (int e = threadIdx.x; e < LL; e += blockDim.x) sbuf[e] = 0.0;
+    __syncthreads();
+
+    const long long sl = blockIdx.x;       // one scanline per workgroup
+    int ri = 0;
+    while (ri + 1 < P.r_count && sl >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = sl - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+
+    if (wv == 0) {
+        // ---- the chain: step tt handles node len-1-tt ---------------------------------------
+        const double cscale = (double)P.carry_scale[r];
+        double carry[LP];
+#pragma unroll
+        for (int s = 0; s < LP; ++s) carry[s] = 0.0;
+        int seen[NI];
+#pragma unroll
+        for (int u = 0; u < NI; ++u) seen[u] = -1;
+        int sb = 0;                         // slot of step t0 (t0 is a multiple of NI)
+        for (int t0 = 0; t0 < len; t0 += NI) {
+#pragma unroll
+            for (int u = 0; u < NI; ++u) {
+                const int tt = t0 + u;
+                if (tt < len) {
+                    const int slot = sb + u;
+                    while (seen[u] < tt) {
+                        seen[u] = __builtin_amdgcn_readfirstlane(
+                            __hip_atomic_load(&pre_done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                        if (seen[u] < tt) __builtin_amdgcn_s_sleep(1);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                    const double tot = a_tot[slot];
+                    const int qv = a_q[slot];
+                    double g[LP];
+                    int pv[LP];
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const int lam = lane + 64 * s;
+                        pv[s] = a_p[slot][lam];
+                        g[s] = carry[s] + a_ext[slot][lam];
+                        if (lam == qv) g[s] = g[s] - tot;           // back Eq. isgmr-norm
+                        b_cin[slot][lam] = carry[s];
+                    }
+                    // index scatter: s(mu) = sum over lambda with p(lambda) = mu
+#pragma unroll
+                    for (int s = 0; s < LP; ++s)
+                        if (lane + 64 * s < L)
+                            __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    mrf_wave_lds_fence();
+                    double sv[LP];
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
+                    mrf_wave_lds_fence();
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        sbuf[lane + 64 * s] = 0.0;
+                        b_sv[slot][lane + 64 * s] = sv[s];
+                        carry[s] = cscale * sv[s];
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane == 0) __hip_atomic_store(&chain_done, tt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+            sb = (sb + NI >= NR) ? 0 : sb + NI;
+        }
+        return;
+    }
+
+    // ---- helpers ---------------------------------------------------------------------------
+    const int jw = wv - 1;
+    const bool own_unary = (r == P.unary_dir);
+    const bool unary_old = own_unary && !P.unary_init;
+    const size_t umul = unary_old ? 1 : 0;
+    const uint8_t *pbase = P.p + (size_t)r * N * L;
+    const uint8_t *qbase = P.q + (size_t)r * N;
+    const int vzero = mrf_opaque_zero();
+
+    // source slots; unused ones re-read grad c / the first source with coefficient 0
+    const float *src[NS];
+    double cG[NS], cT[NS];
+    const int nsrc = P.n_src[r];
+#pragma unroll
+    for (int c = 0; c < NS; ++c) {
+        const bool live = c < nsrc;
+        const bool isgc = (c == nsrc) && P.use_gc;
+        src[c] = live ? P.src_base + (size_t)P.src_dir[r][c] * P.src_stride : P.gc;
+        cG[c] = live ? (double)P.coefG[r][c] : (isgc ? 1.0 : 0.0);
+        cT[c] = live ? (double)P.coefT[r][c] : (isgc ? 1.0 : 0.0);
+    }
+
+    // the last node of the scanline has no successor in direction r
+    if (jw == 0) {
+        const long long last = head + (long long)(len - 1) * nstep;
+#pragma unroll
+        for (int s = 0; s < LP; ++s) {
+            const int lam = lane + 64 * s;
+            if (lam < L) P.S[((size_t)r * N + last) * L + lam] = 0.0f;
+        }
+    }
+
+    // own steps: tt = jw + it * NI, it = 0 .. T-1; one more turn for the last post
+    const int T = len > jw ? (len - jw + NI - 1) / NI : 0;
+    float cur[D][NS][LP], nxt[D][NS][LP];
+    float ucur[D][LP], unxt[D][LP];
+    int pcur[D][LP], pnxt[D][LP];
+    int qcur[D], qnxt[D];
+    auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, int it) {
+        int n = len - 1 - (jw + it * NI);
+        n = n > 0 ? n : 0;
+        const long long i = head + (long long)n * nstep;
+#pragma unroll
+        for (int s = 0; s < LP; ++s) {
+            const int lam = lane + 64 * s;
+            const int lc = lam < L ? lam : 0;
+#pragma unroll
+            for (int c = 0; c < NS; ++c) dst[c][s] = src[c][(size_t)i * L + lc];
+            udst[s] = P.gunary[((size_t)i * L + lc) * umul];   // one cached word unless it is needed
+            pdst[s] = pbase[(size_t)i * L + lc];
+        }
+        qdst = qbase[(size_t)i + vzero];
+    };
+    if (T > 0) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], u);
+    }
+
+    int chain_seen = -1;
+    for (int it0 = 0; it0 < T + 1 && T > 0; it0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], it0 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int tt = jw + (it0 + u) * NI;
+            if (tt < len) {
+                // ---- pre(tt): everything of node len-1-tt that does not need the carry -------
+                const int slot = tt % NR;
+                double part = 0.0;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    double e = 0.0, eT = 0.0;
+#pragma unroll
+                    for (int c = 0; c < NS; ++c) {
+                        e += cG[c] * (double)cur[u][c][s];
+                        eT += cT[c] * (double)cur[u][c][s];
+                    }
+                    eT += unary_old ? (double)ucur[u][s] : 0.0;     // (the buffer may hold anything at first)
+                    e = lam < L ? e : 0.0;
+                    part += e;
+                    a_ext[slot][lam] = e;
+                    if (own_unary) a_extT[slot][lam] = eT;
+                    a_p[slot][lam] = pcur[u][s] < L ? pcur[u][s] : L - 1;
+                }
+                const double tot = mrf_wave_sum_f64(part);
+                int qv = __builtin_amdgcn_readfirstlane(qcur[u]);
+                qv = qv < L ? qv : L - 1;
+                if (lane == 0) { a_tot[slot] = tot; a_q[slot] = qv; }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                __builtin_amdgcn_wave_barrier();
+                if (lane == 0) __hip_atomic_store(&pre_done[jw], tt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            const int tp = tt - NI;
+            if (tp >= 0 && tp < len) {
+                // ---- post(tp): what is left of node len-1-tp once the chain has passed --------
+                while (chain_seen < tp) {
+                    chain_seen = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(&chain_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    if (chain_seen < tp) __builtin_amdgcn_s_sleep(1);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                const int slot = tp % NR;
+                const int n = len - 1 - tp;
+                const bool update = n > 0;             // node i has a predecessor: its update is replayed
+                const long long i = head + (long long)n * nstep;
+                const long long j = i - nstep;
+                const double tot = a_tot[slot];
+                const int qv = a_q[slot];
+                double acc = 0.0;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    const double cin = b_cin[slot][lam];
+                    if (own_unary && lam < L)
+                        P.gunary[(size_t)i * L + lam] = (float)(cin + a_extT[slot][lam]);
+                    if (update && lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)b_sv[slot][lam];
+                    if (P.gw && lam < L) {
+                        double g = cin + a_ext[slot][lam];          // as the chain formed it
+                        if (lam == qv) g = g - tot;
+                        const int pv = a_p[slot][lam];
+                        float vv;
+                        if (VG) {
+                            vv = P.V[(size_t)pv * L + lam];
+                        } else {
+                            const int dist = pv > lam ? pv - lam : lam - pv;
+                            vv = vl[dist];
+                        }
+                        acc += g * (double)vv;
+                    }
+                }
+                if (P.gw) {
+                    acc = mrf_wave_sum_f64(acc);
+                    // one writer per entry and launch: a no-return atomic is a plain accumulate
+                    if (update && lane == 0)
+                        __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            qcur[u] = qnxt[u];
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                ucur[u][s] = unxt[u][s];
+                pcur[u][s] = pnxt[u][s];
+#pragma unroll
+                for (int c = 0; c < NS; ++c) cur[u][c][s] = nxt[u][c][s];
+            }
+        }
+    }
+}
+
 // ---- index replay, one label per lane, ceil(L/64) wavefronts per scanline --------------------
 //
 // Same arithmetic as mrf_bwd_sweep for launches with few scanlines and many labels (a lone

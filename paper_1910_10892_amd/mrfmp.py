@@ -22,7 +22,9 @@ _lib = None
 class MrfError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__("%s failed: %s (status %d)" % (where, mrf_strerror(status), status))
+        detail = mrf_last_error_detail() if status == -9 else ""
+        super().__init__("%s failed: %s (status %d)%s" % (where, mrf_strerror(status), status,
+                                                          " [" + detail + "]" if detail else ""))
 
 
 class _CProblem(ctypes.Structure):
@@ -53,6 +55,11 @@ def load_library():
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             "libmrfmp.so not built: run `python -m paper_1910_10892_amd.build` (needs hipcc)")
+    # The tensors this binding is handed live in PyTorch's HIP runtime.  Import torch first, so
+    # that the library's dependency on libamdhip64 binds to the copy torch has loaded; loaded
+    # the other way round the process ends up with two runtimes and the library's own sees
+    # no initialised device.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     P = ctypes.POINTER(_CProblem)
@@ -75,6 +82,8 @@ def load_library():
     lib.mrf_scanline_head.restype = ci
     lib.mrf_scanline_head.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_int64] + [ctypes.POINTER(ctypes.c_int32)] * 3
     lib.mrf_strerror.restype = ctypes.c_char_p
+    lib.mrf_last_error_detail.restype = ctypes.c_char_p
+    lib.mrf_last_error_detail.argtypes = []
     lib.mrf_strerror.argtypes = [ci]
     lib.mrf_version.restype = ctypes.c_char_p
     lib.mrf_set_sweep_events.restype = ci
@@ -146,6 +155,10 @@ def _stream_handle(stream):
 
 def mrf_strerror(status: int) -> str:
     return load_library().mrf_strerror(int(status)).decode()
+
+
+def mrf_last_error_detail() -> str:
+    return load_library().mrf_last_error_detail().decode()
 
 
 def mrf_version() -> str:

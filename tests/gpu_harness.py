@@ -75,10 +75,13 @@ class GpuProblem:
         return out
 
 
-def run_gpu(pr, backward=True) -> GpuRun:
+def run_gpu(pr, backward=True, want_V=True) -> GpuRun:
     g = GpuProblem(pr)
     g.poison_outputs()
     g.forward()
     if backward:
-        g.backward()
-    return g.results(backward)
+        g.backward(want_V=want_V)
+    out = g.results(backward)
+    if backward and not want_V:
+        out.grad_pairwise = None
+    return out

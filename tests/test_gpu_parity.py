@@ -46,20 +46,23 @@ def check_grad(name, got, ref32, ref64):
         name, worst, e32.max(), e64.max())
 
 
-def check_backward(g, b32, b64):
+def check_backward(g, b32, b64, want_V=True):
     check_grad("grad_unary", g.grad_unary, b32.grad_unary, b64.grad_unary)
     check_grad("grad_edge_weight", g.grad_edge_weight, b32.grad_edge_weight, b64.grad_edge_weight)
-    check_grad("grad_pairwise", g.grad_pairwise, b32.grad_pairwise, b64.grad_pairwise)
+    if want_V:
+        check_grad("grad_pairwise", g.grad_pairwise, b32.grad_pairwise, b64.grad_pairwise)
 
 
-def full_check(oracle, pr, threads=False):
+def full_check(oracle, pr, threads=False, want_V=True):
+    """want_V=False: the caller passes no grad_pairwise buffer (a model whose V has no free
+    parameters); the library may then pick other backward kernels."""
     from gpu_harness import run_gpu
-    g = run_gpu(pr)
+    g = run_gpu(pr, want_V=want_V)
     f = oracle_forward(oracle, pr, threads=threads)
     check_forward(g, f)
     b32 = oracle_backward(oracle, pr, f.p, f.q, np.float32)
     b64 = oracle_backward(oracle, pr, f.p, f.q, np.float64)
-    check_backward(g, b32, b64)
+    check_backward(g, b32, b64, want_V)
     return g
 
 
@@ -195,6 +198,52 @@ def test_window_path_is_exact(oracle, case):
             np.testing.assert_array_equal(getattr(g, name), getattr(d, name), err_msg="%s %s" % (layout, name))
 
 
+CHAIN_CASES = [
+    # seed, algo, B, H, W, L, dirs, K, integer_valued, per_edge
+    (81, "trwp", 1, 3, 70, 96, DIRS4, 2, False, True),      # scanlines many times the ring
+    (82, "isgmr", 1, 2, 45, 40, DIRS8, 2, True, True),
+    (83, "trwp", 2, 5, 6, 128, DIRS8, 2, False, False),
+    (84, "isgmr", 1, 7, 9, 1, DIRS4, 2, False, True),
+    (85, "trwp", 1, 1, 11, 20, DIRS16, 2, True, True),      # one row: most scanlines have one node
+    (86, "trwp", 1, 9, 2, 65, [(0, 1), (1, 0), (-1, 0)], 3, False, True),
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_CASES, ids=lambda c: "seed%d" % c[0])
+def test_chain_wavefront_backward_layout(oracle, case):
+    """Backward sweeps that keep only the node-to-node chain on one wavefront and give the rest
+    of a node to 2, 3 or 4 helper wavefronts (chosen for launches with few scanlines when no
+    grad_pairwise is asked for): each against the oracle, and against the one-wavefront sweep."""
+    import paper_1910_10892_amd as mrf
+    print("case chain backward", case[:8], flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv, pe = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=pe,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    got = {}
+    try:
+        assert mrf.mrf_tune(6, 1) == 0
+        got[0] = full_check(oracle, pr, want_V=False)
+        assert mrf.mrf_tune(6, 2) == 0
+        for ni in (2, 3, 4):
+            assert mrf.mrf_tune(7, ni) == 0
+            got[ni] = full_check(oracle, pr, want_V=False)
+    finally:
+        mrf.mrf_tune(6, 0)
+        mrf.mrf_tune(7, 0)
+    for ni in (2, 3, 4):
+        for name in ("grad_unary", "grad_edge_weight"):
+            np.testing.assert_allclose(getattr(got[ni], name), getattr(got[0], name), rtol=1e-5, atol=1e-4,
+                                       err_msg="%d helpers, %s" % (ni, name))
+
+
+@pytest.mark.parametrize("index,crop,algo,K", [c for c in CONFIG_CASES if c[0] != 5])
+def test_benchmark_configs_cropped_without_pairwise_gradient(oracle, index, crop, algo, K):
+    """The truncated models have no free parameters in V: run them the way bench.py does."""
+    print("case config, no grad_pairwise", index, crop, algo, K, flush=True)
+    pr = make_config(index, crop=crop, algo=algo, K=K)
+    full_check(oracle, pr, want_V=False)
+
+
 @pytest.mark.parametrize("case", [
     (61, "trwp", 1, 6, 7, 200, DIRS4, 3, False, True),
     (62, "isgmr", 1, 5, 6, 256, DIRS8, 2, True, True),
@@ -313,8 +362,17 @@ def test_large_configs(oracle, index, crop, algo):
 
 def test_full_size_stereo_config_trwp(oracle):
     """The configuration the bench times (TRWP, 256x512, L = 96, K = 5), whole grid, in the
-    launch configuration the bench uses; oracle forward on all host threads (bit-identical
-    to one thread, asserted in the CPU suite)."""
+    launch configuration the bench uses (no grad_pairwise buffer: truncated linear V), and once
+    more with that buffer; oracle forward on all host threads (bit-identical to one thread,
+    asserted in the CPU suite)."""
+    from gpu_harness import run_gpu
     print("case full config 2", flush=True)
     pr = make_config(2)
-    full_check(oracle, pr, threads=True)
+    f = oracle_forward(oracle, pr, threads=True)
+    b32 = oracle_backward(oracle, pr, f.p, f.q, np.float32)
+    b64 = oracle_backward(oracle, pr, f.p, f.q, np.float64)
+    for want_V in (False, True):
+        print("  grad_pairwise buffer:", want_V, flush=True)
+        g = run_gpu(pr, want_V=want_V)
+        check_forward(g, f)
+        check_backward(g, b32, b64, want_V)
