@@ -81,7 +81,7 @@ int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
 int g_tune_duo = 0;        // 0 auto, 1 never, 2 whenever the window applies
 int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
 int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
-int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 3, 4
+int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 char g_error_detail[256] = "";
@@ -408,14 +408,15 @@ template <int LP, int NS, int D>
 hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t st)
 {
     const dim3 grid((unsigned)P.total_scanlines);
-    const size_t lds = vg ? 0 : sizeof(float) * (size_t)P.g.L;
+    const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg);
+    if (lds > 64 * 1024) return hipErrorInvalidValue;
 #define MRF_CH(n) \
     if (ni == n) { \
         if (vg) hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, true>), grid, dim3(64 * (1 + n)), lds, st, P); \
         else hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
         return hipGetLastError(); \
     }
-    MRF_CH(2) MRF_CH(3) MRF_CH(4)
+    MRF_CH(2) MRF_CH(4) MRF_CH(6) MRF_CH(8)
 #undef MRF_CH
     return hipErrorInvalidValue;
 }
@@ -463,7 +464,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     // few scanlines: the node-to-node chain on a wavefront of its own, helpers around it
     if (LP <= 2 && !P.gV && ns <= 8 && g_tune_chain != 1 && (g_tune_chain == 2 || P.total_scanlines <= 1024)) {
-        const int ni = g_tune_chain_ni ? g_tune_chain_ni : 3;
+        const int ni = g_tune_chain_ni ? g_tune_chain_ni : 4;
         const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
 #define MRF_CCASE(lp) \
         if (LP == lp && ns == 1) return launch_bwd_chain<lp, 1, 2>(P, ni, vg, st); \
@@ -738,7 +739,7 @@ int mrf_tune(int knob, int value)
     if (knob == 4) { g_tune_duo = value; return MRF_OK; }
     if (knob == 5) { g_tune_duo_ni = (value == 1 || value == 2) ? value : 0; return MRF_OK; }
     if (knob == 6) { g_tune_chain = value; return MRF_OK; }
-    if (knob == 7) { g_tune_chain_ni = (value >= 2 && value <= 4) ? value : 0; return MRF_OK; }
+    if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

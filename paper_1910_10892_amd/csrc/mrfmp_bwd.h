@@ -62,6 +62,15 @@ struct MrfBwdParams {
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
+#define MRF_CHAIN_MAX_HELPERS 8
+
+// dynamic LDS of mrf_bwd_sweep_chain (host and device agree through this one expression)
+__host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L, bool with_theta, bool vg)
+{
+    const size_t NR = 2 * (size_t)NI, LL = 64 * (size_t)LP;
+    return sizeof(double) * (3 * NR * LL + LL) + sizeof(float) * (with_theta ? NR * LL : 0) +
+           sizeof(int) * (MRF_CHAIN_MAX_HELPERS + 1) + sizeof(float) * (vg ? 0 : (size_t)L) + NR * LL;
+}
 
 // LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
 // gradient is gathered from global memory (it fits neither LDS layout), HOT: pre-reduce the
@@ -335,17 +344,20 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 // (ext), subtract the label sum at q, scatter through p, scale.  The label sum itself does
 // not: the scattered vector of a node sums to zero (the reparametrisation took exactly its
 // sum off one entry, back Eq. isgmr-norm), hence so does the carry, and the label sum of
-// carry + ext is the label sum of ext up to rounding of the last place of a double.
+// carry + ext is the label sum of ext up to rounding in the last place of a double.  So the
+// correction at q can be applied to ext before the carry is known.
 //
-// So a scanline gets 1 + NI wavefronts.  The helpers take the nodes in turn: they load,
-// form ext, its label sum, p and q and publish them through a ring in LDS (stage "pre");
-// the chain wavefront touches only LDS: a few adds, the scatter, one read, one publish;
-// the same helpers later pick up what the chain left for a node (incoming carry and
-// scattered vector) and do the rest: grad theta (Alg. 4 line 8), the stored s, the
+// A scanline gets 1 + NI wavefronts.  The helpers take the nodes in turn: they load, form
+// ext with the correction at q, and publish it with p through a ring in LDS (stage "pre");
+// the chain wavefront touches only LDS: one add per label, the scatter, one read, one
+// multiply; the same helpers later pick up what the chain left for a node (incoming carry
+// and scattered vector) and do the rest: grad theta (Alg. 4 line 8), the stored s, the
 // edge-weight gradient (Eq. supp-gradient-edge) (stage "post").  A helper runs pre(t) then
 // post(t - NI), with a ring of 2 NI slots: every slot is free again exactly when its owner
-// comes round to it, so only two kinds of wait exist (chain on pre, post on chain), each on a
-// counter that only grows.
+// comes round to it, so only two kinds of wait exist (chain on pre, post on chain), each on
+// a counter that only grows.  The chain reads one node ahead and frees a node for post one
+// step late; with NI >= 2 no wait can depend on itself: post(t - 2 NI), which precedes
+// pre(t) in its helper, needs the chain to have passed step t - 2 NI + 1 only.
 //
 // Not for launches that also want the V gradient.
 template <int LP, int NS, int D, int NI, bool VG>
@@ -353,27 +365,26 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
 {
     constexpr int NR = 2 * NI;
     constexpr int LL = 64 * LP;
-    static_assert(NI >= 1 && NI <= 4, "helpers per scanline");
+    static_assert(NI >= 2 && NI <= MRF_CHAIN_MAX_HELPERS, "helpers per scanline");
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
-    __shared__ double a_ext[NR][LL];      // pre -> chain, post
-    __shared__ double a_extT[NR][LL];     // pre -> post
-    __shared__ int a_p[NR][LL];
-    __shared__ double a_tot[NR];
-    __shared__ int a_q[NR];
-    __shared__ double b_cin[NR][LL];      // chain -> post: carry that entered the node
-    __shared__ double b_sv[NR][LL];       //                scattered vector that left it
-    __shared__ double sbuf[LL];
-    __shared__ __align__(16) int pre_done[4];     // per helper: last step published
-    __shared__ int chain_done;                    // last step the chain finished
-    float *vl = reinterpret_cast<float *>(mrf_bsmem);
+    // carved in the order of mrf_bwd_chain_lds_bytes
+    double *a_ext = reinterpret_cast<double *>(mrf_bsmem);       // [NR][LL] pre -> chain, post
+    double *b_cin = a_ext + NR * LL;                             // [NR][LL] chain -> post: carry that entered the node
+    double *b_sv = b_cin + NR * LL;                              // [NR][LL]                scattered vector that left it
+    double *sbuf = b_sv + NR * LL;                               // [LL] scatter target of the chain
+    float *a_extT = reinterpret_cast<float *>(sbuf + LL);        // [NR][LL] pre -> post (launches that form grad theta)
+    int *pre_done = reinterpret_cast<int *>(a_extT + (P.unary_dir >= 0 ? NR * LL : 0));   // [MRF_CHAIN_MAX_HELPERS] per helper: last step published
+    int *chain_done = pre_done + MRF_CHAIN_MAX_HELPERS;          // last step the chain finished
+    float *vl = reinterpret_cast<float *>(chain_done + 1);       // [L] first row of V (unless VG)
+    uint8_t *a_p = reinterpret_cast<uint8_t *>(vl + (VG ? 0 : P.g.L));   // [NR][LL]
     const int L = P.g.L;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const long long N = P.g.N;
 
     if (!VG)
         for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
-    if (threadIdx.x < 4) pre_done[threadIdx.x] = (int)threadIdx.x - NI;
-    if (threadIdx.x == 0) chain_done = -1;
+    if (threadIdx.x < MRF_CHAIN_MAX_HELPERS) pre_done[threadIdx.x] = (int)threadIdx.x - NI;
+    if (threadIdx.x == 0) *chain_done = -1;
     for (int e = threadIdx.x; e < LL; e += blockDim.x) sbuf[e] = 0.0;
     __syncthreads();
 
@@ -393,13 +404,28 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
 
     if (wv == 0) {
         // ---- the chain: step tt handles node len-1-tt ---------------------------------------
+        // One wait per step: the read of the scattered vector.  What the step needs from the
+        // ring is read one step ahead, and the counter that frees a step for the helpers is
+        // written one step late, when the LDS queue is known to have drained past it.
         const double cscale = (double)P.carry_scale[r];
-        double carry[LP];
+        double carry[LP], ext[LP];
+        int pv[LP];
+        auto await = [&](int u, int tt) {
+            int sn;
+            do {
+                sn = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&pre_done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (sn < tt) __builtin_amdgcn_s_sleep(1);
+            } while (sn < tt);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        };
+        await(0, 0);
 #pragma unroll
-        for (int s = 0; s < LP; ++s) carry[s] = 0.0;
-        int seen[NI];
-#pragma unroll
-        for (int u = 0; u < NI; ++u) seen[u] = -1;
+        for (int s = 0; s < LP; ++s) {
+            carry[s] = 0.0;
+            ext[s] = a_ext[lane + 64 * s];
+            pv[s] = a_p[lane + 64 * s];
+        }
         int sb = 0;                         // slot of step t0 (t0 is a multiple of NI)
         for (int t0 = 0; t0 < len; t0 += NI) {
 #pragma unroll
@@ -407,47 +433,58 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                 const int tt = t0 + u;
                 if (tt < len) {
                     const int slot = sb + u;
-                    while (seen[u] < tt) {
-                        seen[u] = __builtin_amdgcn_readfirstlane(
-                            __hip_atomic_load(&pre_done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                        if (seen[u] < tt) __builtin_amdgcn_s_sleep(1);
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-                    const double tot = a_tot[slot];
-                    const int qv = a_q[slot];
-                    double g[LP];
-                    int pv[LP];
+                    const int un = (u + 1 == NI) ? 0 : u + 1;
+                    const int slotn = (u + 1 == NI) ? (sb == 0 ? NI : 0) : slot + 1;
+                    const bool more = tt + 1 < len;
+                    // index scatter: s(mu) = sum over lambda with p(lambda) = mu (labels past L
+                    // carry zeros to entries of their own)
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
                         const int lam = lane + 64 * s;
-                        pv[s] = a_p[slot][lam];
-                        g[s] = carry[s] + a_ext[slot][lam];
-                        if (lam == qv) g[s] = g[s] - tot;           // back Eq. isgmr-norm
-                        b_cin[slot][lam] = carry[s];
+                        const double g = carry[s] + ext[s];
+                        b_cin[slot * LL + lam] = carry[s];
+                        __hip_atomic_fetch_add(&sbuf[pv[s]], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     }
-                    // index scatter: s(mu) = sum over lambda with p(lambda) = mu
-#pragma unroll
-                    for (int s = 0; s < LP; ++s)
-                        if (lane + 64 * s < L)
-                            __hip_atomic_fetch_add(&sbuf[pv[s]], g[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     mrf_wave_lds_fence();
+                    // In one batch behind the scatter: the counter of the next node's helper, then
+                    // (the LDS queue keeps this order) that node's ring entries, then the scattered
+                    // vector.  If the counter turns out not to cover the node, its entries are read
+                    // again after waiting.
+                    const int flag = __hip_atomic_load(&pre_done[un], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                     double sv[LP];
 #pragma unroll
-                    for (int s = 0; s < LP; ++s) sv[s] = sbuf[lane + 64 * s];
-                    mrf_wave_lds_fence();
+                    for (int s = 0; s < LP; ++s) {
+                        ext[s] = a_ext[slotn * LL + lane + 64 * s];
+                        pv[s] = a_p[slotn * LL + lane + 64 * s];
+                        sv[s] = sbuf[lane + 64 * s];
+                    }
+                    if (more && __builtin_amdgcn_readfirstlane(flag) < tt + 1) {
+                        await(un, tt + 1);
+#pragma unroll
+                        for (int s = 0; s < LP; ++s) {
+                            ext[s] = a_ext[slotn * LL + lane + 64 * s];
+                            pv[s] = a_p[slotn * LL + lane + 64 * s];
+                        }
+                    }
+                    // everything this wavefront sent to LDS before the reads above has landed
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane == 0 && tt > 0)
+                        __hip_atomic_store(chain_done, tt - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
                         sbuf[lane + 64 * s] = 0.0;
-                        b_sv[slot][lane + 64 * s] = sv[s];
+                        b_sv[slot * LL + lane + 64 * s] = sv[s];
                         carry[s] = cscale * sv[s];
                     }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-                    __builtin_amdgcn_wave_barrier();
-                    if (lane == 0) __hip_atomic_store(&chain_done, tt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            sb = (sb + NI >= NR) ? 0 : sb + NI;
+            sb = (sb == 0) ? NI : 0;
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) __hip_atomic_store(chain_done, len - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         return;
     }
 
@@ -520,26 +557,34 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                 // ---- pre(tt): everything of node len-1-tt that does not need the carry -------
                 const int slot = tt % NR;
                 double part = 0.0;
+                double ev[LP];
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
                     double e = 0.0, eT = 0.0;
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) {
-                        e += cG[c] * (double)cur[u][c][s];
-                        eT += cT[c] * (double)cur[u][c][s];
+                    for (int c = 0; c < NS; ++c) e += cG[c] * (double)cur[u][c][s];
+                    if (own_unary) {
+#pragma unroll
+                        for (int c = 0; c < NS; ++c) eT += cT[c] * (double)cur[u][c][s];
+                        eT += unary_old ? (double)ucur[u][s] : 0.0;     // (the buffer may hold anything at first)
                     }
-                    eT += unary_old ? (double)ucur[u][s] : 0.0;     // (the buffer may hold anything at first)
-                    e = lam < L ? e : 0.0;
-                    part += e;
-                    a_ext[slot][lam] = e;
-                    if (own_unary) a_extT[slot][lam] = eT;
-                    a_p[slot][lam] = pcur[u][s] < L ? pcur[u][s] : L - 1;
+                    ev[s] = lam < L ? e : 0.0;
+                    part += ev[s];
+                    if (own_unary) a_extT[slot * LL + lam] = (float)eT;
+                    // (labels past L scatter their zeros to entries of their own)
+                    a_p[slot * LL + lam] = (uint8_t)(lam < L ? (pcur[u][s] < L ? pcur[u][s] : L - 1) : lam);
                 }
+                // back Eq. isgmr-norm, on the part of g that is known here: the entry at q loses
+                // the label sum
                 const double tot = mrf_wave_sum_f64(part);
                 int qv = __builtin_amdgcn_readfirstlane(qcur[u]);
                 qv = qv < L ? qv : L - 1;
-                if (lane == 0) { a_tot[slot] = tot; a_q[slot] = qv; }
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    a_ext[slot * LL + lam] = (lam == qv) ? ev[s] - tot : ev[s];
+                }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
                 __builtin_amdgcn_wave_barrier();
                 if (lane == 0) __hip_atomic_store(&pre_done[jw], tt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -549,7 +594,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                 // ---- post(tp): what is left of node len-1-tp once the chain has passed --------
                 while (chain_seen < tp) {
                     chain_seen = __builtin_amdgcn_readfirstlane(
-                        __hip_atomic_load(&chain_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                        __hip_atomic_load(chain_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
                     if (chain_seen < tp) __builtin_amdgcn_s_sleep(1);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
@@ -558,20 +603,17 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                 const bool update = n > 0;             // node i has a predecessor: its update is replayed
                 const long long i = head + (long long)n * nstep;
                 const long long j = i - nstep;
-                const double tot = a_tot[slot];
-                const int qv = a_q[slot];
                 double acc = 0.0;
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    const double cin = b_cin[slot][lam];
+                    const double cin = b_cin[slot * LL + lam];
                     if (own_unary && lam < L)
-                        P.gunary[(size_t)i * L + lam] = (float)(cin + a_extT[slot][lam]);
-                    if (update && lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)b_sv[slot][lam];
+                        P.gunary[(size_t)i * L + lam] = (float)(cin + (double)a_extT[slot * LL + lam]);
+                    if (update && lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)b_sv[slot * LL + lam];
                     if (P.gw && lam < L) {
-                        double g = cin + a_ext[slot][lam];          // as the chain formed it
-                        if (lam == qv) g = g - tot;
-                        const int pv = a_p[slot][lam];
+                        const double g = cin + a_ext[slot * LL + lam];    // as the chain formed it
+                        const int pv = a_p[slot * LL + lam];
                         float vv;
                         if (VG) {
                             vv = P.V[(size_t)pv * L + lam];

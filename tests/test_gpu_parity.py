@@ -212,7 +212,7 @@ CHAIN_CASES = [
 @pytest.mark.parametrize("case", CHAIN_CASES, ids=lambda c: "seed%d" % c[0])
 def test_chain_wavefront_backward_layout(oracle, case):
     """Backward sweeps that keep only the node-to-node chain on one wavefront and give the rest
-    of a node to 2, 3 or 4 helper wavefronts (chosen for launches with few scanlines when no
+    of a node to 2, 4, 6 or 8 helper wavefronts (chosen for launches with few scanlines when no
     grad_pairwise is asked for): each against the oracle, and against the one-wavefront sweep."""
     import paper_1910_10892_amd as mrf
     print("case chain backward", case[:8], flush=True)
@@ -224,13 +224,13 @@ def test_chain_wavefront_backward_layout(oracle, case):
         assert mrf.mrf_tune(6, 1) == 0
         got[0] = full_check(oracle, pr, want_V=False)
         assert mrf.mrf_tune(6, 2) == 0
-        for ni in (2, 3, 4):
+        for ni in (2, 4, 6, 8):
             assert mrf.mrf_tune(7, ni) == 0
             got[ni] = full_check(oracle, pr, want_V=False)
     finally:
         mrf.mrf_tune(6, 0)
         mrf.mrf_tune(7, 0)
-    for ni in (2, 3, 4):
+    for ni in (2, 4, 6, 8):
         for name in ("grad_unary", "grad_edge_weight"):
             np.testing.assert_allclose(getattr(got[ni], name), getattr(got[0], name), rtol=1e-5, atol=1e-4,
                                        err_msg="%d helpers, %s" % (ni, name))
