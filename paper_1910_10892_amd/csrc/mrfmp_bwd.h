@@ -80,7 +80,8 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 {
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
     const int L = P.g.L;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     double *sbuf = reinterpret_cast<double *>(mrf_bsmem) + wv * 64 * LP;
     double *gvl = reinterpret_cast<double *>(mrf_bsmem) + MRF_BWD_WAVES * 64 * LP + (P.gv_lds ? wv * L * L : 0);
     float *vl = reinterpret_cast<float *>(reinterpret_cast<double *>(mrf_bsmem) + MRF_BWD_WAVES * 64 * LP +
@@ -378,7 +379,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     float *vl = reinterpret_cast<float *>(chain_done + 1);       // [L] first row of V (unless VG)
     uint8_t *a_p = reinterpret_cast<uint8_t *>(vl + (VG ? 0 : P.g.L));   // [NR][LL]
     const int L = P.g.L;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     const long long N = P.g.N;
 
     if (!VG)
@@ -563,10 +565,10 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     const int lam = lane + 64 * s;
                     double e = 0.0, eT = 0.0;
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) e += cG[c] * (double)cur[u][c][s];
+                    for (int c = 0; c < NS; ++c) e = __builtin_fma(cG[c], (double)cur[u][c][s], e);
                     if (own_unary) {
 #pragma unroll
-                        for (int c = 0; c < NS; ++c) eT += cT[c] * (double)cur[u][c][s];
+                        for (int c = 0; c < NS; ++c) eT = __builtin_fma(cT[c], (double)cur[u][c][s], eT);
                         eT += unary_old ? (double)ucur[u][s] : 0.0;     // (the buffer may hold anything at first)
                     }
                     ev[s] = lam < L ? e : 0.0;
@@ -621,7 +623,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                             const int dist = pv > lam ? pv - lam : lam - pv;
                             vv = vl[dist];
                         }
-                        acc += g * (double)vv;
+                        acc = __builtin_fma(g, (double)vv, acc);
                     }
                 }
                 if (P.gw) {
@@ -666,7 +668,8 @@ __global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
     __shared__ int pqs[2];
     float *vl = reinterpret_cast<float *>(mrf_bsmem);
     const int L = P.g.L;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     const int NWV = blockDim.x >> 6;
     const int lam = wv * 64 + lane;
     const bool valid = lam < L;

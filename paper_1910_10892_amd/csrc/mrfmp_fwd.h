@@ -48,7 +48,8 @@ mrf_fwd_sweep(const MrfFwdParams P)
     constexpr int LPAD = NWMAX * MCH;
     constexpr int SLOTS = 64 * LP;
     const int L = P.g.L, NW = P.NW;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     float *hbuf = reinterpret_cast<float *>(mrf_smem) + wv * LPAD;          // private to this wavefront
     float2 *part = reinterpret_cast<float2 *>(reinterpret_cast<float *>(mrf_smem) + NWMAX * LPAD);  // [2][NWMAX][SLOTS]
 
@@ -295,7 +296,7 @@ struct MrfAggParams {
 __global__ void __launch_bounds__(256) mrf_aggregate(const MrfAggParams P)
 {
     const int lane = threadIdx.x & 63;
-    const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const long long nwaves = (long long)gridDim.x * (blockDim.x >> 6);
     const int L = P.L;
     for (long long i = wave; i < P.N; i += nwaves) {
@@ -601,7 +602,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     __shared__ __align__(16) int consumed[4];     // per index wavefront: last step finished
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
-    const bool index_wave = threadIdx.x >= 64;
+    const bool index_wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) > 0;
 
     const long long blk = blockIdx.x;
     int ri = 0;
@@ -635,7 +636,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 
     if (index_wave) {
         // ---- p, q and all stores -----------------------------------------------------------
-        const int jw = (int)(threadIdx.x >> 6) - 1;
+        const int jw = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) - 1;
         if (jw == 0) {
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
@@ -935,7 +936,8 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
     __shared__ __align__(16) float tmslot[2][4];     // local minima of the new message (general path)
     __shared__ __align__(16) int qslot[2][4];        // local candidates for q
     const int L = P.g.L;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     const int NWV = blockDim.x >> 6;
     const int lam = wv * 64 + lane;
     const bool valid = lam < L;

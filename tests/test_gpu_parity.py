@@ -315,7 +315,8 @@ def test_optional_outputs_may_be_null(oracle):
         torch.cuda.synchronize()
         np.testing.assert_array_equal(g.cost.cpu().numpy(), ref.cost)
         np.testing.assert_array_equal(g.p.cpu().numpy(), ref.p)
-        np.testing.assert_array_equal(g.grad_unary.cpu().numpy(), ref.grad_unary)
+        # (without grad_pairwise the library may run other backward kernels: same sums, other order)
+        np.testing.assert_allclose(g.grad_unary.cpu().numpy(), ref.grad_unary, rtol=1e-5, atol=1e-5)
 
 
 def test_backward_is_reproducible_run_to_run():
