@@ -230,7 +230,13 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         }
         // few scanlines: a second wavefront per scanline takes the argmin tables and the
         // stores off the dependency chain
-        const bool duo = g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= 4096);
+        // (its addressing wants a node step times L in 32 bits)
+        bool step_fits = true;
+        for (int r = P.r_first; r < P.r_first + P.r_count; ++r) {
+            const long long st = ((long long)mrf_iabs(P.g.dh[r]) * P.g.W + mrf_iabs(P.g.dw[r])) * P.g.L;
+            if (st > 0x7fffffffLL) step_fits = false;
+        }
+        const bool duo = step_fits && g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= 4096);
         if (ms + 1 <= 8 && duo) {
             P.NW = 1;
             // two index wavefronts while the launch is far from filling the machine

@@ -770,19 +770,27 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     const int vzero = mrf_opaque_zero();
     const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
     const int lastsrc = len - 2;
+    // addresses relative to the head of the scanline: one 32 x 32 bit product per node (the
+    // host has checked that a node step times L fits 32 bits)
+    const int step_l = (int)nstep * L;
+    const int step_w = (int)nstep * P.w_mul;
+    const float *srcb[RMAX];
+#pragma unroll
+    for (int c = 0; c < RMAX; ++c) srcb[c] = src[c] + (size_t)head * L;
+    const float *wb = wbase + (size_t)((head + nstep) * P.w_mul);
     float cur[D][RMAX][LP], nxt[D][RMAX][LP];
     float wcur[D], wnxt[D];
     auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, int nj) {
         nj = nj < lastsrc ? nj : lastsrc;
-        const long long j = head + (long long)nj * nstep;
+        const long long o = (long long)nj * step_l;
 #pragma unroll
         for (int c = 0; c < RMAX; ++c)
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 const int lam = lane + 64 * s;
-                dst[c][s] = src[c][(size_t)j * L + (lam < L ? lam : 0)];
+                dst[c][s] = srcb[c][o + (lam < L ? lam : 0)];
             }
-        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+        wdst = wb[(long long)nj * step_w + vzero];
     };
     if (len >= 2) {
 #pragma unroll
