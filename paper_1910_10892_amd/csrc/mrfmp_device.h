@@ -101,16 +101,32 @@ __device__ inline float mrf_min3(float a, float b, float c)
     return r;
 }
 
-// minimum over the 64 lanes, returned to every lane (wave-uniform)
+// minimum over the 64 lanes, returned to every lane (wave-uniform).
+// Six DPP minima in place: within quads, within half rows, within rows of 16, then the last
+// lane of rows 0 and 2 into rows 1 and 3, then the last lane of row 1 into rows 2 and 3; lane 63
+// ends up with the minimum of all.  Written out because the compiler's own sequence spends
+// four instructions per stage (move, wait, DPP move, min).  Every DPP read of a register that
+// a vector instruction has just written needs two wait states (the s_nop 1 before each).
+// All 64 lanes must be active.
 __device__ inline float mrf_wave_min(float v)
 {
-    v = mrf_min(v, mrf_dpp_f32<0xB1>(v));
-    v = mrf_min(v, mrf_dpp_f32<0x4E>(v));
-    v = mrf_min(v, mrf_dpp_f32<0x141>(v));
-    v = mrf_min(v, mrf_dpp_f32<0x140>(v));
-    const float r0 = mrf_readlane_f32(v, 0), r1 = mrf_readlane_f32(v, 16);
-    const float r2 = mrf_readlane_f32(v, 32), r3 = mrf_readlane_f32(v, 48);
-    return fminf(fminf(r0, r1), fminf(r2, r3));
+    float r;
+    asm("s_nop 1\n\t"
+        "v_min_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_readlane_b32 %0, %1, 63"
+        : "=s"(r), "+v"(v));
+    return r;
 }
 
 // sum over the 64 lanes in a fixed tree order, returned to every lane

@@ -855,6 +855,15 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 a[s] = lam < L ? v : INFINITY;
                 hm = mrf_min(hm, a[s]);
             }
+            // the neighbours' h for the window, requested before the reduction so that the LDS
+            // latency passes behind it (the LDS queue keeps the order: writes above, then reads)
+            mrf_wave_lds_fence();
+            float nb[LP][2 * TW - 1];
+#pragma unroll
+            for (int s = 0; s < LP; ++s)
+#pragma unroll
+                for (int o = 0; o < 2 * TW - 1; ++o)
+                    nb[s][o] = (o == TW - 1) ? a[s] : hbuf[lane + 64 * s + o - (TW - 1)];
             const float hmin = mrf_wave_min(hm);
             if (lane == 0 && !past) { ringw[slot] = wgt; ringhm[slot] = hmin; }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -874,8 +883,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                     for (int o = 0; o < 2 * TW - 1; ++o) {
                         const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
-                        const float hv = (o == TW - 1) ? a[s] : hbuf[lam + o - (TW - 1)];
-                        dl[o] = __builtin_fmaf(wgt, f[dist], hv);
+                        dl[o] = __builtin_fmaf(wgt, f[dist], nb[s][o]);
                     }
                     float W = dl[0];
 #pragma unroll
