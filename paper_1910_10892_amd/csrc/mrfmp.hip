@@ -469,16 +469,18 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256))
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     // few scanlines: the node-to-node chain on a wavefront of its own, helpers around it
-    if (LP <= 2 && !P.gV && ns <= 8 && g_tune_chain != 1 && (g_tune_chain == 2 || P.total_scanlines <= 2048)) {
-        // as many helpers as keep up with the chain while the machine has room for them
-        const int ni = g_tune_chain_ni ? g_tune_chain_ni
-                                       : (P.total_scanlines <= 512 ? 8 : (P.total_scanlines <= 1024 ? 6 : 4));
+    if (!P.gV && ns <= 8 && g_tune_chain != 1 &&
+        (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512))) {
+        // as many helpers as keep up with the chain while the machine and the LDS have room
+        int ni = g_tune_chain_ni ? g_tune_chain_ni
+                                 : (P.total_scanlines <= 512 ? 8 : (P.total_scanlines <= 1024 ? 6 : 4));
         const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
+        while (ni > 2 && mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg) > 64 * 1024) ni -= 2;
 #define MRF_CCASE(lp) \
         if (LP == lp && ns == 1) return launch_bwd_chain<lp, 1, 2>(P, ni, vg, st); \
-        if (LP == lp && ns == 4) return launch_bwd_chain<lp, 4, 2>(P, ni, vg, st); \
+        if (LP == lp && ns == 4) return launch_bwd_chain<lp, 4, (lp <= 2 ? 2 : 1)>(P, ni, vg, st); \
         if (LP == lp && ns == 8) return launch_bwd_chain<lp, 8, 1>(P, ni, vg, st);
-        MRF_CCASE(1) MRF_CCASE(2)
+        MRF_CCASE(1) MRF_CCASE(2) MRF_CCASE(3) MRF_CCASE(4)
 #undef MRF_CCASE
     }
     // few scanlines and many labels: one wavefront per 64 labels

@@ -206,6 +206,8 @@ CHAIN_CASES = [
     (84, "isgmr", 1, 7, 9, 1, DIRS4, 2, False, True),
     (85, "trwp", 1, 1, 11, 20, DIRS16, 2, True, True),      # one row: most scanlines have one node
     (86, "trwp", 1, 9, 2, 65, [(0, 1), (1, 0), (-1, 0)], 3, False, True),
+    (87, "trwp", 1, 4, 30, 200, DIRS4, 2, False, True),     # three and four labels per lane
+    (88, "isgmr", 1, 3, 20, 256, DIRS8, 2, True, False),
 ]
 
 
