@@ -167,6 +167,11 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 4: window sweep with separate value and index wavefronts: 0 = by launch size, 1 = never,
  *           2 = whenever the window sweep applies (knob 2 = 2 takes precedence for L > 64)
  *   knob 5: index wavefronts per scanline in that sweep: 0 = by launch size, 1, 2
+ *   knob 6: backward sweep with the node-to-node chain on its own wavefront: 0 = by launch size,
+ *           1 = never, 2 = whenever it applies (no grad_pairwise asked for)
+ *   knob 7: helper wavefronts per scanline in that sweep: 0 = by launch size, 2, 4, 6, 8
+ *   knob 8: loader wavefront in front of the value wavefront (TRWP, window sweep, two index
+ *           wavefronts): 0 = by launch size, 1 = never, 2 = whenever it applies
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

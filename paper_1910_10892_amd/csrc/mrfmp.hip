@@ -80,6 +80,7 @@ int g_tune_split = 0;      // 0 auto, 1 never, 2 whenever L > 64
 int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
 int g_tune_duo = 0;        // 0 auto, 1 never, 2 whenever the window applies
 int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
+int g_tune_loader = 0;     // loader wavefront in the window sweep: 0 auto, 1 never, 2 whenever possible
 int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
 int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
@@ -148,8 +149,22 @@ hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long 
 {
 #define MRF_W(twv) \
     if (tw == twv) { \
-        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, true, twv, NI>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
-        else hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, false, twv, NI>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, true, twv, NI, false>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, false, twv, NI, false>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2) MRF_W(8) MRF_W(16)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
+// value + loader + two index wavefronts (TRWP, up to three other directions)
+template <int LP>
+hipError_t launch_window_loader(const MrfFwdParams &P, int tw, long long blocks, hipStream_t st)
+{
+#define MRF_W(twv) \
+    if (tw == twv) { \
+        hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, 4, (LP <= 2 ? 4 : 2), true, twv, 2, true>), dim3((unsigned)blocks), dim3(256), 0, st, P); \
         return hipGetLastError(); \
     }
     MRF_W(2) MRF_W(8) MRF_W(16)
@@ -241,6 +256,14 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
             P.NW = 1;
             // two index wavefronts while the launch is far from filling the machine
             const int ni = g_tune_duo_ni ? g_tune_duo_ni : (blocks <= 1536 ? 2 : 1);
+            // TRWP launches that leave SIMDs idle: a loader wavefront in front of the value wavefront
+            if (algo == MRF_TRWP && ms + 1 <= 4 && ni == 2 && g_tune_loader != 1 &&
+                (g_tune_loader == 2 || blocks <= 512)) {
+                if (LPw == 1) return launch_window_loader<1>(P, tw, blocks, st);
+                if (LPw == 2) return launch_window_loader<2>(P, tw, blocks, st);
+                if (LPw == 3) return launch_window_loader<3>(P, tw, blocks, st);
+                if (LPw == 4) return launch_window_loader<4>(P, tw, blocks, st);
+            }
 #define MRF_WCASE(lp) \
             if (LPw == lp && ms + 1 <= 4 && ni == 2) return launch_window_duo<lp, 4, (lp <= 2 ? 4 : 2), 2>(P, algo, tw, blocks, st); \
             if (LPw == lp && ms + 1 <= 4) return launch_window_duo<lp, 4, (lp <= 2 ? 4 : 2), 1>(P, algo, tw, blocks, st); \
@@ -749,6 +772,7 @@ int mrf_tune(int knob, int value)
     if (knob == 4) { g_tune_duo = value; return MRF_OK; }
     if (knob == 5) { g_tune_duo_ni = (value == 1 || value == 2) ? value : 0; return MRF_OK; }
     if (knob == 6) { g_tune_chain = value; return MRF_OK; }
+    if (knob == 8) { g_tune_loader = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

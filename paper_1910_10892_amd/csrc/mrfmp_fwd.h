@@ -587,14 +587,29 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
 // nodes of a scanline in turn (it is somewhat more work per node than the value chain).
 // Nobody meets at a barrier: the producer only waits when the ring is full, a consumer when
 // its next node is not there yet, and every counter only grows, so all waits end.
-template <int LP, int RMAX, int D, bool TRWP, int TW, int NI>
-__global__ void __launch_bounds__(64 * (1 + NI))
+//
+// LOADER (TRWP with at most three other directions) adds a fourth kind of wavefront in front
+// of the value wavefront.  It does the global loads and whatever of h does not need the
+// running message: the partial sum theta + (messages of the directions before r), in the
+// order Eq. trwp is summed, and the vector of r-.  It hands these, the later directions'
+// messages and the weight over through a second ring; the value wavefront then touches LDS
+// only, adds the running message and the later directions to the partial sum (same order,
+// same roundings), and reads the next node's entries while it reduces the current one.
+template <int LP, int RMAX, int D, bool TRWP, int TW, int NI, bool LOADER>
+__global__ void __launch_bounds__(64 * ((LOADER ? 2 : 1) + NI))
 mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 {
+    static_assert(!LOADER || (TRWP && RMAX == 4), "loader wavefront: TRWP with up to three other directions");
+    constexpr int NW0 = LOADER ? 2 : 1;           // wavefronts in front of the index wavefronts
+    constexpr int NRL = 8;                        // slots of the loader's ring (a power of two, >= D)
+    constexpr int LL = 64 * LP;
+    __shared__ float lring[LOADER ? NRL : 1][5][LOADER ? LL : 1];   // partial sum, 3 messages, r- vector
+    __shared__ float lw[NRL];
+    __shared__ int loaded;                        // last step the loader has published
     constexpr int HB = 64 * LP + 2 * TW;          // h with TW entries of padding on both sides
     constexpr int NR = 8;                         // ring slots (a power of two, >= D)
     static_assert(NR >= D && (NR & (NR - 1)) == 0 && NI <= 4, "ring depth");
-    constexpr int NT = 64 * (1 + NI);
+    constexpr int NT = 64 * (NW0 + NI);
     __shared__ float ring[NR][HB];
     __shared__ float ringw[NR], ringhm[NR];
     __shared__ float ftab[TW + 1];
@@ -602,7 +617,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     __shared__ __align__(16) int consumed[4];     // per index wavefront: last step finished
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
-    const bool index_wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) > 0;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const bool index_wave = wave >= NW0;
 
     const long long blk = blockIdx.x;
     int ri = 0;
@@ -629,14 +645,14 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     if ((int)threadIdx.x <= TW) ftab[threadIdx.x] = (int)threadIdx.x < TW ? P.V[(int)threadIdx.x < L ? threadIdx.x : L - 1] : fT;
     // padding and the entries of labels >= L are never written again: they never win a strict '<'
     for (int i = threadIdx.x; i < NR * HB; i += NT) (&ring[0][0])[i] = INFINITY;
-    if (threadIdx.x == 0) produced = 0;
+    if (threadIdx.x == 0) { produced = 0; loaded = 0; }
     // index wavefront j takes steps 1 + j, 1 + j + NI, ...; "finished" starts one turn before
     if (threadIdx.x < 4) consumed[threadIdx.x] = (int)threadIdx.x + 1 - NI;
     __syncthreads();
 
     if (index_wave) {
         // ---- p, q and all stores -----------------------------------------------------------
-        const int jw = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) - 1;
+        const int jw = wave - NW0;
         if (jw == 0) {
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
@@ -792,15 +808,223 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             }
         wdst = wb[(long long)nj * step_w + vzero];
     };
-    if (len >= 2) {
+    if (LOADER && wave == 1) {
+        // ---- loads and the part of h that does not wait for the running message -----------
+        float before[RMAX];                   // sources summed before the running message
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+        for (int c = 1; c < RMAX; ++c) before[c] = ((c <= n_pre && c <= n_src) ? 1.0f : 0.0f) + vz;
+        if (len >= 2) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+        }
+        int pseen = 0;
+        for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int nn = n0 + u;
+                if (nn < len) {
+                    // the slot was last read for step nn - NRL, before that step was published
+                    while (pseen < nn - NRL) {
+                        pseen = __builtin_amdgcn_readfirstlane(
+                            __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                        if (pseen < nn - NRL) __builtin_amdgcn_s_sleep(1);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                    const int ls = nn & (NRL - 1);
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        float v = cur[u][0][s];
+                        float mrm = 0.0f;
+#pragma unroll
+                        for (int c = 1; c < RMAX; ++c) {
+                            v = __builtin_fmaf(before[c], cur[u][c][s], v);
+                            mrm = __builtin_fmaf(is_rm[c], cur[u][c][s], mrm);
+                            lring[ls][c][lane + 64 * s] = cur[u][c][s];
+                        }
+                        lring[ls][0][lane + 64 * s] = v;
+                        lring[ls][4][lane + 64 * s] = mrm;
+                    }
+                    if (lane == 0) lw[ls] = wcur[u];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane == 0) __hip_atomic_store(&loaded, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                wcur[u] = wnxt[u];
+#pragma unroll
+                for (int c = 0; c < RMAX; ++c)
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) cur[u][c][s] = nxt[u][c][s];
+            }
+        }
+        return;
     }
 
     float carry[LP];
 #pragma unroll
     for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
     int freed = 0;          // every step <= freed is finished (a possibly stale, hence conservative, view)
+
+    if (LOADER) {
+        // ---- values, fed by the loader -------------------------------------------------------
+        float after[RMAX];                    // sources summed after the running message
+#pragma unroll
+        for (int c = 1; c < RMAX; ++c) after[c] = ((c > n_pre && c <= n_src) ? 1.0f : 0.0f) + vz;
+        auto await_loader = [&](int nn) {
+            int sn;
+            do {
+                sn = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&loaded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (sn < nn) __builtin_amdgcn_s_sleep(1);
+            } while (sn < nn);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            return sn;
+        };
+        float in[5][LP], wgt = 0.0f;
+        int lseen = 0;
+        if (len >= 2) {
+            lseen = await_loader(1);
+#pragma unroll
+            for (int c = 0; c < 5; ++c)
+#pragma unroll
+                for (int s = 0; s < LP; ++s) in[c][s] = lring[1][c][lane + 64 * s];
+            wgt = lw[1];
+        }
+        for (int nn = 1; nn < len; ++nn) {
+            const int slot = nn & (NR - 1);
+            float *hbuf = &ring[slot][TW];
+            while (freed < nn - NR) {
+                int lo = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+#pragma unroll
+                for (int j = 1; j < NI; ++j) {
+                    const int cj = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(&consumed[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    lo = cj < lo ? cj : lo;
+                }
+                freed = lo + NI - 1;
+                if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+            float a[LP];
+            float hm = INFINITY;
+#pragma unroll
+            for (int s = 0; s < LP; ++s) {
+                float v = in[0][s] + carry[s];
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(after[c], in[c][s], v);
+                v = rho * v;
+                v = v - in[4][s];
+                const int lam = lane + 64 * s;
+                if (lam < L) hbuf[lam] = v;
+                a[s] = lam < L ? v : INFINITY;
+                hm = mrf_min(hm, a[s]);
+            }
+            mrf_wave_lds_fence();
+            float nb[LP][2 * TW - 1];
+#pragma unroll
+            for (int s = 0; s < LP; ++s)
+#pragma unroll
+                for (int o = 0; o < 2 * TW - 1; ++o)
+                    nb[s][o] = (o == TW - 1) ? a[s] : hbuf[lane + 64 * s + o - (TW - 1)];
+            // the next node's entries, in the same batch of LDS reads; if the loader's counter
+            // (read first: the LDS queue keeps the order) does not cover them yet, they are read
+            // again after waiting
+            const bool more = nn + 1 < len;
+            const bool ask = more && lseen < nn + 1;
+            const int lsn = (nn + 1) & (NRL - 1);
+            int flag = lseen;
+            if (ask) flag = __hip_atomic_load(&loaded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            float nin[5][LP];
+#pragma unroll
+            for (int c = 0; c < 5; ++c)
+#pragma unroll
+                for (int s = 0; s < LP; ++s) nin[c][s] = lring[lsn][c][lane + 64 * s];
+            float nwgt = lw[lsn];
+
+            const float hmin = mrf_wave_min(hm);
+            if (lane == 0) { ringw[slot] = wgt; ringhm[slot] = hmin; }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_wave_barrier();
+            if (lane == 0) __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (ask) {
+                lseen = __builtin_amdgcn_readfirstlane(flag);
+                if (lseen < nn + 1) {
+                    lseen = await_loader(nn + 1);
+#pragma unroll
+                    for (int c = 0; c < 5; ++c)
+#pragma unroll
+                        for (int s = 0; s < LP; ++s) nin[c][s] = lring[lsn][c][lane + 64 * s];
+                    nwgt = lw[lsn];
+                }
+            }
+
+            float tv[LP];
+            float tq;
+            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float dl[2 * TW - 1];
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o) {
+                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                        dl[o] = __builtin_fmaf(wgt, f[dist], nb[s][o]);
+                    }
+                    float W = dl[0];
+#pragma unroll
+                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
+                    tv[s] = (lam < L) ? mrf_min(W, gmin) : INFINITY;
+                }
+                if (f0zero) {
+                    tq = hmin;
+                } else {
+                    float mn = INFINITY;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                    tq = mrf_wave_min(mn);
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < LP; ++s) {
+                    const int lam = lane + 64 * s;
+                    float best = INFINITY;
+                    for (int mu = 0; mu < L; ++mu) {
+                        int dist = mu > lam ? mu - lam : lam - mu;
+                        dist = dist < TW ? dist : TW;
+                        const float dlt = __builtin_fmaf(wgt, ftab[dist], hbuf[mu]);
+                        if (dlt < best) best = dlt;
+                    }
+                    tv[s] = (lam < L) ? best : INFINITY;
+                }
+                float mn = INFINITY;
+#pragma unroll
+                for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                tq = mrf_wave_min(mn);
+            }
+#pragma unroll
+            for (int s = 0; s < LP; ++s) carry[s] = (lane + 64 * s < L) ? tv[s] - tq : 0.0f;
+            wgt = nwgt;
+#pragma unroll
+            for (int c = 0; c < 5; ++c)
+#pragma unroll
+                for (int s = 0; s < LP; ++s) in[c][s] = nin[c][s];
+        }
+        return;
+    }
+
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
 
     for (int n0 = 1; n0 < len; n0 += D) {
 #pragma unroll

@@ -184,14 +184,16 @@ def test_window_path_is_exact(oracle, case):
         got["single"] = full_check(oracle, pr)
         assert mrf.mrf_tune(4, 2) == 0 and mrf.mrf_tune(5, 1) == 0      # value + one index wavefront
         got["pair"] = full_check(oracle, pr)
-        assert mrf.mrf_tune(5, 2) == 0                                  # value + two index wavefronts
+        assert mrf.mrf_tune(5, 2) == 0 and mrf.mrf_tune(8, 1) == 0      # value + two index wavefronts
         got["trio"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(8, 2) == 0                                  # and a loader wavefront (TRWP)
+        got["quad"] = full_check(oracle, pr)
         assert mrf.mrf_tune(2, 2) == 0                                  # one wavefront per 64 labels
         got["split"] = full_check(oracle, pr)
         assert mrf.mrf_tune(1, 1) == 0                                  # dense sweep
         d = run_gpu(pr)
     finally:
-        for knob in (1, 2, 4, 5):
+        for knob in (1, 2, 4, 5, 8):
             mrf.mrf_tune(knob, 0)
     for layout, g in got.items():
         for name in ("p", "q", "labels", "cost", "messages"):
