@@ -151,6 +151,11 @@ const char *mrf_strerror(int status);
  * library owns the string. */
 const char *mrf_last_error_detail(void);
 
+/* Name of the kernel template that the most recent forward (backward = 0) or backward
+ * (backward != 0) call launched for its last scanline sweep, "" before the first call: which
+ * of the sweep layouts the launch-size rules picked.  For reports; process-global. */
+const char *mrf_last_sweep_kernel(int backward);
+
 /* Profiling hook: while set (both non-NULL hipEvent_t handles), every forward or backward
  * call records `start_event` on its stream just before its first scanline-sweep launch and
  * `stop_event` just after its last one, so a caller can time the sweeps apart from the

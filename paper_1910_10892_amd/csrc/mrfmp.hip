@@ -86,6 +86,7 @@ int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 char g_error_detail[256] = "";
+const char *g_last_sweep[2] = {"", ""};      // kernel of the last forward / backward sweep launch
 
 // records which call failed and how, for mrf_last_error_detail
 int hip_fail(hipError_t e, const char *what)
@@ -102,6 +103,7 @@ inline void mark(hipEvent_t ev, hipStream_t st)
 template <int LP, int MCH, int RMAX, int D>
 hipError_t launch_fwd(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
+    g_last_sweep[0] = "mrf_fwd_sweep";
     constexpr int NWMAX = (64 * LP + MCH - 1) / MCH;
     const size_t lds = (size_t)NWMAX * NWMAX * MCH * sizeof(float) +
                        (NWMAX > 1 ? (size_t)2 * NWMAX * 64 * LP * sizeof(float2) : 0);
@@ -133,6 +135,7 @@ int pick_mch(int L, int LP, bool many_sources)
 template <int LP, int RMAX, int D>
 hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
+    g_last_sweep[0] = "mrf_fwd_sweep_window";
 #define MRF_W(twv) \
     if (tw == twv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, true, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
@@ -147,6 +150,7 @@ hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long bloc
 template <int LP, int RMAX, int D, int NI>
 hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
+    g_last_sweep[0] = "mrf_fwd_sweep_window_duo";
 #define MRF_W(twv) \
     if (tw == twv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, true, twv, NI, false>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
@@ -162,6 +166,7 @@ hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long 
 template <int LP>
 hipError_t launch_window_loader(const MrfFwdParams &P, int tw, long long blocks, hipStream_t st)
 {
+    g_last_sweep[0] = "mrf_fwd_sweep_window_duo";
 #define MRF_W(twv) \
     if (tw == twv) { \
         hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, 4, (LP <= 2 ? 4 : 2), true, twv, 2, true>), dim3((unsigned)blocks), dim3(256), 0, st, P); \
@@ -175,6 +180,7 @@ hipError_t launch_window_loader(const MrfFwdParams &P, int tw, long long blocks,
 template <int RMAX, int D>
 hipError_t launch_window_split(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
+    g_last_sweep[0] = "mrf_fwd_sweep_window_split";
     const unsigned threads = 64u * (unsigned)((P.g.L + 63) / 64);
 #define MRF_W(twv) \
     if (tw == twv) { \
@@ -204,6 +210,7 @@ int window_width(const mrf_problem *pr)
 template <int SEG>
 hipError_t launch_packed(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
 {
+    g_last_sweep[0] = "mrf_fwd_sweep_packed";
     const unsigned blocks = (unsigned)((scanlines + 64 / SEG - 1) / (64 / SEG));
 #define MRF_P(rm, d) \
     if (rmax == rm) { \
@@ -412,6 +419,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
 template <int LP, int NS, int D>
 hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
+    g_last_sweep[1] = "mrf_bwd_sweep";
     const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_WAVES);
     if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false>), grid, block, lds, st, P);
@@ -425,6 +433,7 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
 template <int NS, int D>
 hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
+    g_last_sweep[1] = "mrf_bwd_sweep_split";
     const dim3 grid((unsigned)blocks), block(64u * (unsigned)((P.g.L + 63) / 64));
     if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep_split<NS, D, true>), grid, block, lds, st, P);
@@ -436,6 +445,7 @@ hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds,
 template <int LP, int NS, int D>
 hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t st)
 {
+    g_last_sweep[1] = "mrf_bwd_sweep_chain";
     const dim3 grid((unsigned)P.total_scanlines);
     const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
@@ -453,6 +463,7 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
 template <int SEG>
 hipError_t launch_bwd_packed(const MrfBwdParams &P, int ns, hipStream_t st)
 {
+    g_last_sweep[1] = "mrf_bwd_sweep_packed";
     constexpr int NSEG = 64 / SEG;
     const int L = P.g.L;
     long long blocks = (P.total_scanlines + NSEG - 1) / NSEG;
@@ -753,6 +764,8 @@ const char *mrf_strerror(int status)
 }
 
 const char *mrf_last_error_detail(void) { return g_error_detail; }
+
+const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ? 1 : 0]; }
 
 const char *mrf_version(void) { return "0.1.0"; }
 

@@ -84,6 +84,8 @@ def load_library():
     lib.mrf_strerror.restype = ctypes.c_char_p
     lib.mrf_last_error_detail.restype = ctypes.c_char_p
     lib.mrf_last_error_detail.argtypes = []
+    lib.mrf_last_sweep_kernel.restype = ctypes.c_char_p
+    lib.mrf_last_sweep_kernel.argtypes = [ci]
     lib.mrf_strerror.argtypes = [ci]
     lib.mrf_version.restype = ctypes.c_char_p
     lib.mrf_set_sweep_events.restype = ci
@@ -159,6 +161,10 @@ def mrf_strerror(status: int) -> str:
 
 def mrf_last_error_detail() -> str:
     return load_library().mrf_last_error_detail().decode()
+
+
+def mrf_last_sweep_kernel(backward: bool) -> str:
+    return load_library().mrf_last_sweep_kernel(1 if backward else 0).decode()
 
 
 def mrf_version() -> str:
