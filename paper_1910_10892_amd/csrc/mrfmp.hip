@@ -503,7 +503,13 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256))
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     // few scanlines: the node-to-node chain on a wavefront of its own, helpers around it
-    if (!P.gV && ns <= 8 && g_tune_chain != 1 &&
+    // (its addressing wants a node step times L in 32 bits)
+    bool step_fits = true;
+    for (int r = P.r_first; r < P.r_first + P.r_count; ++r) {
+        const long long stp = ((long long)mrf_iabs(P.g.dh[r]) * P.g.W + mrf_iabs(P.g.dw[r])) * L;
+        if (stp > 0x7fffffffLL) step_fits = false;
+    }
+    if (step_fits && !P.gV && ns <= 8 && g_tune_chain != 1 &&
         (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512))) {
         // as many helpers as keep up with the chain while the machine and the LDS have room
         int ni = g_tune_chain_ni ? g_tune_chain_ni

@@ -528,25 +528,40 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     float ucur[D][LP], unxt[D][LP];
     int pcur[D][LP], pnxt[D][LP];
     int qcur[D], qnxt[D];
+    // addresses relative to the head of the scanline: one 32 x 32 bit product per node (the
+    // host has checked that a node step times L fits 32 bits)
+    const int step_l = (int)nstep * L;
+    const int step_n = (int)nstep;
+    const float *srcb[NS];
+#pragma unroll
+    for (int c = 0; c < NS; ++c) srcb[c] = src[c] + (size_t)head * L;
+    const float *gub = P.gunary + (size_t)head * L * umul;
+    const int step_u = unary_old ? step_l : 0;
+    const uint8_t *pb = pbase + (size_t)head * L;
+    const uint8_t *qb = qbase + (size_t)head;
     auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, int it) {
         int n = len - 1 - (jw + it * NI);
         n = n > 0 ? n : 0;
-        const long long i = head + (long long)n * nstep;
+        const long long o = (long long)n * step_l;
+        const long long ou = (long long)n * step_u;
 #pragma unroll
         for (int s = 0; s < LP; ++s) {
             const int lam = lane + 64 * s;
             const int lc = lam < L ? lam : 0;
 #pragma unroll
-            for (int c = 0; c < NS; ++c) dst[c][s] = src[c][(size_t)i * L + lc];
-            udst[s] = P.gunary[((size_t)i * L + lc) * umul];   // one cached word unless it is needed
-            pdst[s] = pbase[(size_t)i * L + lc];
+            for (int c = 0; c < NS; ++c) dst[c][s] = srcb[c][o + lc];
+            udst[s] = gub[ou + (unary_old ? lc : 0)];      // one cached word unless it is needed
+            pdst[s] = pb[o + lc];
         }
-        qdst = qbase[(size_t)i + vzero];
+        qdst = qb[(long long)n * step_n + vzero];
     };
     if (T > 0) {
 #pragma unroll
         for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], u);
     }
+    float *guw = P.gunary + (size_t)head * L;                       // stores of stage "post"
+    float *sw = P.S + ((size_t)r * N + head) * L;
+    float *gww = P.gw ? P.gw + (size_t)r * N + head : nullptr;
 
     int chain_seen = -1;
     for (int it0 = 0; it0 < T + 1 && T > 0; it0 += D) {
@@ -603,16 +618,16 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                 const int slot = tp % NR;
                 const int n = len - 1 - tp;
                 const bool update = n > 0;             // node i has a predecessor: its update is replayed
-                const long long i = head + (long long)n * nstep;
-                const long long j = i - nstep;
+                const long long oi = (long long)n * step_l;              // node i, in label entries from the head
+                const long long oj = oi - step_l;                        // node i - r
                 double acc = 0.0;
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
                     const double cin = b_cin[slot * LL + lam];
                     if (own_unary && lam < L)
-                        P.gunary[(size_t)i * L + lam] = (float)(cin + (double)a_extT[slot * LL + lam]);
-                    if (update && lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)b_sv[slot * LL + lam];
+                        guw[oi + lam] = (float)(cin + (double)a_extT[slot * LL + lam]);
+                    if (update && lam < L) sw[oj + lam] = (float)b_sv[slot * LL + lam];
                     if (P.gw && lam < L) {
                         const double g = cin + a_ext[slot * LL + lam];    // as the chain formed it
                         const int pv = a_p[slot * LL + lam];
@@ -630,7 +645,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     acc = mrf_wave_sum_f64(acc);
                     // one writer per entry and launch: a no-return atomic is a plain accumulate
                     if (update && lane == 0)
-                        __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
+                        __hip_atomic_fetch_add(&gww[(long long)n * step_n], (float)acc, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
