@@ -636,7 +636,9 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
             { const hipError_t e_ = dispatch_bwd(P, pr->pairwise_kind, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_bwd"); }
             C.first = (k == K - 1);
             C.ghat = (k > 0) ? buf0 : nullptr;
-            hipLaunchKernelGGL(mrf_isgmr_bwd_combine, dim3((unsigned)cblocks), dim3(256), 0, st, C);
+            if (R <= 4) hipLaunchKernelGGL(mrf_isgmr_bwd_combine<4>, dim3((unsigned)cblocks), dim3(256), 0, st, C);
+            else if (R <= 8) hipLaunchKernelGGL(mrf_isgmr_bwd_combine<8>, dim3((unsigned)cblocks), dim3(256), 0, st, C);
+            else hipLaunchKernelGGL(mrf_isgmr_bwd_combine<16>, dim3((unsigned)cblocks), dim3(256), 0, st, C);
             { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
         }
     } else {

@@ -1054,16 +1054,18 @@ struct MrfCombineParams {
     int first;               // first processed iteration: grad theta starts from grad c
 };
 
+// RT: number of directions rounded up to 4, 8 or 16 (the loops below are unrolled to it)
+template <int RT>
 __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombineParams P)
 {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < P.NL; e += stride) {
         // every s^r_i is read once; sums are formed in double, where removing the two excluded
         // directions from the total loses nothing that float storage would keep
-        double sv[MRF_MAXR];
+        double sv[RT];
         double tot = 0.0;
 #pragma unroll
-        for (int r = 0; r < MRF_MAXR; ++r) {
+        for (int r = 0; r < RT; ++r) {
             sv[r] = (r < P.R) ? (double)P.S[(size_t)r * P.NL + e] : 0.0;
             tot += sv[r];
         }
@@ -1071,11 +1073,11 @@ __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombinePar
         P.gunary[e] = (float)(base + tot);
         if (P.ghat) {
 #pragma unroll
-            for (int d = 0; d < MRF_MAXR; ++d) {
+            for (int d = 0; d < RT; ++d) {
                 if (d < P.R) {
                     double v = tot - sv[d];
 #pragma unroll
-                    for (int r = 0; r < MRF_MAXR; ++r)
+                    for (int r = 0; r < RT; ++r)
                         if (r == P.opp[d]) v -= sv[r];
                     P.ghat[(size_t)d * P.NL + e] = (float)v;
                 }
