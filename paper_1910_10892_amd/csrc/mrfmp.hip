@@ -628,6 +628,11 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         C.S = buf1; C.gc = grad_cost; C.gunary = grad_unary;
         long long cblocks = (NL + 255) / 256;
         if (cblocks > 32768) cblocks = 32768;
+        // four entries per thread where every array starts on a 16-byte boundary
+        const bool cvec = (NL % 4 == 0) && (((uintptr_t)buf0 | (uintptr_t)buf1 | (uintptr_t)grad_cost | (uintptr_t)grad_unary) % 16 == 0);
+        long long cblocks4 = (NL / 4 + 255) / 256;
+        if (cblocks4 > 32768) cblocks4 = 32768;
+        if (cblocks4 < 1) cblocks4 = 1;
         for (int k = K - 1; k >= 0; --k) {
             if (k == K - 1) { P.src_base = grad_cost; P.src_stride = 0; }   // back Eq. isgmr-aggregation
             else { P.src_base = buf0; P.src_stride = NL; }
@@ -636,9 +641,12 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
             { const hipError_t e_ = dispatch_bwd(P, pr->pairwise_kind, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_bwd"); }
             C.first = (k == K - 1);
             C.ghat = (k > 0) ? buf0 : nullptr;
-            if (R <= 4) hipLaunchKernelGGL(mrf_isgmr_bwd_combine<4>, dim3((unsigned)cblocks), dim3(256), 0, st, C);
-            else if (R <= 8) hipLaunchKernelGGL(mrf_isgmr_bwd_combine<8>, dim3((unsigned)cblocks), dim3(256), 0, st, C);
-            else hipLaunchKernelGGL(mrf_isgmr_bwd_combine<16>, dim3((unsigned)cblocks), dim3(256), 0, st, C);
+            const dim3 cg((unsigned)(cvec ? cblocks4 : cblocks)), cb(256);
+            if (R <= 4 && cvec) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<4, 4>), cg, cb, 0, st, C);
+            else if (R <= 4) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<4, 1>), cg, cb, 0, st, C);
+            else if (R <= 8 && cvec) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<8, 4>), cg, cb, 0, st, C);
+            else if (R <= 8) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<8, 1>), cg, cb, 0, st, C);
+            else hipLaunchKernelGGL((mrf_isgmr_bwd_combine<16, 1>), cg, cb, 0, st, C);
             { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
         }
     } else {

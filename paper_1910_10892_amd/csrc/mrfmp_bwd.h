@@ -1054,34 +1054,47 @@ struct MrfCombineParams {
     int first;               // first processed iteration: grad theta starts from grad c
 };
 
-// RT: number of directions rounded up to 4, 8 or 16 (the loops below are unrolled to it)
-template <int RT>
+// RT: number of directions rounded up to 4, 8 or 16 (the loops below are unrolled to it);
+// VEC: consecutive entries per thread (4 needs N*L divisible by 4 and 16-byte aligned arrays)
+template <int RT, int VEC>
 __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombineParams P)
 {
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < P.NL; e += stride) {
+    typedef float vecf __attribute__((ext_vector_type(VEC)));
+    const long long stride = (long long)gridDim.x * blockDim.x * VEC;
+    for (long long e = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * VEC; e < P.NL; e += stride) {
         // every s^r_i is read once; sums are formed in double, where removing the two excluded
         // directions from the total loses nothing that float storage would keep
-        double sv[RT];
-        double tot = 0.0;
+        vecf sraw[RT];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            sv[r] = (r < P.R) ? (double)P.S[(size_t)r * P.NL + e] : 0.0;
-            tot += sv[r];
-        }
-        const double base = (double)(P.first ? P.gc[e] : P.gunary[e]);
-        P.gunary[e] = (float)(base + tot);
-        if (P.ghat) {
+        for (int r = 0; r < RT; ++r)
+            sraw[r] = (r < P.R) ? *reinterpret_cast<const vecf *>(P.S + (size_t)r * P.NL + e) : vecf(0.0f);
+        const vecf braw = *reinterpret_cast<const vecf *>((P.first ? P.gc : P.gunary) + e);
+        vecf uout;
+        vecf gout[RT];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            double sv[RT];
+            double tot = 0.0;
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                sv[r] = (double)sraw[r][v];
+                tot += sv[r];
+            }
+            uout[v] = (float)((double)braw[v] + tot);
 #pragma unroll
             for (int d = 0; d < RT; ++d) {
-                if (d < P.R) {
-                    double v = tot - sv[d];
+                double g = tot - sv[d];
 #pragma unroll
-                    for (int r = 0; r < RT; ++r)
-                        if (r == P.opp[d]) v -= sv[r];
-                    P.ghat[(size_t)d * P.NL + e] = (float)v;
-                }
+                for (int r = 0; r < RT; ++r)
+                    if (r == P.opp[d]) g -= sv[r];
+                gout[d][v] = (float)g;
             }
+        }
+        *reinterpret_cast<vecf *>(P.gunary + e) = uout;
+        if (P.ghat) {
+#pragma unroll
+            for (int d = 0; d < RT; ++d)
+                if (d < P.R) *reinterpret_cast<vecf *>(P.ghat + (size_t)d * P.NL + e) = gout[d];
         }
     }
 }
