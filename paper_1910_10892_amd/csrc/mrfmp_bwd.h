@@ -193,7 +193,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 for (int s = 0; s < LP; ++s) {
                     double acc = carry[s];
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) acc += cG[c] * (double)cur[u][c][s];
+                    for (int c = 0; c < NS; ++c) acc = __builtin_fma(cG[c], (double)cur[u][c][s], acc);
                     g[s] = (lane + 64 * s < L) ? acc : 0.0;
                 }
                 if (own_unary) {
@@ -202,7 +202,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     for (int s = 0; s < LP; ++s) {
                         double accT = carry[s];
 #pragma unroll
-                        for (int c = 0; c < NS; ++c) accT += cT[c] * (double)cur[u][c][s];
+                        for (int c = 0; c < NS; ++c) accT = __builtin_fma(cT[c], (double)cur[u][c][s], accT);
                         accT += unary_old ? (double)ucur[u][s] : 0.0;   // (the buffer may hold anything at first)
                         if (!past && lane + 64 * s < L) P.gunary[(size_t)i * L + lane + 64 * s] = (float)accT;
                     }
@@ -294,7 +294,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                                 const int dist = pv[s] > lam ? pv[s] - lam : lam - pv[s];
                                 vv = vl[P.v_mode == 1 ? pv[s] * L + lam : dist];
                             }
-                            acc += g[s] * (double)vv;
+                            acc = __builtin_fma(g[s], (double)vv, acc);
                         }
                     }
                     acc = mrf_wave_sum_f64(acc);
@@ -310,7 +310,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     for (int s = 0; s < LP; ++s) {
                         const int lam = lane + 64 * s;
                         if (update && lam < L) {
-                            if (P.gv_lds) gvl[pv[s] * L + lam] += wgt * g[s];
+                            if (P.gv_lds) gvl[pv[s] * L + lam] = __builtin_fma(wgt, g[s], gvl[pv[s] * L + lam]);
                             else __hip_atomic_fetch_add(&gVs[(size_t)pv[s] * L + lam], wgt * g[s],
                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
@@ -773,12 +773,12 @@ __global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
 
                 double g = carry;
 #pragma unroll
-                for (int c = 0; c < NS; ++c) g += cG[c] * (double)cur[u][c];
+                for (int c = 0; c < NS; ++c) g = __builtin_fma(cG[c], (double)cur[u][c], g);
                 g = valid ? g : 0.0;
                 if (own_unary) {
                     double accT = carry;
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) accT += cT[c] * (double)cur[u][c];
+                    for (int c = 0; c < NS; ++c) accT = __builtin_fma(cT[c], (double)cur[u][c], accT);
                     accT += unary_old ? (double)ucur[u] : 0.0;
                     if (!past && valid) P.gunary[(size_t)i * L + lam] = (float)accT;
                 }
@@ -991,12 +991,12 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
 
                 double g = carry;
 #pragma unroll
-                for (int c = 0; c < NS; ++c) g += cG[c] * (double)cur[u][c];
+                for (int c = 0; c < NS; ++c) g = __builtin_fma(cG[c], (double)cur[u][c], g);
                 g = valid ? g : 0.0;
                 {
                     double accT = carry;
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) accT += cT[c] * (double)cur[u][c];
+                    for (int c = 0; c < NS; ++c) accT = __builtin_fma(cT[c], (double)cur[u][c], accT);
                     accT += unary_old ? (double)ucur[u] : 0.0;
                     if (own_unary && !past && valid) P.gunary[(size_t)i * L + lam] = (float)accT;
                 }
@@ -1022,7 +1022,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
                         __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
                 }
-                if (gVs && update && valid) gvl[pv * L + lam] += wgt * g;
+                if (gVs && update && valid) gvl[pv * L + lam] = __builtin_fma(wgt, g, gvl[pv * L + lam]);
             }
 #pragma unroll
             for (int u = 0; u < D; ++u) {
