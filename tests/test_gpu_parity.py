@@ -167,6 +167,9 @@ WINDOW_CASES = [
     (50, "trwp", 3, 41, 96, DIRS4, 2, 1, 8.0, False, "pos"),
     (51, "isgmr", 2, 37, 40, DIRS8, 2, 1, 2.0, True, "zero_mix"),
     (52, "trwp", 2, 33, 70, DIRS4, 2, 2, 30.0, True, "neg_mix"),
+    (53, "trwp", 1, 12, 40, DIRS8, 2, 1, 2.0, False, "pos"),       # one row: vertical and diagonal scanlines of one node
+    (54, "trwp", 5, 6, 96, [(0, 1), (1, 0), (-1, 0)], 3, 1, 8.0, False, "pos"),   # a direction without its opposite
+    (55, "isgmr", 6, 1, 33, DIRS4, 2, 1, 4.0, True, "zero_mix"),   # one column
 ]
 
 
