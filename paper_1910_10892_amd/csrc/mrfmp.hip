@@ -81,6 +81,8 @@ int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
 int g_tune_duo = 0;        // 0 auto, 1 never, 2 whenever the window applies
 int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
 int g_tune_loader = 0;     // loader wavefront in the window sweep: 0 auto, 1 never, 2 whenever possible
+int g_tune_squad = 0;      // index wavefronts next to the split layout: 0 by launch size, 1 never, 2 always
+int g_tune_squad_ni = 0;   // how many: 0 auto, 4, 8
 int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
 int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
@@ -193,6 +195,22 @@ hipError_t launch_window_split(const MrfFwdParams &P, int algo, int tw, long lon
     return hipErrorInvalidValue;
 }
 
+template <int RMAX, int D>
+hipError_t launch_window_squad(const MrfFwdParams &P, int algo, int tw, int ni, long long blocks, hipStream_t st)
+{
+    g_last_sweep[0] = "mrf_fwd_sweep_window_squad";
+    const unsigned nwv = (unsigned)((P.g.L + 63) / 64);
+#define MRF_W(twv, niv) \
+    if (tw == twv && ni == niv) { \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_squad<RMAX, D, true, twv, niv>), dim3((unsigned)blocks), dim3(64u * (nwv + niv)), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_window_squad<RMAX, D, false, twv, niv>), dim3((unsigned)blocks), dim3(64u * (nwv + niv)), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2, 4) MRF_W(8, 4) MRF_W(16, 4) MRF_W(2, 8) MRF_W(8, 8) MRF_W(16, 8)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
 // Distance from which a truncated pairwise function is constant, or 0 if the window
 // kernel does not apply (dense kind, no truncation inside the label range, wide window).
 int window_width(const mrf_problem *pr)
@@ -245,6 +263,13 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         // (wide windows over many labels only: otherwise the value/index pair below is faster)
         const bool split = LPw > 1 && g_tune_split != 1 &&
                            (g_tune_split == 2 || (LPw >= 3 && tw >= 8 && blocks * LPw <= 4096));
+        if (ms + 1 <= 8 && split && g_tune_squad != 1 && (g_tune_squad == 2 || blocks <= 512)) {
+            // the value wavefronts of the split layout, with the index work on wavefronts of their own
+            P.NW = LPw;
+            const int ni = (g_tune_squad_ni == 4 || g_tune_squad_ni == 8) ? g_tune_squad_ni : 8;
+            if (ms + 1 <= 4) return launch_window_squad<4, 4>(P, algo, tw, ni, blocks, st);
+            return launch_window_squad<8, 2>(P, algo, tw, ni, blocks, st);
+        }
         if (ms + 1 <= 8 && split) {
             P.NW = LPw;
             if (ms + 1 <= 4) return launch_window_split<4, 4>(P, algo, tw, blocks, st);
@@ -802,6 +827,8 @@ int mrf_tune(int knob, int value)
     if (knob == 5) { g_tune_duo_ni = (value == 1 || value == 2) ? value : 0; return MRF_OK; }
     if (knob == 6) { g_tune_chain = value; return MRF_OK; }
     if (knob == 8) { g_tune_loader = value; return MRF_OK; }
+    if (knob == 9) { g_tune_squad = value; return MRF_OK; }
+    if (knob == 10) { g_tune_squad_ni = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

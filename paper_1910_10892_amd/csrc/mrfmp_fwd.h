@@ -1384,6 +1384,353 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
     }
 }
 
+// ---- window sweep: value wavefronts per 64 labels, index wavefronts per node -----------------
+//
+// Both ideas above together, for wide windows over many labels in small launches.  NWV =
+// ceil(L/64) value wavefronts walk the scanline in lock step as in mrf_fwd_sweep_window_split
+// but compute the values of the new message only; NI index wavefronts take the nodes in
+// turn as in mrf_fwd_sweep_window_duo, each doing the argmin bookkeeping of a whole node (all
+// labels) and the stores.  The value wavefronts publish h through a ring; all of a node's
+// entries are written before the node's barrier, so the wavefront that raises the counter
+// after the barrier needs no further wait.
+template <int RMAX, int D, bool TRWP, int TW, int NI>
+__global__ void __launch_bounds__(64 * (4 + NI))
+mrf_fwd_sweep_window_squad(const MrfFwdParams P)
+{
+    constexpr int HB = 256 + 2 * TW;
+    constexpr int NR = 8;                          // ring slots
+    constexpr int LPI = 4;                         // label slots of an index wavefront
+    static_assert(NR >= D && (NR & (NR - 1)) == 0 && NI >= 1 && NI <= 8, "ring depth");
+    __shared__ float ring[NR][HB];
+    __shared__ float ringw[NR];
+    __shared__ float ftab[TW + 1];
+    // exchanges among the value wavefronts: {step, float} per wavefront, two sets by step parity
+    __shared__ __align__(16) unsigned long long hmx[2][4];     // local minima of h
+    __shared__ __align__(16) unsigned long long tmx[2][4];     // local minima of the new message (general path)
+    __shared__ int produced;
+    __shared__ __align__(16) int consumed[8];
+    const int L = P.g.L;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int NWV = (int)(blockDim.x >> 6) - NI;   // value wavefronts come first
+
+    const long long blk = blockIdx.x;
+    int ri = 0;
+    while (ri + 1 < P.r_count && blk >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = blk - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long N = P.g.N;
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const float vz = mrf_opaque_zero_f();     // keeps uniform constants in vector registers
+
+    float f[TW];
+#pragma unroll
+    for (int d = 0; d < TW; ++d) f[d] = P.V[d < L ? d : L - 1] + vz;
+    const float fT = P.V[L - 1] + vz;
+    const bool f0zero = (P.V[0] == 0.0f);
+    if ((int)threadIdx.x <= TW) ftab[threadIdx.x] = (int)threadIdx.x < TW ? P.V[(int)threadIdx.x < L ? threadIdx.x : L - 1] : fT;
+    // padding and the entries of labels >= L are never written again: they never win a strict '<'
+    for (int i = threadIdx.x; i < NR * HB; i += blockDim.x) (&ring[0][0])[i] = INFINITY;
+    if (threadIdx.x < 8) {
+        (&hmx[0][0])[threadIdx.x] = 0ull;                      // step 0: no step waits for it
+        (&tmx[0][0])[threadIdx.x] = 0ull;
+        consumed[threadIdx.x] = (int)threadIdx.x + 1 - NI;     // "finished" starts one turn before
+    }
+    if (threadIdx.x == 0) produced = 0;
+    __syncthreads();
+
+    if (wv >= NWV) {
+        // ---- p, q and all stores: index wavefront jw takes steps 1 + jw, 1 + jw + NI, ... ------
+        const int jw = wv - NWV;
+        if (jw == 0) {
+#pragma unroll
+            for (int s = 0; s < LPI; ++s) {
+                const int lam = lane + 64 * s;
+                if (lam < L) {
+                    P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
+                    P.p[((size_t)r * N + head) * L + lam] = 0;
+                }
+            }
+            if (lane == 0) P.q[(size_t)r * N + head] = 0;
+        }
+        int seen = 0;
+        for (int n = 1 + jw; n < len; n += NI) {
+            while (seen < n) {
+                seen = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (seen < n) __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            const int slot = n & (NR - 1);
+            const float *hbuf = &ring[slot][TW];
+            const float wgt = ringw[slot];
+            const long long i = head + (long long)n * nstep;
+
+            float hv[LPI];
+            float hm = INFINITY;
+#pragma unroll
+            for (int s = 0; s < LPI; ++s) {
+                hv[s] = hbuf[lane + 64 * s];           // +inf for labels >= L
+                hm = mrf_min(hm, hv[s]);
+            }
+            const float hmin = mrf_wave_min(hm);
+
+            float tv[LPI];
+            int tp[LPI];
+            float tq;
+            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
+                int mug = 0;
+                bool found = false;
+#pragma unroll
+                for (int s = 0; s < LPI; ++s) {
+                    const int lam = lane + 64 * s;
+                    const float gfar = lam < L ? __builtin_fmaf(wgt, fT, hv[s]) : INFINITY;
+                    const unsigned long long bal = __ballot(gfar == gmin);
+                    if (!found && bal != 0ull) { found = true; mug = 64 * s + __ffsll((long long)bal) - 1; }
+                }
+#pragma unroll
+                for (int s = 0; s < LPI; ++s) {
+                    const int lam = lane + 64 * s;
+                    float dl[2 * TW - 1];
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o) {
+                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                        dl[o] = __builtin_fmaf(wgt, f[dist], hbuf[lam + o - (TW - 1)]);
+                    }
+                    float W = dl[0];
+#pragma unroll
+                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
+                    int po = 2 * TW - 2;
+#pragma unroll
+                    for (int o = 2 * TW - 3; o >= 0; --o) po = (dl[o] == W) ? o : po;
+                    const int pW = lam + po - (TW - 1);
+                    const bool wlt = W < gmin, wgt_ = W > gmin;
+                    tv[s] = (lam < L) ? (wlt ? W : gmin) : INFINITY;
+                    const int tie = pW < mug ? pW : mug;
+                    tp[s] = wlt ? pW : (wgt_ ? mug : tie);
+                }
+                if (f0zero) {
+                    tq = hmin;
+                } else {
+                    float mn = INFINITY;
+#pragma unroll
+                    for (int s = 0; s < LPI; ++s) mn = fminf(mn, tv[s]);
+                    tq = mrf_wave_min(mn);
+                }
+            } else {
+                // negative weight: the ordering argument does not hold, evaluate every mu
+#pragma unroll
+                for (int s = 0; s < LPI; ++s) {
+                    const int lam = lane + 64 * s;
+                    float best = INFINITY;
+                    int bi = 0;
+                    for (int mu = 0; mu < L; ++mu) {
+                        int dist = mu > lam ? mu - lam : lam - mu;
+                        dist = dist < TW ? dist : TW;
+                        const float dlt = __builtin_fmaf(wgt, ftab[dist], hbuf[mu]);
+                        if (dlt < best) { best = dlt; bi = mu; }
+                    }
+                    tv[s] = (lam < L) ? best : INFINITY;
+                    tp[s] = bi;
+                }
+                float mn = INFINITY;
+#pragma unroll
+                for (int s = 0; s < LPI; ++s) mn = fminf(mn, tv[s]);
+                tq = mrf_wave_min(mn);
+            }
+            // this slot has been read: hand it back
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            if (lane == 0) __hip_atomic_store(&consumed[jw], n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+
+            int qidx = -1;
+#pragma unroll
+            for (int s = 0; s < LPI; ++s) {
+                const unsigned long long bal = __ballot(tv[s] == tq);
+                if (qidx < 0 && bal != 0ull) qidx = 64 * s + __ffsll((long long)bal) - 1;
+            }
+#pragma unroll
+            for (int s = 0; s < LPI; ++s) {
+                const int lam = lane + 64 * s;
+                if (lam < L) {
+                    P.m_out[((size_t)r * N + i) * L + lam] = tv[s] - tq;
+                    P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
+                }
+            }
+            if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+        }
+        return;
+    }
+
+    // ---- values: wavefront wv owns labels 64 wv .. 64 wv + 63 ---------------------------------
+    const int lam = wv * 64 + lane;
+    const bool valid = lam < L;
+    const int lamc = valid ? lam : 0;
+    const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
+        is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = ((c == n_pre + 1) ? 1.0f : 0.0f) + vz;
+
+    const int vzero = mrf_opaque_zero();
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len - 2;
+    float cur[D][RMAX], nxt[D][RMAX];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX], float &wdst, int nj) {
+        nj = nj < lastsrc ? nj : lastsrc;
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][(size_t)j * L + lamc];
+        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+    };
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
+
+    // Meeting point of the value wavefronts.  The hardware barrier would also wait for the index
+    // wavefronts, so each value wavefront posts {step, its value} and reads the others' until all
+    // carry this step; LDS keeps a wavefront's operations in order, so whoever sees the post also
+    // sees what that wavefront wrote to the ring before it.  Two sets by step parity: a wavefront
+    // can be at most one step ahead of the slowest, because it needs that one's post to go on.
+    auto exchange_min = [&](unsigned long long (&box)[2][4], int par, int step, float val) {
+        if (lane == 0)
+            __hip_atomic_store(&box[par][wv], ((unsigned long long)(unsigned)step << 32) | (unsigned)__float_as_int(val),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        float m;
+        bool all;
+        do {
+            m = INFINITY;
+            all = true;
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                if (w2 < NWV) {
+                    const unsigned long long e = __hip_atomic_load(&box[par][w2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    all = all && (int)(e >> 32) == step;
+                    m = fminf(m, __int_as_float((int)(unsigned)e));
+                }
+            }
+            all = __builtin_amdgcn_readfirstlane((int)all) != 0;
+        } while (!all);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        return m;
+    };
+
+    float carry = 0.0f;
+    int par = 0;
+    int freed = 0;          // every step <= freed is finished by the index wavefronts (possibly stale view)
+    for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int nn = n0 + u;
+            const bool past = nn >= len;
+            const float wgt = wcur[u];
+            const int slot = nn & (NR - 1);
+            float *hb = &ring[slot][TW];
+
+            // the slot was last used by step nn - NR
+            while (!past && freed < nn - NR) {
+                int lo = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+#pragma unroll
+                for (int j = 1; j < NI; ++j) {
+                    const int cj = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(&consumed[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    lo = cj < lo ? cj : lo;
+                }
+                freed = lo + NI - 1;
+                if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+            float v = cur[u][0];
+            if (TRWP) {
+                float mrm = 0.0f;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) {
+                    v = __builtin_fmaf(carry_at[c], carry, v);
+                    v = __builtin_fmaf(use[c], cur[u][c], v);
+                    mrm = __builtin_fmaf(is_rm[c], cur[u][c], mrm);
+                }
+                v = __builtin_fmaf(carry_at[RMAX], carry, v);
+                v = rho * v;
+                v = v - mrm;
+            } else {
+                v = v + carry;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+            }
+            if (valid && !past) hb[lam] = v;
+            const float hloc = mrf_wave_min(valid ? v : INFINITY);
+            if (threadIdx.x == 0 && !past) ringw[slot] = wgt;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            const float hmin = exchange_min(hmx, par, nn, hloc);
+            // every entry of the node is in the ring: let the index wavefronts have it
+            if (threadIdx.x == 0 && !past)
+                __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const bool wpos = __builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0;
+            float tv;
+            if (wpos) {
+                const float gmin = __builtin_fmaf(wgt, fT, hmin);
+                float dl[2 * TW - 1];
+#pragma unroll
+                for (int o = 0; o < 2 * TW - 1; ++o) {
+                    const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
+                    const float hvv = (o == TW - 1) ? v : hb[lam + o - (TW - 1)];
+                    dl[o] = __builtin_fmaf(wgt, f[dist], hvv);
+                }
+                float W = dl[0];
+#pragma unroll
+                for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
+                tv = valid ? mrf_min(W, gmin) : INFINITY;
+            } else {
+                float best = INFINITY;
+                for (int mu = 0; mu < L; ++mu) {
+                    int dist = mu > lam ? mu - lam : lam - mu;
+                    dist = dist < TW ? dist : TW;
+                    const float dlt = __builtin_fmaf(wgt, ftab[dist], hb[mu]);
+                    if (dlt < best) best = dlt;
+                }
+                tv = valid ? best : INFINITY;
+            }
+            float tq = hmin;
+            if (!(wpos && f0zero)) {
+                // general case: the minimum of the new message needs its own exchange
+                const float tloc = mrf_wave_min(tv);
+                tq = exchange_min(tmx, par, nn, tloc);
+            }
+            carry = valid ? tv - tq : 0.0f;
+            par ^= 1;
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c) cur[u][c] = nxt[u][c];
+        }
+    }
+}
+
 // ---- dense sweep for few labels: several scanlines per wavefront ----------------------------
 //
 // For L <= 32 a wavefront with one scanline leaves most lanes idle.  Here a wavefront is cut

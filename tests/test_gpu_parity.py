@@ -191,12 +191,16 @@ def test_window_path_is_exact(oracle, case):
         got["trio"] = full_check(oracle, pr)
         assert mrf.mrf_tune(8, 2) == 0                                  # and a loader wavefront (TRWP)
         got["quad"] = full_check(oracle, pr)
-        assert mrf.mrf_tune(2, 2) == 0                                  # one wavefront per 64 labels
+        assert mrf.mrf_tune(2, 2) == 0 and mrf.mrf_tune(9, 1) == 0      # one wavefront per 64 labels
         got["split"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(9, 2) == 0 and mrf.mrf_tune(10, 4) == 0     # ... for the values, 4 index wavefronts
+        got["squad4"] = full_check(oracle, pr)
+        assert mrf.mrf_tune(10, 8) == 0
+        got["squad8"] = full_check(oracle, pr)
         assert mrf.mrf_tune(1, 1) == 0                                  # dense sweep
         d = run_gpu(pr)
     finally:
-        for knob in (1, 2, 4, 5, 8):
+        for knob in (1, 2, 4, 5, 8, 9, 10):
             mrf.mrf_tune(knob, 0)
     for layout, g in got.items():
         for name in ("p", "q", "labels", "cost", "messages"):
