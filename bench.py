@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 1 GiB device-to-device copy (calibration of HBM byte counters)")
     ap.add_argument("--tune-mch", type=int, default=0, help="experiment: source labels per wavefront (0 = heuristic)")
+    ap.add_argument("--heads", action="store_true",
+                    help="also time the energy and SoftMin + L1 heads on the same workload (extra \"heads\" object)")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
                     help="experiment: set a kernel-choice knob of mrf_tune (results never depend on them)")
     args = ap.parse_args()
@@ -203,6 +205,39 @@ def main():
         "forward_updates_per_s": updates / (fwd_sweeps_ms * 1e-3),
         "backward_updates_per_s": updates / (bwd_sweeps_ms * 1e-3),
     }
+    if args.heads:
+        # the two heads around the path, on this workload's final costs and labels: streaming kernels,
+        # priced against HBM with their algorithmic bytes
+        N = B * H * W
+        ws = torch.empty(max(mrf.mrf_energy_workspace_bytes(g.prob), mrf.mrf_softmin_l1_workspace_bytes()),
+                         dtype=torch.uint8, device="cuda:0")
+        energy = torch.empty((B,), dtype=torch.float64, device="cuda:0")
+        target = torch.rand((B, H, W), device="cuda:0") * (L - 1)
+        disp = torch.empty((B, H, W), device="cuda:0")
+        loss = torch.empty((1,), dtype=torch.float64, device="cuda:0")
+        gcost = torch.empty_like(g.cost)
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        t_e = timed(lambda: mrf.mrf_energy(g.prob, g.labels, energy, ws))
+        t_l = timed(lambda: mrf.mrf_softmin_l1(g.cost, target, None, disp, loss, gcost, ws))
+        n_edge_dirs = sum(1 for i, d in enumerate(pr.dirs.tolist())
+                          if [-d[0], -d[1]] not in pr.dirs.tolist() or pr.dirs.tolist().index([-d[0], -d[1]]) > i)
+        e_bytes = N * (1 + 4) + sum(E[i] for i in range(R) if i < R) // R * n_edge_dirs * (4 + 4)   # label, theta(x), per edge: weight, V entry
+        l_bytes = N * (L * 4 * 2 + 4 * 2)
+        out["heads"] = {
+            "energy": {"ms": t_e, "bound": "hbm", "achieved": e_bytes / (t_e * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "frac": e_bytes / (t_e * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "softmin_l1": {"ms": t_l, "bound": "hbm", "achieved": l_bytes / (t_l * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": l_bytes / (t_l * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, pr.algo)
     print(json.dumps(out))

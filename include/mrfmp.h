@@ -143,6 +143,39 @@ int64_t mrf_scanline_count(int32_t H, int32_t W, int32_t dh, int32_t dw);
 int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
                       int32_t *y0, int32_t *x0, int32_t *len);
 
+/* Energy of a labelling, Sec. 3.1 Eq. energy-function:
+ *   energy[b] = sum_i theta_i(x_i) + sum over edges (i-r, i) of theta_{i-r,i} V(x_{i-r}, x_i)
+ * for every batch image b.  The edge set holds every undirected neighbour pair once: the
+ * edges of the first direction of each opposite pair in prob->dirs (and of every direction
+ * without an opposite), with that direction's weights.  prob->K and prob->rho are not used.
+ *   labels   DEVICE [B][H][W] uint8 (values >= L are read as L-1)
+ *   energy   DEVICE [B] double, assigned
+ *   workspace DEVICE, at least mrf_energy_workspace_bytes(prob), 256-byte aligned
+ * Sums are formed in double in an order fixed by the launch shape.  Asynchronous on
+ * hip_stream.  Returns MRF_OK or a negative MRF_ERR_* before any GPU work is issued. */
+size_t mrf_energy_workspace_bytes(const mrf_problem *prob);
+int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, void *workspace,
+               size_t workspace_bytes, void *hip_stream);
+
+/* Loss head of the learning set-up (Appendix, Eqs. supp-isgmr-confidence,
+ * supp-isgmr-regression, and the L1 loss named there): per pixel
+ *   f(lambda) = exp(-c(lambda)) / sum_mu exp(-c(mu)),  d = sum_lambda lambda f(lambda),
+ *   loss = (1/n) sum over counted pixels |d - target|,
+ *   grad_cost(lambda) = d loss / d c(lambda) = sign(d - target)/n * (-f(lambda)) * (lambda - d)
+ * (0 for pixels that do not count; sign(0) = 0), n = number of counted pixels.
+ *   cost      DEVICE [n_pixels][L] float: the final costs c of a forward call
+ *   target    DEVICE [n_pixels] float: real-valued ground-truth disparities
+ *   mask      DEVICE [n_pixels] uint8 or NULL: non-zero = the pixel counts (NULL: all count)
+ *   disparity DEVICE [n_pixels] float or NULL, assigned
+ *   loss      DEVICE double, assigned
+ *   grad_cost DEVICE [n_pixels][L] float or NULL, assigned: the grad_cost of mrf_*_backward
+ *   workspace DEVICE, at least mrf_softmin_l1_workspace_bytes(), 256-byte aligned
+ * Arithmetic in double, reproducible run to run.  Asynchronous on hip_stream. */
+size_t mrf_softmin_l1_workspace_bytes(void);
+int mrf_softmin_l1(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
+                   float *disparity, double *loss, float *grad_cost, void *workspace, size_t workspace_bytes,
+                   void *hip_stream);
+
 /* Static text for a status code. */
 const char *mrf_strerror(int status);
 

@@ -4,6 +4,7 @@
 #include "mrfmp_device.h"
 #include "mrfmp_fwd.h"
 #include "mrfmp_bwd.h"
+#include "mrfmp_head.h"
 
 #include <math.h>
 #include <stdio.h>
@@ -802,6 +803,81 @@ const char *mrf_strerror(int status)
     case MRF_ERR_HIP: return "HIP runtime call or kernel launch failed";
     default: return "unknown status";
     }
+}
+
+size_t mrf_energy_workspace_bytes(const mrf_problem *prob)
+{
+    if (check_problem(prob, MRF_ISGMR, false) != MRF_OK) return 0;
+    return sizeof(double) * (size_t)prob->B * MRF_HEAD_BLOCKS;
+}
+
+int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, void *workspace,
+               size_t workspace_bytes, void *hip_stream)
+{
+    const int rc = check_problem(prob, MRF_ISGMR, true);
+    if (rc != MRF_OK) return rc;
+    if (!labels || !energy || !workspace) return MRF_ERR_NULL_POINTER;
+    if (workspace_bytes < mrf_energy_workspace_bytes(prob)) return MRF_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    MrfEnergyParams E;
+    memset(&E, 0, sizeof(E));
+    fill_geom(prob, E.g);
+    E.unary = prob->unary; E.V = prob->pairwise; E.labels = labels;
+    E.partial = (double *)workspace;
+    if (prob->edge_weight) { E.w = prob->edge_weight; E.w_mul = 1; }
+    else { E.w = nullptr; E.w_mul = 0; }
+    for (int r = 0; r < prob->R; ++r)
+        if (E.g.opp[r] < 0 || r < E.g.opp[r]) E.edge_dir[E.n_edge_dir++] = r;
+    const long long HW = (long long)prob->H * prob->W;
+    long long blocks = (HW + 255) / 256;
+    if (blocks > MRF_HEAD_BLOCKS) blocks = MRF_HEAD_BLOCKS;
+    E.w_scalar = prob->edge_weight_scalar;
+    hipLaunchKernelGGL(mrf_energy_partial, dim3((unsigned)blocks, (unsigned)prob->B), dim3(256), 0, st, E);
+    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "mrf_energy_partial"); }
+    hipLaunchKernelGGL(mrf_sum_partials, dim3((unsigned)prob->B), dim3(64), 0, st, (const double *)E.partial, (int)blocks,
+                       energy, (const long long *)nullptr);
+    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "mrf_sum_partials"); }
+    return MRF_OK;
+}
+
+size_t mrf_softmin_l1_workspace_bytes(void)
+{
+    return kAlign + (sizeof(double) + sizeof(long long)) * MRF_HEAD_BLOCKS;
+}
+
+int mrf_softmin_l1(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
+                   float *disparity, double *loss, float *grad_cost, void *workspace, size_t workspace_bytes,
+                   void *hip_stream)
+{
+    if (n_pixels < 1 || n_pixels > 0x7fffffffLL) return MRF_ERR_BAD_SHAPE;
+    if (L < 1 || L > MRF_MAX_LABELS) return MRF_ERR_BAD_LABELS;
+    if (!cost || !target || !loss || !workspace) return MRF_ERR_NULL_POINTER;
+    if (workspace_bytes < mrf_softmin_l1_workspace_bytes()) return MRF_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    MrfLossParams Q;
+    memset(&Q, 0, sizeof(Q));
+    Q.N = n_pixels; Q.L = L; Q.cost = cost; Q.target = target; Q.mask = mask;
+    Q.disparity = disparity; Q.grad_cost = grad_cost;
+    Q.count = (long long *)workspace;
+    Q.partial = (double *)((char *)workspace + kAlign);
+    Q.cpartial = (long long *)((char *)workspace + kAlign + sizeof(double) * MRF_HEAD_BLOCKS);
+    if (mask) {
+        long long cb = (n_pixels + 255) / 256;
+        if (cb > MRF_HEAD_BLOCKS) cb = MRF_HEAD_BLOCKS;
+        hipLaunchKernelGGL(mrf_count_mask_partial, dim3((unsigned)cb), dim3(256), 0, st, Q);
+        hipLaunchKernelGGL(mrf_count_mask_final, dim3(1), dim3(64), 0, st, Q, (int)cb);
+    } else {
+        hipLaunchKernelGGL(mrf_set_i64, dim3(1), dim3(64), 0, st, Q.count, (long long)n_pixels);
+    }
+    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "mrf_softmin_l1 count"); }
+    long long blocks = (n_pixels + 3) / 4;
+    if (blocks > MRF_HEAD_BLOCKS) blocks = MRF_HEAD_BLOCKS;
+    hipLaunchKernelGGL(mrf_softmin_l1_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Q);
+    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "mrf_softmin_l1_kernel"); }
+    hipLaunchKernelGGL(mrf_sum_partials, dim3(1), dim3(64), 0, st, (const double *)Q.partial, (int)blocks, loss,
+                       (const long long *)Q.count);
+    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "mrf_sum_partials"); }
+    return MRF_OK;
 }
 
 const char *mrf_last_error_detail(void) { return g_error_detail; }

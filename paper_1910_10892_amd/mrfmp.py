@@ -86,6 +86,14 @@ def load_library():
     lib.mrf_last_error_detail.argtypes = []
     lib.mrf_last_sweep_kernel.restype = ctypes.c_char_p
     lib.mrf_last_sweep_kernel.argtypes = [ci]
+    lib.mrf_energy_workspace_bytes.restype = sz
+    lib.mrf_energy_workspace_bytes.argtypes = [P]
+    lib.mrf_energy.restype = ci
+    lib.mrf_energy.argtypes = [P, vp, vp, vp, sz, vp]
+    lib.mrf_softmin_l1_workspace_bytes.restype = sz
+    lib.mrf_softmin_l1_workspace_bytes.argtypes = []
+    lib.mrf_softmin_l1.restype = ci
+    lib.mrf_softmin_l1.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mrf_strerror.argtypes = [ci]
     lib.mrf_version.restype = ctypes.c_char_p
     lib.mrf_set_sweep_events.restype = ci
@@ -248,3 +256,38 @@ def mrf_trwp_backward(prob, grad_cost, p, q, grad_unary, grad_edge_weight, grad_
                       stream=None):
     _backward("mrf_trwp_backward", prob, grad_cost, p, q, grad_unary, grad_edge_weight, grad_pairwise,
               workspace, stream)
+
+
+def _ws_size(workspace) -> int:
+    return 0 if workspace is None else workspace.numel() * workspace.element_size()
+
+
+def mrf_energy_workspace_bytes(prob) -> int:
+    c = prob.c_struct()
+    return int(load_library().mrf_energy_workspace_bytes(ctypes.byref(c)))
+
+
+def mrf_energy(prob, labels, energy, workspace, stream=None):
+    """labels [B,H,W] uint8, energy [B] float64 (assigned), workspace uint8 tensor."""
+    c = prob.c_struct()
+    rc = load_library().mrf_energy(ctypes.byref(c), _dev_ptr(labels, "uint8"), _dev_ptr(energy, "float64"),
+                                   _dev_ptr(workspace), _ws_size(workspace), _stream_handle(stream))
+    if rc != 0:
+        raise MrfError(rc, "mrf_energy")
+
+
+def mrf_softmin_l1_workspace_bytes() -> int:
+    return int(load_library().mrf_softmin_l1_workspace_bytes())
+
+
+def mrf_softmin_l1(cost, target, mask, disparity, loss, grad_cost, workspace, stream=None):
+    """cost [..., L] float32, target [...] float32, mask [...] uint8 or None, disparity [...] float32 or
+    None, loss [1] float64, grad_cost like cost or None."""
+    L = int(cost.shape[-1])
+    n = int(cost.numel() // L)
+    rc = load_library().mrf_softmin_l1(n, L, _dev_ptr(cost, "float32"), _dev_ptr(target, "float32"),
+                                       _dev_ptr(mask, "uint8"), _dev_ptr(disparity, "float32"),
+                                       _dev_ptr(loss, "float64"), _dev_ptr(grad_cost, "float32"),
+                                       _dev_ptr(workspace), _ws_size(workspace), _stream_handle(stream))
+    if rc != 0:
+        raise MrfError(rc, "mrf_softmin_l1")

@@ -1,0 +1,88 @@
+"""GPU parity of the two heads (energy of a labelling, SoftMin regression + L1) with their fp64
+oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from mrf_inputs import DIRS4, DIRS8, make_config, random_problem
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_problem(pr):
+    from gpu_harness import GpuProblem
+    return GpuProblem(pr, want_messages=False)
+
+
+@pytest.mark.parametrize("case", [
+    (1, 1, 5, 7, 9, DIRS4, True), (2, 3, 6, 5, 33, DIRS8, True), (3, 1, 1, 9, 4, DIRS4, False),
+    (4, 2, 40, 70, 96, DIRS4, True), (5, 1, 7, 1, 256, [(0, 1), (1, 0), (-1, 0)], True),
+], ids=lambda c: "seed%d" % c[0])
+def test_energy_matches_oracle(case):
+    import torch
+    import paper_1910_10892_amd as mrf
+    from oracle import mrf_heads_oracle as ho
+    seed, B, H, W, L, dirs, per_edge = case
+    print("case energy", case[:5], flush=True)
+    pr = random_problem(seed, "isgmr", B, H, W, L, dirs, 1, per_edge=per_edge, symmetric=False)
+    rng = np.random.default_rng(seed + 500)
+    lab = rng.integers(0, L, (B, H, W)).astype(np.uint8)
+    g = _gpu_problem(pr)
+    ws = torch.empty(mrf.mrf_energy_workspace_bytes(g.prob), dtype=torch.uint8, device="cuda:0")
+    out = torch.full((B,), float("nan"), dtype=torch.float64, device="cuda:0")
+    mrf.mrf_energy(g.prob, torch.from_numpy(lab).cuda(), out, ws)
+    ref = ho.energy(pr.unary, pr.pairwise, pr.dirs, lab, edge_weight=pr.edge_weight,
+                    edge_weight_scalar=pr.edge_weight_scalar)
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-12, atol=1e-9)
+
+
+def test_energy_of_the_labelling_the_sweeps_return():
+    """Forward pass, then the energy of its labels, on the stereo recipe (cropped)."""
+    import torch
+    import paper_1910_10892_amd as mrf
+    from oracle import mrf_heads_oracle as ho
+    print("case energy of forward labels", flush=True)
+    pr = make_config(2, crop=(24, 40))
+    g = _gpu_problem(pr)
+    g.forward()
+    ws = torch.empty(mrf.mrf_energy_workspace_bytes(g.prob), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((1,), dtype=torch.float64, device="cuda:0")
+    mrf.mrf_energy(g.prob, g.labels, out, ws)
+    ref = ho.energy(pr.unary, pr.pairwise, pr.dirs, g.labels.cpu().numpy(), edge_weight=pr.edge_weight,
+                    edge_weight_scalar=pr.edge_weight_scalar)
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-12, atol=1e-9)
+
+
+@pytest.mark.parametrize("n,L,masked", [(1, 1, False), (37, 2, False), (1000, 96, True), (513, 200, True),
+                                        (4099, 21, False), (64, 256, True)])
+def test_softmin_l1_matches_oracle(n, L, masked):
+    import torch
+    import paper_1910_10892_amd as mrf
+    from oracle import mrf_heads_oracle as ho
+    print("case softmin", n, L, masked, flush=True)
+    rng = np.random.default_rng(900 + n + L)
+    cost = rng.normal(0.0, 3.0, (n, L)).astype(np.float32)
+    target = rng.uniform(0.0, max(L - 1, 1), n).astype(np.float32)
+    mask = (rng.random(n) > 0.25).astype(np.uint8) if masked else None
+    ws = torch.empty(mrf.mrf_softmin_l1_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
+    disp = torch.full((n,), float("nan"), device="cuda:0")
+    grad = torch.full((n, L), float("nan"), device="cuda:0")
+    loss = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    for _ in range(2):      # twice: the workspace keeps nothing that matters from call to call
+        mrf.mrf_softmin_l1(torch.from_numpy(cost).cuda(), torch.from_numpy(target).cuda(),
+                           None if mask is None else torch.from_numpy(mask).cuda(), disp, loss, grad, ws)
+    d, l, gr = ho.softmin_l1(cost, target, mask)
+    np.testing.assert_allclose(disp.cpu().numpy(), d, rtol=1e-5, atol=1e-4)
+    np.testing.assert_allclose(loss.cpu().numpy()[0], l, rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(grad.cpu().numpy(), gr, rtol=1e-5, atol=1e-7 / max(n, 1) + 1e-12)
+
+
+def test_heads_reject_bad_arguments():
+    import torch
+    import paper_1910_10892_amd as mrf
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    c = torch.zeros((4, 3), device="cuda:0")
+    t = torch.zeros((4,), device="cuda:0")
+    loss = torch.zeros((1,), dtype=torch.float64, device="cuda:0")
+    with pytest.raises(mrf.MrfError) as ei:
+        mrf.mrf_softmin_l1(c, t, None, None, loss, None, ws)
+    assert ei.value.status == -6
