@@ -65,7 +65,10 @@ enum { MRF_ISGMR = 0, MRF_TRWP = 1 };
 enum {
     MRF_PAIRWISE_DENSE = 0,            /* no structure assumed */
     MRF_PAIRWISE_TRUNC_LINEAR = 1,     /* V(mu,lambda) = scale * min(|mu-lambda|, trunc)      */
-    MRF_PAIRWISE_TRUNC_QUADRATIC = 2   /* V(mu,lambda) = scale * min((mu-lambda)^2, trunc)    */
+    MRF_PAIRWISE_TRUNC_QUADRATIC = 2,  /* V(mu,lambda) = scale * min((mu-lambda)^2, trunc)    */
+    MRF_PAIRWISE_DISTANCE = 3          /* V(mu,lambda) = f(|mu-lambda|), f(0) <= f(1) <= ..., constant for
+                                          |mu-lambda| >= trunc: e.g. the three SGM penalties 0, P1, P2
+                                          of Eq. vsgm with trunc = 2 (scale is not used)              */
 };
 
 /* The problem as the paper states it: energy parameters Theta = {theta_i, theta_ij} with
@@ -83,7 +86,7 @@ typedef struct {
     float edge_weight_scalar;
     const float *rho;           /* HOST  [R] rho_{i-r,i} per direction; TRWP only, ignored by ISGMR */
     int32_t pairwise_kind;      /* MRF_PAIRWISE_* */
-    float trunc, scale;         /* parameters of kinds 1 and 2 (trunc > 0) */
+    float trunc, scale;         /* parameters of kinds 1, 2 and 3 (trunc > 0) */
 } mrf_problem;
 
 /* Bytes of DEVICE workspace (256-byte aligned base required) that the forward

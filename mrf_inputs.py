@@ -22,7 +22,7 @@ DIRS4 = [(0, 1), (0, -1), (1, 0), (-1, 0)]
 DIRS8 = DIRS4 + [(1, 1), (-1, -1), (1, -1), (-1, 1)]
 DIRS16 = DIRS8 + [(1, 2), (-1, -2), (2, 1), (-2, -1), (1, -2), (-1, 2), (2, -1), (-2, 1)]
 
-KIND_DENSE, KIND_TRUNC_LINEAR, KIND_TRUNC_QUADRATIC = 0, 1, 2
+KIND_DENSE, KIND_TRUNC_LINEAR, KIND_TRUNC_QUADRATIC, KIND_DISTANCE = 0, 1, 2, 3
 
 
 @dataclass
@@ -57,6 +57,14 @@ class Problem:
         for dh, dw in self.dirs.tolist():
             tot += B * max(H - abs(dh), 0) * max(W - abs(dw), 0)
         return tot * L * self.K
+
+
+def sgm_penalties(L: int, p1: float, p2: float) -> np.ndarray:
+    """The three-penalty pairwise function of SGM (Eq. vsgm): 0 on the diagonal, p1 for label
+    distance 1, p2 from distance 2 on."""
+    a = np.arange(L)
+    d = np.abs(a[:, None] - a[None, :])
+    return np.where(d == 0, 0.0, np.where(d == 1, p1, p2)).astype(np.float32)
 
 
 def truncated_linear(L: int, trunc: float, scale: float = 1.0) -> np.ndarray:

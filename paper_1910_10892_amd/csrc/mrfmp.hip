@@ -40,7 +40,7 @@ int check_problem(const mrf_problem *pr, int algo, bool forward)
     if (forward && !pr->unary) return MRF_ERR_NULL_POINTER;
     if (algo == MRF_TRWP && !pr->rho) return MRF_ERR_NULL_POINTER;
     if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && pr->pairwise_kind != MRF_PAIRWISE_TRUNC_LINEAR &&
-        pr->pairwise_kind != MRF_PAIRWISE_TRUNC_QUADRATIC)
+        pr->pairwise_kind != MRF_PAIRWISE_TRUNC_QUADRATIC && pr->pairwise_kind != MRF_PAIRWISE_DISTANCE)
         return MRF_ERR_BAD_PAIRWISE_KIND;
     if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && !(pr->trunc > 0.0f)) return MRF_ERR_BAD_PAIRWISE_KIND;
     return MRF_OK;

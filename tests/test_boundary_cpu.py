@@ -83,6 +83,9 @@ def test_forward_kernel_choice_is_host_arithmetic():
     assert W(L=21, pairwise_kind=0) == 0
     assert W(L=12, pairwise_kind=1, trunc=20.0) == 0          # never truncates inside the label range
     assert W(L=200, pairwise_kind=1, trunc=40.0) == 0         # window wider than the kernel supports
+    assert W(L=64, pairwise_kind=3, trunc=2.0) == 2           # SGM penalties: constant from distance 2
+    assert W(L=64, pairwise_kind=3, trunc=5.0) == 8
+    assert W(L=64, pairwise_kind=4, trunc=2.0) == -7          # unknown kind
     assert W(L=0, pairwise_kind=1, trunc=4.0) == -3
 
 

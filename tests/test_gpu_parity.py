@@ -255,6 +255,29 @@ def test_benchmark_configs_cropped_without_pairwise_gradient(oracle, index, crop
     full_check(oracle, pr, want_V=False)
 
 
+@pytest.mark.parametrize("algo,K,L,p1,p2", [("isgmr", 1, 64, 0.3, 1.7), ("isgmr", 3, 96, 1.0, 1.0),
+                                           ("trwp", 2, 130, 0.5, 2.0)])
+def test_sgm_penalties_through_the_window_path(oracle, algo, K, L, p1, p2):
+    """The three SGM penalties (Eq. vsgm) announced as a distance function that is constant from
+    distance 2 on; K = 1 with ISGMR is the revised single-pass SGM (Eq. sgm).  Window sweep against
+    the oracle and, bit for bit, against the dense sweep."""
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import run_gpu
+    from mrf_inputs import sgm_penalties
+    print("case sgm penalties", algo, K, L, flush=True)
+    pr = random_problem(71, algo, 1, 6, 8, L, DIRS8, K, rho=np.linspace(0.3, 0.9, 8))
+    pr.pairwise = sgm_penalties(L, p1, p2)
+    pr.pairwise_kind, pr.trunc, pr.scale = 3, 2.0, 1.0
+    g = full_check(oracle, pr)
+    try:
+        assert mrf.mrf_tune(1, 1) == 0
+        d = run_gpu(pr)
+    finally:
+        mrf.mrf_tune(1, 0)
+    for name in ("p", "q", "labels", "cost", "messages"):
+        np.testing.assert_array_equal(getattr(g, name), getattr(d, name), err_msg=name)
+
+
 @pytest.mark.parametrize("case", [
     (61, "trwp", 1, 6, 7, 200, DIRS4, 3, False, True),
     (62, "isgmr", 1, 5, 6, 256, DIRS8, 2, True, True),
