@@ -50,7 +50,7 @@ def cpu_baseline(index, algo):
     import numpy as np
     from mrf_inputs import make_config
     from oracle import mrf_oracle
-    crop = (64, 128)
+    crop = (128, 256)
     pr = make_config(index, crop=crop, algo=algo)
     mrf_oracle.build()
     t0 = time.perf_counter()
