@@ -25,6 +25,16 @@
 // (message gradient, its label sum, the scatter sums) and the V-gradient accumulators are
 // kept in double, so that rounding does not build up along a scanline.  On this chip
 // double adds issue at the same rate as unpacked float adds.
+//
+// Kernels in this file:
+//   mrf_bwd_sweep          one wavefront per scanline (the description above)
+//   mrf_bwd_sweep_chain    the node-to-node chain on a wavefront of its own, helper wavefronts
+//                          for everything else (launches with few scanlines, no V gradient)
+//   mrf_bwd_sweep_split    one wavefront per 64 labels in lock step
+//   mrf_bwd_sweep_packed   L <= 32: several scanlines per wavefront
+//   mrf_isgmr_bwd_combine  ISGMR's sums over directions between two iterations
+//   mrf_reduce_slot_*      fixed-order reduction of the private V-gradient accumulators
+// Which sweep a launch gets is host arithmetic on the launch shape (dispatch_bwd).
 #pragma once
 
 #include "mrfmp_device.h"

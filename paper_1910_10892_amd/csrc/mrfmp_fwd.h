@@ -14,6 +14,17 @@
 // depend on the previous node (unary, other directions' messages, edge weight) is loaded
 // a group of D nodes ahead into a second register set, unconditionally (clamped
 // addresses), so that a load is first waited for at least D node steps after its issue.
+//
+// Kernels in this file, all computing the same update in the same rounding order:
+//   mrf_fwd_sweep               dense O(L^2), NW wavefronts per scanline split the source labels
+//   mrf_fwd_sweep_packed        dense, L <= 32: several scanlines per wavefront
+//   mrf_aggregate               final costs and labels
+//   mrf_fwd_sweep_window        truncated models: window of 2 TW - 1 source labels per label
+//   mrf_fwd_sweep_window_duo    the same with the dependency chain (values) on one wavefront and
+//                               index / loader wavefronts beside it, connected by LDS rings
+//   mrf_fwd_sweep_window_split  the same, one wavefront per 64 labels in lock step
+//   mrf_fwd_sweep_window_squad  value wavefronts per 64 labels plus index wavefronts per node
+// Which one a launch gets is host arithmetic on the launch shape (dispatch_fwd).
 #pragma once
 
 #include "mrfmp_device.h"
