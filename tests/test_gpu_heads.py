@@ -86,3 +86,37 @@ def test_heads_reject_bad_arguments():
     with pytest.raises(mrf.MrfError) as ei:
         mrf.mrf_softmin_l1(c, t, None, None, loss, None, ws)
     assert ei.value.status == -6
+
+
+@pytest.mark.parametrize("algo", ["isgmr", "trwp"])
+def test_autograd_wrapper_returns_the_library_gradients(algo):
+    """cost -> SoftMin + L1 head -> backward through torch.autograd equals the oracle's gradients of
+    the same composite (oracle backward fed with the oracle head's grad_cost)."""
+    import torch
+    from oracle import mrf_oracle, mrf_heads_oracle as ho
+    from paper_1910_10892_amd.autograd import message_passing
+    import paper_1910_10892_amd as mrf
+    print("case autograd", algo, flush=True)
+    pr = random_problem(33, algo, 1, 6, 7, 12, DIRS4, 2, rho=np.linspace(0.4, 0.8, 4))
+    rng = np.random.default_rng(77)
+    target = rng.uniform(0, 11, (1, 6, 7)).astype(np.float32)
+    unary = torch.from_numpy(pr.unary).cuda().requires_grad_(True)
+    V = torch.from_numpy(pr.pairwise).cuda().requires_grad_(True)
+    w = torch.from_numpy(pr.edge_weight).cuda().requires_grad_(True)
+    cost, labels = message_passing(unary, V, w, algo=algo, dirs=pr.dirs, K=pr.K, rho=pr.rho)
+    ws = torch.empty(mrf.mrf_softmin_l1_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
+    loss = torch.empty((1,), dtype=torch.float64, device="cuda:0")
+    gcost = torch.empty_like(cost)
+    mrf.mrf_softmin_l1(cost.detach(), torch.from_numpy(target).cuda(), None, None, loss, gcost, ws)
+    cost.backward(gcost)
+    f = mrf_oracle.forward(pr.algo, pr.unary, pr.pairwise, pr.dirs, pr.K, edge_weight=pr.edge_weight,
+                           edge_weight_scalar=pr.edge_weight_scalar, rho=pr.rho)
+    assert (labels.cpu().numpy() == f.labels).all()
+    _, l_ref, g_ref = ho.softmin_l1(f.cost, target)
+    b = mrf_oracle.backward(pr.algo, pr.shape, pr.pairwise, pr.dirs, pr.K, g_ref.astype(np.float32), f.p, f.q,
+                            edge_weight=pr.edge_weight, edge_weight_scalar=pr.edge_weight_scalar, rho=pr.rho,
+                            dtype=np.float64)
+    assert loss.cpu().numpy()[0] == pytest.approx(l_ref, rel=1e-6)
+    np.testing.assert_allclose(unary.grad.cpu().numpy(), b.grad_unary, rtol=1e-4, atol=1e-6)
+    np.testing.assert_allclose(w.grad.cpu().numpy(), b.grad_edge_weight, rtol=1e-4, atol=1e-6)
+    np.testing.assert_allclose(V.grad.cpu().numpy(), b.grad_pairwise, rtol=1e-4, atol=1e-6)
