@@ -464,3 +464,30 @@ def test_drawn_problems_default_dispatch(oracle, seed):
     if big > 10.0:
         pr.grad_cost = (pr.grad_cost * np.float32(10.0 / big)).astype(np.float32)
     full_check(oracle, pr, want_V=want_V)
+
+
+@pytest.mark.parametrize("seed", range(120))
+def test_drawn_problems_forced_layouts(oracle, seed):
+    """The same kind of random problems with the kernel-choice knobs drawn at random too, so that
+    layouts meet shapes they would not be picked for (the results may not depend on the knobs)."""
+    import paper_1910_10892_amd as mrf
+    pr, want_V = _drawn_problem(1000 + seed)
+    rng = np.random.default_rng(9000 + seed)
+    knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
+             5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8])),
+             8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8]))}
+    print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
+          flush=True)
+    f = oracle_forward(oracle, pr)
+    b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
+    big = max(float(np.abs(b.grad_unary).max()), float(np.abs(b.grad_pairwise).max()),
+              float(np.abs(b.grad_edge_weight).max()) if b.grad_edge_weight is not None else 0.0)
+    if big > 10.0:
+        pr.grad_cost = (pr.grad_cost * np.float32(10.0 / big)).astype(np.float32)
+    try:
+        for k, v in knobs.items():
+            assert mrf.mrf_tune(k, v) == 0
+        full_check(oracle, pr, want_V=want_V)
+    finally:
+        for k in knobs:
+            mrf.mrf_tune(k, 0)
