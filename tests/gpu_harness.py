@@ -9,7 +9,7 @@ import paper_1910_10892_amd as mrf
 
 
 @dataclass
-class GpuRun:
+class DeviceResults:
     cost: np.ndarray
     labels: np.ndarray
     p: np.ndarray
@@ -65,17 +65,17 @@ class GpuProblem:
             x.fill_(173)
         self.workspace.fill_(0xFF)
 
-    def results(self, backward=True) -> GpuRun:
+    def results(self, backward=True) -> DeviceResults:
         torch.cuda.synchronize()
         n = lambda x: None if x is None else x.cpu().numpy()
-        out = GpuRun(n(self.cost), n(self.labels), n(self.p), n(self.q), n(self.messages))
+        out = DeviceResults(n(self.cost), n(self.labels), n(self.p), n(self.q), n(self.messages))
         if backward:
             out.grad_unary, out.grad_edge_weight, out.grad_pairwise = (
                 n(self.grad_unary), n(self.grad_edge_weight), n(self.grad_pairwise))
         return out
 
 
-def run_gpu(pr, backward=True, want_V=True) -> GpuRun:
+def run_gpu(pr, backward=True, want_V=True) -> DeviceResults:
     g = GpuProblem(pr)
     g.poison_outputs()
     g.forward()
