@@ -226,20 +226,31 @@ int window_width(const mrf_problem *pr)
     return ti <= 2 ? 2 : (ti <= 8 ? 8 : 16);
 }
 
-template <int SEG>
-hipError_t launch_packed(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
+template <int SEG, int MU>
+hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_packed";
     const unsigned blocks = (unsigned)((scanlines + 64 / SEG - 1) / (64 / SEG));
 #define MRF_P(rm, d) \
     if (rmax == rm) { \
-        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, rm, d, true>), dim3(blocks), dim3(64), 0, st, P); \
-        else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, rm, d, false>), dim3(blocks), dim3(64), 0, st, P); \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true>), dim3(blocks), dim3(64), 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false>), dim3(blocks), dim3(64), 0, st, P); \
         return hipGetLastError(); \
     }
     MRF_P(4, 4) MRF_P(8, 2) MRF_P(16, 1)
 #undef MRF_P
     return hipErrorInvalidValue;
+}
+
+template <int SEG>
+hipError_t launch_packed(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
+{
+    g_last_sweep[0] = "mrf_fwd_sweep_packed";
+    // source labels per node: L rounded up to a multiple of four
+    const int mu = (P.g.L + 3) / 4 * 4;
+    if (mu <= SEG - 12) return launch_packed_mu<SEG, SEG - 12>(P, algo, rmax, scanlines, st);
+    if (mu <= SEG - 8) return launch_packed_mu<SEG, SEG - 8>(P, algo, rmax, scanlines, st);
+    if (mu <= SEG - 4) return launch_packed_mu<SEG, SEG - 4>(P, algo, rmax, scanlines, st);
+    return launch_packed_mu<SEG, SEG>(P, algo, rmax, scanlines, st);
 }
 
 hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)

@@ -1763,10 +1763,12 @@ __device__ inline float mrf_segment_min(float v)
     return v;
 }
 
-template <int SEG, int RMAX, int D, bool TRWP>
+// MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG)
+template <int SEG, int MU, int RMAX, int D, bool TRWP>
 __global__ void __launch_bounds__(64)
 mrf_fwd_sweep_packed(const MrfFwdParams P)
 {
+    static_assert(MU % 4 == 0 && MU <= SEG, "source label count");
     constexpr int NSEG = 64 / SEG;
     constexpr int SEGP = SEG + 4;                 // row stride: keeps the segments on different banks
     __shared__ __align__(16) float hseg[NSEG][SEGP];
@@ -1821,9 +1823,9 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 #pragma unroll
     for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
 
-    float Vr[SEG];
+    float Vr[MU];
 #pragma unroll
-    for (int mu = 0; mu < SEG; ++mu) Vr[mu] = (mu < L && valid) ? P.V[(size_t)mu * L + lam] : 0.0f;
+    for (int mu = 0; mu < MU; ++mu) Vr[mu] = (mu < L && valid) ? P.V[(size_t)mu * L + lam] : 0.0f;
     hseg[seg][lam] = INFINITY;                    // entries mu >= L stay +inf: they never win
     if (lam < 4) hseg[seg][SEG + lam] = INFINITY;
     __syncthreads();
@@ -1891,7 +1893,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             float best = INFINITY;
             int bidx = 0;
 #pragma unroll
-            for (int m4 = 0; m4 < SEG; m4 += 4) {
+            for (int m4 = 0; m4 < MU; m4 += 4) {
                 const float4 hv = *reinterpret_cast<const float4 *>(&hseg[seg][m4]);
                 const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
 #pragma unroll
