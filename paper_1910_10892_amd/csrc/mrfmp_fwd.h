@@ -1890,19 +1890,23 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             if (valid) hseg[seg][lam] = v;
             mrf_wave_lds_fence();
 
-            float best = INFINITY;
-            int bidx = 0;
+            // all candidates, their minimum with three-operand minima, then the lowest index
+            // that attains it (scanning downwards, so the lowest survives)
+            float dl[MU];
 #pragma unroll
             for (int m4 = 0; m4 < MU; m4 += 4) {
                 const float4 hv = *reinterpret_cast<const float4 *>(&hseg[seg][m4]);
                 const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float dlt = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
-                    if (dlt < best) { best = dlt; bidx = m4 + c; }
-                }
+                for (int c = 0; c < 4; ++c) dl[m4 + c] = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
             }
             mrf_wave_lds_fence();
+            float best = mrf_min(dl[0], dl[1]);
+#pragma unroll
+            for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
+            int bidx = MU - 1;
+#pragma unroll
+            for (int m = MU - 2; m >= 0; --m) bidx = (dl[m] == best) ? m : bidx;
 
             const float tv = valid ? best : INFINITY;
             const float tq = mrf_segment_min<SEG>(tv);
