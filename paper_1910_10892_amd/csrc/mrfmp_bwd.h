@@ -910,6 +910,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     sbuf[lam] = 0.0;
     __syncthreads();
 
+    const bool any_unary = P.unary_dir >= P.r_first && P.unary_dir < P.r_first + P.r_count;
     const long long npacks = (P.total_scanlines + NSEG - 1) / NSEG;
     for (long long pk = blockIdx.x; pk < npacks; pk += gridDim.x) {
         const long long sl = pk * NSEG + seg;
@@ -1003,7 +1004,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
 #pragma unroll
                 for (int c = 0; c < NS; ++c) g = __builtin_fma(cG[c], (double)cur[u][c], g);
                 g = valid ? g : 0.0;
-                {
+                if (any_unary) {        // (uniform) some scanline of this launch forms grad theta
                     double accT = carry;
 #pragma unroll
                     for (int c = 0; c < NS; ++c) accT = __builtin_fma(cT[c], (double)cur[u][c], accT);
