@@ -84,6 +84,7 @@ int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
 int g_tune_loader = 0;     // loader wavefront in the window sweep: 0 auto, 1 never, 2 whenever possible
 int g_tune_squad = 0;      // index wavefronts next to the split layout: 0 by launch size, 1 never, 2 always
 int g_tune_squad_ni = 0;   // how many: 0 auto, 4, 8
+int g_tune_pack_idx = 0;   // index wavefront in the packed dense sweep: 0 by launch size, 1 never, 2 always
 int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
 int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
@@ -230,10 +231,17 @@ template <int SEG, int MU>
 hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((scanlines + 64 / SEG - 1) / (64 / SEG));
+    // few wavefronts in the launch: a second one per workgroup for the argmin tables and the stores
+    const bool idx = g_tune_pack_idx != 1 && (g_tune_pack_idx == 2 || blocks <= 1024);
 #define MRF_P(rm, d) \
     if (rmax == rm) { \
-        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true>), dim3(blocks), dim3(64), 0, st, P); \
-        else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false>), dim3(blocks), dim3(64), 0, st, P); \
+        if (idx) { \
+            if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true, true>), dim3(blocks), dim3(128), 0, st, P); \
+            else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false, true>), dim3(blocks), dim3(128), 0, st, P); \
+        } else { \
+            if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true, false>), dim3(blocks), dim3(64), 0, st, P); \
+            else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false, false>), dim3(blocks), dim3(64), 0, st, P); \
+        } \
         return hipGetLastError(); \
     }
     MRF_P(4, 4) MRF_P(8, 2) MRF_P(16, 1)
@@ -915,6 +923,7 @@ int mrf_tune(int knob, int value)
     if (knob == 6) { g_tune_chain = value; return MRF_OK; }
     if (knob == 8) { g_tune_loader = value; return MRF_OK; }
     if (knob == 9) { g_tune_squad = value; return MRF_OK; }
+    if (knob == 11) { g_tune_pack_idx = value; return MRF_OK; }
     if (knob == 10) { g_tune_squad_ni = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;

@@ -1763,17 +1763,25 @@ __device__ inline float mrf_segment_min(float v)
     return v;
 }
 
-// MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG)
-template <int SEG, int MU, int RMAX, int D, bool TRWP>
-__global__ void __launch_bounds__(64)
+// MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG).
+// IDX: a second wavefront per workgroup takes the argmin tables and the stores (as in
+// mrf_fwd_sweep_window_duo): the first computes values only and hands each node's h and
+// weights over through a ring in LDS.  For launches that leave most issue slots idle.
+template <int SEG, int MU, int RMAX, int D, bool TRWP, bool IDX>
+__global__ void __launch_bounds__(IDX ? 128 : 64)
 mrf_fwd_sweep_packed(const MrfFwdParams P)
 {
     static_assert(MU % 4 == 0 && MU <= SEG, "source label count");
     constexpr int NSEG = 64 / SEG;
     constexpr int SEGP = SEG + 4;                 // row stride: keeps the segments on different banks
-    __shared__ __align__(16) float hseg[NSEG][SEGP];
+    constexpr int NR = IDX ? 8 : 1;               // ring slots (IDX), else the one working row set
+    static_assert(NR >= D || !IDX, "ring depth");
+    __shared__ __align__(16) float hring[NR][NSEG][SEGP];
+    __shared__ float wring[NR][64];
+    __shared__ int produced, consumed;
     const int L = P.g.L;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const bool index_wave = IDX && __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) > 0;
     const int seg = lane / SEG, lam = lane % SEG;
     const bool valid = lam < L;
     const int lamc = valid ? lam : 0;
@@ -1826,11 +1834,17 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     float Vr[MU];
 #pragma unroll
     for (int mu = 0; mu < MU; ++mu) Vr[mu] = (mu < L && valid) ? P.V[(size_t)mu * L + lam] : 0.0f;
-    hseg[seg][lam] = INFINITY;                    // entries mu >= L stay +inf: they never win
-    if (lam < 4) hseg[seg][SEG + lam] = INFINITY;
+    if (!index_wave) {
+#pragma unroll
+        for (int sl2 = 0; sl2 < NR; ++sl2) {
+            hring[sl2][seg][lam] = INFINITY;      // entries mu >= L stay +inf: they never win
+            if (lam < 4) hring[sl2][seg][SEG + lam] = INFINITY;
+        }
+        if (lane == 0) { produced = 0; consumed = 0; }
+    }
     __syncthreads();
 
-    if (act_seg && valid) {
+    if ((!IDX || index_wave) && act_seg && valid) {
         P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
         P.p[((size_t)r * N + head) * L + lam] = 0;
         if (lam == 0) P.q[(size_t)r * N + head] = 0;
@@ -1842,6 +1856,51 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     for (int sg = 0; sg < NSEG; ++sg) {
         const int l2 = __builtin_amdgcn_readlane(len, sg * SEG);
         maxlen = l2 > maxlen ? l2 : maxlen;
+    }
+
+    if (index_wave) {
+        // ---- p, q and all stores, one node behind or more ----------------------------------
+        int seen = 0;
+        for (int nn = 1; nn < maxlen; ++nn) {
+            while (seen < nn) {
+                seen = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (seen < nn) __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            const int slot = nn & (NR - 1);
+            const bool act = act_seg && nn < len;
+            const long long i = head + (long long)nn * nstep;
+            const float wgt = wring[slot][lane];
+            float dl[MU];
+#pragma unroll
+            for (int m4 = 0; m4 < MU; m4 += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(&hring[slot][seg][m4]);
+                const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dl[m4 + c] = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            if (lane == 0) __hip_atomic_store(&consumed, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            float best = mrf_min(dl[0], dl[1]);
+#pragma unroll
+            for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
+            int bidx = MU - 1;
+#pragma unroll
+            for (int m = MU - 2; m >= 0; --m) bidx = (dl[m] == best) ? m : bidx;
+            const float tv = valid ? best : INFINITY;
+            const float tq = mrf_segment_min<SEG>(tv);
+            const unsigned long long bal = __ballot(tv == tq);
+            const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
+            const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
+            const int qidx = __ffs((int)mine) - 1;
+            if (act && valid) {
+                P.m_out[((size_t)r * N + i) * L + lam] = tv - tq;
+                P.p[((size_t)r * N + i) * L + lam] = (uint8_t)bidx;
+                if (lam == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+            }
+        }
+        return;
     }
 
     const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
@@ -1860,6 +1919,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
 
     float carry = 0.0f;
+    int freed = 0;          // every step <= freed has been read by the index wavefront (possibly stale view)
     for (int n0 = 1; n0 < maxlen; n0 += D) {
 #pragma unroll
         for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
@@ -1887,7 +1947,18 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 #pragma unroll
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
             }
-            if (valid) hseg[seg][lam] = v;
+            const int slot = IDX ? (nn & (NR - 1)) : 0;
+            if (IDX) {
+                // the slot was last used by step nn - NR
+                while (freed < nn - NR) {
+                    freed = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(&consumed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                }
+                wring[slot][lane] = wgt;
+            }
+            if (valid) hring[slot][seg][lam] = v;
             mrf_wave_lds_fence();
 
             // all candidates, their minimum with three-operand minima, then the lowest index
@@ -1895,26 +1966,33 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             float dl[MU];
 #pragma unroll
             for (int m4 = 0; m4 < MU; m4 += 4) {
-                const float4 hv = *reinterpret_cast<const float4 *>(&hseg[seg][m4]);
+                const float4 hv = *reinterpret_cast<const float4 *>(&hring[slot][seg][m4]);
                 const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
 #pragma unroll
                 for (int c = 0; c < 4; ++c) dl[m4 + c] = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
             }
-            mrf_wave_lds_fence();
+            if (IDX) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                __builtin_amdgcn_wave_barrier();
+                if (lane == 0) __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else {
+                mrf_wave_lds_fence();
+            }
             float best = mrf_min(dl[0], dl[1]);
 #pragma unroll
             for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
+            const float tv = valid ? best : INFINITY;
+            const float tq = mrf_segment_min<SEG>(tv);
+            carry = valid ? tv - tq : 0.0f;
+            if (IDX) continue;                    // the index wavefront does the rest
+
             int bidx = MU - 1;
 #pragma unroll
             for (int m = MU - 2; m >= 0; --m) bidx = (dl[m] == best) ? m : bidx;
-
-            const float tv = valid ? best : INFINITY;
-            const float tq = mrf_segment_min<SEG>(tv);
             const unsigned long long bal = __ballot(tv == tq);
             const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
             const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
             const int qidx = __ffs((int)mine) - 1;
-            carry = valid ? tv - tq : 0.0f;
 
             if (act && valid) {
                 P.m_out[((size_t)r * N + i) * L + lam] = carry;

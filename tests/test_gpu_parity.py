@@ -324,12 +324,16 @@ def test_packed_scanlines_layout(oracle, case):
     try:
         assert mrf.mrf_tune(3, 1) == 0
         a = full_check(oracle, pr)
-        assert mrf.mrf_tune(3, 2) == 0
+        assert mrf.mrf_tune(3, 2) == 0 and mrf.mrf_tune(11, 1) == 0      # packed, one wavefront does all
         b = full_check(oracle, pr)
+        assert mrf.mrf_tune(11, 2) == 0                                  # packed, value + index wavefront
+        c = full_check(oracle, pr)
     finally:
         mrf.mrf_tune(3, 0)
+        mrf.mrf_tune(11, 0)
     for name in ("p", "q", "labels", "cost", "messages"):
         np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
+        np.testing.assert_array_equal(getattr(a, name), getattr(c, name), err_msg=name)
 
 
 def test_optional_outputs_may_be_null(oracle):
@@ -475,7 +479,8 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     rng = np.random.default_rng(9000 + seed)
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8])),
-             8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8]))}
+             8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
+             11: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
