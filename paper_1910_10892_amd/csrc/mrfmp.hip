@@ -492,12 +492,20 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
 {
     g_last_sweep[1] = "mrf_bwd_sweep_chain";
     const dim3 grid((unsigned)P.total_scanlines);
-    const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg);
+    const bool gv = P.gV != nullptr;
+    if (gv && (LP != 1 || P.g.L > 32 || P.total_scanlines * ni > grad_slots(P.g.L))) return hipErrorInvalidValue;
+    const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg, gv);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
 #define MRF_CH(n) \
     if (ni == n) { \
-        if (vg) hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, true>), grid, dim3(64 * (1 + n)), lds, st, P); \
-        else hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
+        if constexpr (LP == 1) { \
+            if (gv) { \
+                hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false, true>), grid, dim3(64 * (1 + n)), lds, st, P); \
+                return hipGetLastError(); \
+            } \
+        } \
+        if (vg) hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, true, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
+        else hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
         return hipGetLastError(); \
     }
     MRF_CH(2) MRF_CH(4) MRF_CH(6) MRF_CH(8)
@@ -544,23 +552,31 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
         if (P.n_src[r] + (P.use_gc ? 1 : 0) > need) need = P.n_src[r] + (P.use_gc ? 1 : 0);
     const int ns = need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 8 ? 8 : 16));
-    // few labels: several scanlines per wavefront
-    if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256))
-        return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     // few scanlines: the node-to-node chain on a wavefront of its own, helpers around it
-    // (its addressing wants a node step times L in 32 bits)
+    // (its addressing wants a node step times L in 32 bits; with the V gradient, L <= 32 and
+    // a slot per helper)
     bool step_fits = true;
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r) {
         const long long stp = ((long long)mrf_iabs(P.g.dh[r]) * P.g.W + mrf_iabs(P.g.dw[r])) * L;
         if (stp > 0x7fffffffLL) step_fits = false;
     }
-    if (step_fits && !P.gV && ns <= 8 && g_tune_chain != 1 &&
-        (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512))) {
-        // as many helpers as keep up with the chain while the machine and the LDS have room
-        int ni = g_tune_chain_ni ? g_tune_chain_ni
-                                 : (P.total_scanlines <= 512 ? 8 : (P.total_scanlines <= 1024 ? 6 : 4));
-        const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
-        while (ni > 2 && mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg) > 64 * 1024) ni -= 2;
+    const bool gv = P.gV != nullptr;
+    // as many helpers as keep up with the chain while the machine and the LDS have room
+    int ni = g_tune_chain_ni ? g_tune_chain_ni
+                             : (P.total_scanlines <= 512 ? 8 : (P.total_scanlines <= 1024 ? 6 : 4));
+    if (!g_tune_chain_ni && gv && P.total_scanlines > 384 && ni > 6) ni = 6;   // (the accumulators take LDS)
+    const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
+    while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > 64 * 1024 ||
+                      (gv && P.total_scanlines * ni > grad_slots(L)))) ni -= 2;
+    const bool chain_fits = step_fits && ns <= 8 && g_tune_chain != 1 &&
+                            (!gv || (L <= 32 && P.total_scanlines * ni <= grad_slots(L))) &&
+                            mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= 64 * 1024;
+    const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512));
+    // few labels: several scanlines per wavefront, once there are enough of them
+    if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
+        !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= 1024)))
+        return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
+    if (chain) {
 #define MRF_CCASE(lp) \
         if (LP == lp && ns == 1) return launch_bwd_chain<lp, 1, 2>(P, ni, vg, st); \
         if (LP == lp && ns == 4) return launch_bwd_chain<lp, 4, (lp <= 2 ? 2 : 1)>(P, ni, vg, st); \

@@ -29,7 +29,7 @@
 // Kernels in this file:
 //   mrf_bwd_sweep          one wavefront per scanline (the description above)
 //   mrf_bwd_sweep_chain    the node-to-node chain on a wavefront of its own, helper wavefronts
-//                          for everything else (launches with few scanlines, no V gradient)
+//                          for everything else (launches with few scanlines)
 //   mrf_bwd_sweep_split    one wavefront per 64 labels in lock step
 //   mrf_bwd_sweep_packed   L <= 32: several scanlines per wavefront
 //   mrf_isgmr_bwd_combine  ISGMR's sums over directions between two iterations
@@ -75,11 +75,12 @@ struct MrfBwdParams {
 #define MRF_CHAIN_MAX_HELPERS 8
 
 // dynamic LDS of mrf_bwd_sweep_chain (host and device agree through this one expression)
-__host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L, bool with_theta, bool vg)
+__host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L, bool with_theta, bool vg, bool gv)
 {
     const size_t NR = 2 * (size_t)NI, LL = 64 * (size_t)LP;
-    return sizeof(double) * (3 * NR * LL + LL) + sizeof(float) * (with_theta ? NR * LL : 0) +
-           sizeof(int) * (MRF_CHAIN_MAX_HELPERS + 1) + sizeof(float) * (vg ? 0 : (size_t)L) + NR * LL;
+    return sizeof(double) * (3 * NR * LL + LL + (gv ? (size_t)NI * L * L : 0)) +
+           sizeof(float) * (with_theta ? NR * LL : 0) + sizeof(int) * (MRF_CHAIN_MAX_HELPERS + 1) +
+           sizeof(float) * (gv ? (size_t)L * L : (vg ? 0 : (size_t)L)) + NR * LL;
 }
 
 // LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
@@ -370,8 +371,9 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 // step late; with NI >= 2 no wait can depend on itself: post(t - 2 NI), which precedes
 // pre(t) in its helper, needs the chain to have passed step t - 2 NI + 1 only.
 //
-// Not for launches that also want the V gradient.
-template <int LP, int NS, int D, int NI, bool VG>
+// GV (L <= 32): the launch also wants the V gradient; every helper keeps an accumulator of
+// its own in LDS, lane lambda owning column lambda, and adds it to its own slot at the end.
+template <int LP, int NS, int D, int NI, bool VG, bool GV>
 __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBwdParams P)
 {
     constexpr int NR = 2 * NI;
@@ -383,18 +385,23 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     double *b_cin = a_ext + NR * LL;                             // [NR][LL] chain -> post: carry that entered the node
     double *b_sv = b_cin + NR * LL;                              // [NR][LL]                scattered vector that left it
     double *sbuf = b_sv + NR * LL;                               // [LL] scatter target of the chain
-    float *a_extT = reinterpret_cast<float *>(sbuf + LL);        // [NR][LL] pre -> post (launches that form grad theta)
+    double *gvacc = sbuf + LL;                                   // [NI][L*L] V-gradient accumulators (GV)
+    float *a_extT = reinterpret_cast<float *>(gvacc + (GV ? NI * P.g.L * P.g.L : 0));   // [NR][LL] pre -> post (launches that form grad theta)
     int *pre_done = reinterpret_cast<int *>(a_extT + (P.unary_dir >= 0 ? NR * LL : 0));   // [MRF_CHAIN_MAX_HELPERS] per helper: last step published
     int *chain_done = pre_done + MRF_CHAIN_MAX_HELPERS;          // last step the chain finished
-    float *vl = reinterpret_cast<float *>(chain_done + 1);       // [L] first row of V (unless VG)
-    uint8_t *a_p = reinterpret_cast<uint8_t *>(vl + (VG ? 0 : P.g.L));   // [NR][LL]
+    float *vl = reinterpret_cast<float *>(chain_done + 1);       // [L] first row of V (unless VG), all of V (GV)
+    uint8_t *a_p = reinterpret_cast<uint8_t *>(vl + (GV ? P.g.L * P.g.L : (VG ? 0 : P.g.L)));   // [NR][LL]
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     const long long N = P.g.N;
 
-    if (!VG)
+    if (GV) {
+        for (int e = threadIdx.x; e < L * L; e += blockDim.x) vl[e] = P.V[e];
+        for (int e = threadIdx.x; e < NI * L * L; e += blockDim.x) gvacc[e] = 0.0;
+    } else if (!VG) {
         for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
+    }
     if (threadIdx.x < MRF_CHAIN_MAX_HELPERS) pre_done[threadIdx.x] = (int)threadIdx.x - NI;
     if (threadIdx.x == 0) *chain_done = -1;
     for (int e = threadIdx.x; e < LL; e += blockDim.x) sbuf[e] = 0.0;
@@ -538,6 +545,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     float ucur[D][LP], unxt[D][LP];
     int pcur[D][LP], pnxt[D][LP];
     int qcur[D], qnxt[D];
+    float wcur[D], wnxt[D];                 // edge weight of the node's incoming edge (GV)
     // addresses relative to the head of the scanline: one 32 x 32 bit product per node (the
     // host has checked that a node step times L fits 32 bits)
     const int step_l = (int)nstep * L;
@@ -549,7 +557,9 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     const int step_u = unary_old ? step_l : 0;
     const uint8_t *pb = pbase + (size_t)head * L;
     const uint8_t *qb = qbase + (size_t)head;
-    auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, int it) {
+    const float *wb = P.w + (P.w_mul ? (size_t)r * N + head : 0);
+    const int step_w = P.w_mul ? step_n : 0;
+    auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, float &wdst, int it) {
         int n = len - 1 - (jw + it * NI);
         n = n > 0 ? n : 0;
         const long long o = (long long)n * step_l;
@@ -564,11 +574,14 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
             pdst[s] = pb[o + lc];
         }
         qdst = qb[(long long)n * step_n + vzero];
+        wdst = GV ? wb[(long long)n * step_w + vzero] : 0.0f;
     };
     if (T > 0) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], u);
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
     }
+    double *gvl = gvacc + (GV ? jw * L * L : 0);
+    float wlast = 0.0f;                     // weight of the node whose post stage comes next
     float *guw = P.gunary + (size_t)head * L;                       // stores of stage "post"
     float *sw = P.S + ((size_t)r * N + head) * L;
     float *gww = P.gw ? P.gw + (size_t)r * N + head : nullptr;
@@ -576,7 +589,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     int chain_seen = -1;
     for (int it0 = 0; it0 < T + 1 && T > 0; it0 += D) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], it0 + D + u);
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], it0 + D + u);
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             const int tt = jw + (it0 + u) * NI;
@@ -638,17 +651,23 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     if (own_unary && lam < L)
                         guw[oi + lam] = (float)(cin + (double)a_extT[slot * LL + lam]);
                     if (update && lam < L) sw[oj + lam] = (float)b_sv[slot * LL + lam];
-                    if (P.gw && lam < L) {
+                    if ((P.gw || GV) && lam < L) {
                         const double g = cin + a_ext[slot * LL + lam];    // as the chain formed it
                         const int pv = a_p[slot * LL + lam];
-                        float vv;
-                        if (VG) {
-                            vv = P.V[(size_t)pv * L + lam];
-                        } else {
-                            const int dist = pv > lam ? pv - lam : lam - pv;
-                            vv = vl[dist];
+                        if (P.gw) {
+                            float vv;
+                            if (GV) {
+                                vv = vl[pv * L + lam];
+                            } else if (VG) {
+                                vv = P.V[(size_t)pv * L + lam];
+                            } else {
+                                const int dist = pv > lam ? pv - lam : lam - pv;
+                                vv = vl[dist];
+                            }
+                            acc = __builtin_fma(g, (double)vv, acc);
                         }
-                        acc = __builtin_fma(g, (double)vv, acc);
+                        if (GV && update)
+                            gvl[pv * L + lam] = __builtin_fma((double)wlast, g, gvl[pv * L + lam]);
                     }
                 }
                 if (P.gw) {
@@ -659,10 +678,12 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                                                __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
+            wlast = wcur[u];
         }
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             qcur[u] = qnxt[u];
+            wcur[u] = wnxt[u];
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 ucur[u][s] = unxt[u][s];
@@ -671,6 +692,12 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                 for (int c = 0; c < NS; ++c) cur[u][c][s] = nxt[u][c][s];
             }
         }
+    }
+    if (GV) {
+        // one slot per helper of every workgroup
+        mrf_wave_lds_fence();
+        double *gVs = P.gV + ((size_t)blockIdx.x * NI + jw) * L * L;
+        for (int e = lane; e < L * L; e += 64) gVs[e] += gvl[e];
     }
 }
 

@@ -247,6 +247,47 @@ def test_chain_wavefront_backward_layout(oracle, case):
                                        err_msg="%d helpers, %s" % (ni, name))
 
 
+CHAIN_GV_CASES = [
+    # seed, algo, B, H, W, L, dirs, K, integer_valued, per_edge
+    (91, "trwp", 2, 6, 40, 21, DIRS4, 2, False, True),
+    (92, "isgmr", 1, 5, 33, 32, DIRS8, 2, True, True),
+    (93, "trwp", 1, 9, 4, 2, DIRS4, 3, False, False),
+    (94, "trwp", 1, 1, 13, 17, DIRS8, 2, True, True),       # one row: most scanlines have one node
+    (95, "isgmr", 3, 4, 7, 1, DIRS4, 2, False, True),
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_GV_CASES, ids=lambda c: "seed%d" % c[0])
+def test_chain_wavefront_backward_with_pairwise_gradient(oracle, case):
+    """The chain layout when grad_pairwise is asked for (L <= 32: every helper wavefront keeps a
+    V-gradient accumulator of its own): 2, 4, 6, 8 helpers against the oracle and against the
+    one-wavefront sweep."""
+    import paper_1910_10892_amd as mrf
+    print("case chain backward with grad V", case[:8], flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv, pe = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=pe,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    got = {}
+    try:
+        assert mrf.mrf_tune(3, 1) == 0
+        assert mrf.mrf_tune(6, 1) == 0
+        got[0] = full_check(oracle, pr, want_V=True)
+        assert mrf.mrf_last_sweep_kernel(1) == "mrf_bwd_sweep"
+        assert mrf.mrf_tune(6, 2) == 0
+        for ni in (2, 4, 6, 8):
+            assert mrf.mrf_tune(7, ni) == 0
+            got[ni] = full_check(oracle, pr, want_V=True)
+            assert mrf.mrf_last_sweep_kernel(1) == "mrf_bwd_sweep_chain"
+    finally:
+        mrf.mrf_tune(3, 0)
+        mrf.mrf_tune(6, 0)
+        mrf.mrf_tune(7, 0)
+    for ni in (2, 4, 6, 8):
+        for name in ("grad_unary", "grad_edge_weight", "grad_pairwise"):
+            np.testing.assert_allclose(getattr(got[ni], name), getattr(got[0], name), rtol=1e-5, atol=1e-4,
+                                       err_msg="%d helpers, %s" % (ni, name))
+
+
 @pytest.mark.parametrize("index,crop,algo,K", [c for c in CONFIG_CASES if c[0] != 5])
 def test_benchmark_configs_cropped_without_pairwise_gradient(oracle, index, crop, algo, K):
     """The truncated models have no free parameters in V: run them the way bench.py does."""
