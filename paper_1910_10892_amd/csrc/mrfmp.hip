@@ -597,7 +597,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         return launch_bwd_split<8, 2>(P, sblocks, slds, st);
     }
 #define MRF_BCASE(lp) \
-    if (LP == lp && ns == 1) return launch_bwd<lp, 1, 4>(P, blocks, lds, st); \
+    if (LP == lp && ns == 1) return launch_bwd<lp, 1, (lp >= 3 ? 2 : 4)>(P, blocks, lds, st); \
     if (LP == lp && ns == 4) return launch_bwd<lp, 4, (lp <= 2 ? 4 : 2)>(P, blocks, lds, st); \
     if (LP == lp && ns == 8) return launch_bwd<lp, 8, 2>(P, blocks, lds, st); \
     if (LP == lp && ns == 16) return launch_bwd<lp, 16, 1>(P, blocks, lds, st);
