@@ -219,6 +219,8 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           1 = never, 2 = always
  *   knob 8: loader wavefront in front of the value wavefront (TRWP, window sweep, two index
  *           wavefronts): 0 = by launch size, 1 = never, 2 = whenever it applies
+ *   knob 12: in the sweep of knob 6, sum the lanes of the most popular scatter target in registers
+ *           (truncated models): 0 = by launch shape, 1 = never, 2 = whenever V is not a dense table
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

@@ -86,6 +86,7 @@ int g_tune_squad = 0;      // index wavefronts next to the split layout: 0 by la
 int g_tune_squad_ni = 0;   // how many: 0 auto, 4, 8
 int g_tune_pack_idx = 0;   // index wavefront in the packed dense sweep: 0 by launch size, 1 never, 2 always
 int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
+int g_tune_chain_hot = 0;  // its pre-reduction of the most popular scatter target: 0 auto, 1 never, 2 whenever V is no dense table
 int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
@@ -487,6 +488,15 @@ hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds,
     return hipGetLastError();
 }
 
+// LDS a workgroup of the chain sweep may take: the whole 160 KB of a compute unit when every
+// compute unit gets at most one workgroup, half when two, else the 64 KB any launch may have.
+inline size_t chain_lds_cap(long long scanlines)
+{
+    if (scanlines <= 256) return 156 * 1024;
+    if (scanlines <= 512) return 78 * 1024;
+    return 64 * 1024;
+}
+
 template <int LP, int NS, int D>
 hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t st)
 {
@@ -495,21 +505,33 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
     const bool gv = P.gV != nullptr;
     if (gv && (LP != 1 || P.g.L > 32 || P.total_scanlines * ni > grad_slots(P.g.L))) return hipErrorInvalidValue;
     const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg, gv);
-    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    if (lds > chain_lds_cap(P.total_scanlines)) return hipErrorInvalidValue;
+    // (more than 64 KB of dynamic LDS has to be announced per kernel)
+#define MRF_CH_GO(...) \
+    do { \
+        if (lds > 64 * 1024) { \
+            const hipError_t ea_ = hipFuncSetAttribute(reinterpret_cast<const void *>(&__VA_ARGS__), \
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (ea_ != hipSuccess) return ea_; \
+        } \
+        hipLaunchKernelGGL((__VA_ARGS__), grid, dim3(64 * (1 + ni)), lds, st, P); \
+    } while (0)
 #define MRF_CH(n) \
     if (ni == n) { \
         if constexpr (LP == 1) { \
             if (gv) { \
-                hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false, true>), grid, dim3(64 * (1 + n)), lds, st, P); \
+                MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, false, true, false>); \
                 return hipGetLastError(); \
             } \
         } \
-        if (vg) hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, true, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
-        else hipLaunchKernelGGL((mrf_bwd_sweep_chain<LP, NS, D, n, false, false>), grid, dim3(64 * (1 + n)), lds, st, P); \
+        if (vg) MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, true, false, false>); \
+        else if (P.hot_label) MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, false, false, true>); \
+        else MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, false, false, false>); \
         return hipGetLastError(); \
     }
     MRF_CH(2) MRF_CH(4) MRF_CH(6) MRF_CH(8)
 #undef MRF_CH
+#undef MRF_CH_GO
     return hipErrorInvalidValue;
 }
 
@@ -566,17 +588,22 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
                              : (P.total_scanlines <= 512 ? 8 : (P.total_scanlines <= 1024 ? 6 : 4));
     if (!g_tune_chain_ni && gv && P.total_scanlines > 384 && ni > 6) ni = 6;   // (the accumulators take LDS)
     const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
-    while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > 64 * 1024 ||
+    while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > chain_lds_cap(P.total_scanlines) ||
                       (gv && P.total_scanlines * ni > grad_slots(L)))) ni -= 2;
     const bool chain_fits = step_fits && ns <= 8 && g_tune_chain != 1 &&
                             (!gv || (L <= 32 && P.total_scanlines * ni <= grad_slots(L))) &&
-                            mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= 64 * 1024;
+                            mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512));
     // few labels: several scanlines per wavefront, once there are enough of them
     if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
         !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= 1024)))
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     if (chain) {
+        // truncated models: the chain wavefront sums the lanes of the most popular scatter target
+        // in registers
+        // where LDS throughput, not the latency of the chain, bounds the launch
+        P.hot_label = (pairwise_kind != MRF_PAIRWISE_DENSE && !gv && g_tune_chain_hot != 1 &&
+                       (g_tune_chain_hot == 2 || L > 128 || P.total_scanlines > 1024)) ? 1 : 0;
 #define MRF_CCASE(lp) \
         if (LP == lp && ns == 1) return launch_bwd_chain<lp, 1, 2>(P, ni, vg, st); \
         if (LP == lp && ns == 4) return launch_bwd_chain<lp, 4, (lp <= 2 ? 2 : 1)>(P, ni, vg, st); \
@@ -937,6 +964,7 @@ int mrf_tune(int knob, int value)
     if (knob == 4) { g_tune_duo = value; return MRF_OK; }
     if (knob == 5) { g_tune_duo_ni = (value == 1 || value == 2) ? value : 0; return MRF_OK; }
     if (knob == 6) { g_tune_chain = value; return MRF_OK; }
+    if (knob == 12) { g_tune_chain_hot = value; return MRF_OK; }
     if (knob == 8) { g_tune_loader = value; return MRF_OK; }
     if (knob == 9) { g_tune_squad = value; return MRF_OK; }
     if (knob == 11) { g_tune_pack_idx = value; return MRF_OK; }

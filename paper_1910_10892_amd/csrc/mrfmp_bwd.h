@@ -79,7 +79,7 @@ __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L,
 {
     const size_t NR = 2 * (size_t)NI, LL = 64 * (size_t)LP;
     return sizeof(double) * (3 * NR * LL + LL + (gv ? (size_t)NI * L * L : 0)) +
-           sizeof(float) * (with_theta ? NR * LL : 0) + sizeof(int) * (MRF_CHAIN_MAX_HELPERS + 1) +
+           sizeof(float) * (with_theta ? NR * LL : 0) + sizeof(int) * (3 * MRF_CHAIN_MAX_HELPERS + 1) +
            sizeof(float) * (gv ? (size_t)L * L : (vg ? 0 : (size_t)L)) + NR * LL;
 }
 
@@ -373,7 +373,12 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 //
 // GV (L <= 32): the launch also wants the V gradient; every helper keeps an accumulator of
 // its own in LDS, lane lambda owning column lambda, and adds it to its own slot at the end.
-template <int LP, int NS, int D, int NI, bool VG, bool GV>
+// HOT: truncated models send most labels to one source label, and the chain wavefront's LDS
+// adds would queue at that one word; the helpers guess it (as in mrf_bwd_sweep) and the chain
+// sums its lanes with a DPP tree while the LDS round trip is under way.  Costs the chain some
+// twenty instructions per node: for launches that are bound by LDS throughput, not by the
+// latency of the chain.
+template <int LP, int NS, int D, int NI, bool VG, bool GV, bool HOT>
 __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBwdParams P)
 {
     constexpr int NR = 2 * NI;
@@ -389,7 +394,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     float *a_extT = reinterpret_cast<float *>(gvacc + (GV ? NI * P.g.L * P.g.L : 0));   // [NR][LL] pre -> post (launches that form grad theta)
     int *pre_done = reinterpret_cast<int *>(a_extT + (P.unary_dir >= 0 ? NR * LL : 0));   // [MRF_CHAIN_MAX_HELPERS] per helper: last step published
     int *chain_done = pre_done + MRF_CHAIN_MAX_HELPERS;          // last step the chain finished
-    float *vl = reinterpret_cast<float *>(chain_done + 1);       // [L] first row of V (unless VG), all of V (GV)
+    int *a_hot = chain_done + 1;                                 // [NR] pre -> chain: most popular scatter target, or -1
+    float *vl = reinterpret_cast<float *>(a_hot + 2 * MRF_CHAIN_MAX_HELPERS);   // [L] first row of V (unless VG), all of V (GV)
     uint8_t *a_p = reinterpret_cast<uint8_t *>(vl + (GV ? P.g.L * P.g.L : (VG ? 0 : P.g.L)));   // [NR][LL]
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
@@ -445,6 +451,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
             ext[s] = a_ext[lane + 64 * s];
             pv[s] = a_p[lane + 64 * s];
         }
+        int hot = -1;
+        if (HOT) hot = __builtin_amdgcn_readfirstlane(a_hot[0]);
         int sb = 0;                         // slot of step t0 (t0 is a multiple of NI)
         for (int t0 = 0; t0 < len; t0 += NI) {
 #pragma unroll
@@ -457,12 +465,16 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     const bool more = tt + 1 < len;
                     // index scatter: s(mu) = sum over lambda with p(lambda) = mu (labels past L
                     // carry zeros to entries of their own)
+                    double hpart = 0.0;
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
                         const int lam = lane + 64 * s;
                         const double g = carry[s] + ext[s];
                         b_cin[slot * LL + lam] = carry[s];
-                        __hip_atomic_fetch_add(&sbuf[pv[s]], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        const bool ishot = HOT && pv[s] == hot;
+                        if (!ishot)
+                            __hip_atomic_fetch_add(&sbuf[pv[s]], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        if (HOT) hpart += ishot ? g : 0.0;
                     }
                     mrf_wave_lds_fence();
                     // In one batch behind the scatter: the counter of the next node's helper, then
@@ -472,14 +484,19 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     const int flag = __hip_atomic_load(&pre_done[un], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                     double sv[LP];
+                    int hotn = -1;
+                    if (HOT) hotn = a_hot[slotn];
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
                         ext[s] = a_ext[slotn * LL + lane + 64 * s];
                         pv[s] = a_p[slotn * LL + lane + 64 * s];
                         sv[s] = sbuf[lane + 64 * s];
                     }
+                    double hsum = 0.0;
+                    if (HOT) hsum = mrf_wave_sum_f64(hpart);
                     if (more && __builtin_amdgcn_readfirstlane(flag) < tt + 1) {
                         await(un, tt + 1);
+                        if (HOT) hotn = a_hot[slotn];
 #pragma unroll
                         for (int s = 0; s < LP; ++s) {
                             ext[s] = a_ext[slotn * LL + lane + 64 * s];
@@ -493,10 +510,12 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                         __hip_atomic_store(chain_done, tt - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
+                        if (HOT && lane + 64 * s == hot) sv[s] += hsum;
                         sbuf[lane + 64 * s] = 0.0;
                         b_sv[slot * LL + lane + 64 * s] = sv[s];
                         carry[s] = cscale * sv[s];
                     }
+                    if (HOT) hot = __builtin_amdgcn_readfirstlane(hotn);
                 }
             }
             sb = (sb == 0) ? NI : 0;
@@ -614,6 +633,26 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     if (own_unary) a_extT[slot * LL + lam] = (float)eT;
                     // (labels past L scatter their zeros to entries of their own)
                     a_p[slot * LL + lam] = (uint8_t)(lam < L ? (pcur[u][s] < L ? pcur[u][s] : L - 1) : lam);
+                }
+                // the commoner of p at the first and at the last label: for a truncated model one
+                // of the two is far from the far-field minimiser and points to it
+                if (HOT) {
+                    int hot = -1;
+                    const int c0 = __builtin_amdgcn_readlane(pcur[u][0], 0);
+                    int c1 = c0;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s)
+                        if (((L - 1) >> 6) == s) c1 = __builtin_amdgcn_readlane(pcur[u][s], (L - 1) & 63);
+                    int n0 = 0, n1 = 0;
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const bool vld = lane + 64 * s < L;
+                        n0 += __popcll(__ballot(vld && pcur[u][s] == c0));
+                        n1 += __popcll(__ballot(vld && pcur[u][s] == c1));
+                    }
+                    hot = n1 > n0 ? c1 : c0;
+                    hot = hot < L ? hot : -1;
+                    if (lane == 0) a_hot[slot] = hot;
                 }
                 // back Eq. isgmr-norm, on the part of g that is known here: the entry at q loses
                 // the label sum

@@ -247,6 +247,50 @@ def test_chain_wavefront_backward_layout(oracle, case):
                                        err_msg="%d helpers, %s" % (ni, name))
 
 
+CHAIN_HOT_CASES = [
+    # seed, algo, B, H, W, L, dirs, K, kind, trunc, integer_valued
+    (101, "trwp", 1, 4, 60, 96, DIRS4, 2, 1, 8.0, False),
+    (102, "isgmr", 2, 3, 25, 40, DIRS8, 2, 1, 2.0, True),
+    (103, "trwp", 1, 6, 9, 130, DIRS8, 2, 2, 30.0, False),
+    (104, "isgmr", 1, 2, 31, 256, DIRS4, 3, 2, 200.0, False),
+    (105, "trwp", 1, 5, 5, 2, DIRS4, 2, 1, 1.0, True),
+    (106, "trwp", 1, 3, 40, 64, [(0, 1), (0, -1), (1, 1)], 2, 3, 2.0, False),
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_HOT_CASES, ids=lambda c: "seed%d" % c[0])
+def test_chain_wavefront_backward_hot_label(oracle, case):
+    """The chain layout on truncated models, where most labels scatter to one source label: with
+    and without the register sum of that label's lanes, 2 and 8 helpers, against the oracle and
+    against each other."""
+    import paper_1910_10892_amd as mrf
+    from mrf_inputs import truncated_linear, truncated_quadratic, sgm_penalties
+    print("case chain backward, hot label", case, flush=True)
+    seed, algo, B, H, W, L, dirs, K, kind, trunc, iv = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=True,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    scale = 1.0 if iv else 0.37
+    pr.pairwise = (truncated_linear(L, trunc, scale) if kind == 1 else
+                   truncated_quadratic(L, trunc, scale) if kind == 2 else sgm_penalties(L, 0.5, 2.0))
+    pr.pairwise_kind, pr.trunc, pr.scale = kind, trunc, scale
+    got = {}
+    try:
+        assert mrf.mrf_tune(6, 2) == 0
+        for hot in (1, 2):
+            for ni in (2, 8):
+                assert mrf.mrf_tune(12, hot) == 0 and mrf.mrf_tune(7, ni) == 0
+                got[hot, ni] = full_check(oracle, pr, want_V=False)
+                assert mrf.mrf_last_sweep_kernel(1) == "mrf_bwd_sweep_chain"
+    finally:
+        mrf.mrf_tune(6, 0)
+        mrf.mrf_tune(7, 0)
+        mrf.mrf_tune(12, 0)
+    for key in got:
+        for name in ("grad_unary", "grad_edge_weight"):
+            np.testing.assert_allclose(getattr(got[key], name), getattr(got[1, 2], name), rtol=1e-5, atol=1e-4,
+                                       err_msg="%s, %s" % (key, name))
+
+
 CHAIN_GV_CASES = [
     # seed, algo, B, H, W, L, dirs, K, integer_valued, per_edge
     (91, "trwp", 2, 6, 40, 21, DIRS4, 2, False, True),
@@ -521,7 +565,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
