@@ -26,8 +26,9 @@
  *  5. Alg. 3 lines 16-18 are read as "grad m-hat <- grad m" (Appendix D.3 item 2).
  *  6. If the opposite direction r- is not in the direction set its term is absent.
  *  7. V is indexed V[mu at the previous node i-r][lambda at node i] for every direction.
- *  8. rho is one value per direction; the edge weight of edge (i-r,i) in direction r is
- *     stored at node i.
+ *  8. rho is one value per direction, or (optional array) one value per directed edge as Eq.
+ *     trwp writes it; the edge weight and the per-edge rho of edge (i-r,i) in direction r
+ *     are stored at node i.
  *  9. Gradients of theta_i, theta_{i-r,i} and V accumulate over all iterations,
  *     directions and nodes (Appendix D.3 item 1).
  * Pins (tests/test_oracle_*.py): brute-force min-marginals on chains and trees,

@@ -81,8 +81,19 @@ def _common(unary_shape, dirs, dtype):
     return B, H, W, L, dirs, dirs.shape[0]
 
 
+def _rho_args(rho, rho_edge, R, shape, dtype):
+    """rho[R] and the optional per-edge array [R,B,H,W] (TRWP, Eq. trwp)."""
+    if rho is None:
+        rho = 1.0
+    rho_a = np.ascontiguousarray(np.broadcast_to(np.asarray(rho, dtype=dtype), (R,)))
+    rho_e = None if rho_edge is None else np.ascontiguousarray(rho_edge, dtype=dtype)
+    if rho_e is not None:
+        assert rho_e.shape == (R,) + tuple(shape)
+    return rho_a, rho_e
+
+
 def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_weight_scalar=1.0,
-            rho=None, dtype=np.float32, threads: bool = False) -> ForwardResult:
+            rho=None, dtype=np.float32, threads: bool = False, rho_edge=None) -> ForwardResult:
     """Alg. 1 (algo='isgmr') or Alg. 2 (algo='trwp')."""
     sfx, creal = _real(dtype)
     unary = np.ascontiguousarray(unary, dtype=dtype)
@@ -105,9 +116,9 @@ def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_wei
         fn = getattr(lib, "mrfo_isgmr_forward_" + sfx)
         rc = fn(*head, *tail)
     elif algo == "trwp":
-        rho_a = np.ascontiguousarray(np.broadcast_to(np.asarray(rho, dtype=dtype), (R,)))
+        rho_a, rho_e = _rho_args(rho, rho_edge, R, (B, H, W), dtype)
         fn = getattr(lib, "mrfo_trwp_forward_" + sfx)
-        rc = fn(*head, _ptr(rho_a), *tail)
+        rc = fn(*head, _ptr(rho_a), _ptr(rho_e), *tail)
     else:
         raise ValueError(algo)
     if rc != 0:
@@ -116,7 +127,7 @@ def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_wei
 
 
 def backward(algo: str, shape, pairwise, dirs, K: int, grad_cost, p, q, edge_weight=None,
-             edge_weight_scalar=1.0, rho=None, dtype=np.float32) -> BackwardResult:
+             edge_weight_scalar=1.0, rho=None, dtype=np.float32, rho_edge=None) -> BackwardResult:
     """Alg. 3 (algo='isgmr') or Alg. 4 (algo='trwp'); shape = (B,H,W,L)."""
     sfx, creal = _real(dtype)
     B, H, W, L, dirs, R = _common(shape, dirs, dtype)
@@ -137,8 +148,8 @@ def backward(algo: str, shape, pairwise, dirs, K: int, grad_cost, p, q, edge_wei
     if algo == "isgmr":
         rc = getattr(lib, "mrfo_isgmr_backward_" + sfx)(*head, *tail)
     elif algo == "trwp":
-        rho_a = np.ascontiguousarray(np.broadcast_to(np.asarray(rho, dtype=dtype), (R,)))
-        rc = getattr(lib, "mrfo_trwp_backward_" + sfx)(*head, _ptr(rho_a), *tail)
+        rho_a, rho_e = _rho_args(rho, rho_edge, R, (B, H, W), dtype)
+        rc = getattr(lib, "mrfo_trwp_backward_" + sfx)(*head, _ptr(rho_a), _ptr(rho_e), *tail)
     else:
         raise ValueError(algo)
     if rc != 0:

@@ -134,7 +134,7 @@ int NAME(mrfo_isgmr_forward)(int B, int H, int W, int L, int R, const int *dirs,
 /* ================================ Alg. 2 ======================================= */
 int NAME(mrfo_trwp_forward)(int B, int H, int W, int L, int R, const int *dirs, int K,
                             const REAL *unary, const REAL *V, const REAL *w, REAL w_scalar,
-                            const REAL *rho,
+                            const REAL *rho, const REAL *rho_edge,
                             REAL *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
                             REAL *messages)
 {
@@ -163,7 +163,9 @@ int NAME(mrfo_trwp_forward)(int B, int H, int W, int L, int R, const int *dirs, 
                     for (int mu = 0; mu < L; ++mu) {
                         REAL s = unary[j * L + mu];
                         for (int d = 0; d < R; ++d) s = s + m[((size_t)d * N + j) * L + mu];
-                        REAL a = rho[r] * s;
+                        /* rho_{i-r,i} of Eq. trwp: per edge where an array is given (stored like
+                         * the edge weight, at the node the edge arrives at), else per direction */
+                        REAL a = (rho_edge ? rho_edge[(size_t)r * N + i] : rho[r]) * s;
                         if (rm >= 0) a = a - m[((size_t)rm * N + j) * L + mu];
                         h[mu] = a;
                     }
@@ -267,7 +269,7 @@ int NAME(mrfo_isgmr_backward)(int B, int H, int W, int L, int R, const int *dirs
 /* ================================ Alg. 4 ======================================= */
 int NAME(mrfo_trwp_backward)(int B, int H, int W, int L, int R, const int *dirs, int K,
                              const REAL *V, const REAL *w, REAL w_scalar, const REAL *rho,
-                             const REAL *grad_cost, const uint8_t *p, const uint8_t *q,
+                             const REAL *rho_edge, const REAL *grad_cost, const uint8_t *p, const uint8_t *q,
                              REAL *grad_unary, REAL *grad_w, REAL *grad_V)
 {
     grid_t g;
@@ -300,7 +302,7 @@ int NAME(mrfo_trwp_backward)(int B, int H, int W, int L, int R, const int *dirs,
                                                      grad_V);
                     for (int lam = 0; lam < L; ++lam) {
                         int mu = pidx[lam];
-                        REAL sg = rho[r] * gl[lam];
+                        REAL sg = (rho_edge ? rho_edge[(size_t)r * N + i] : rho[r]) * gl[lam];
                         grad_unary[j * L + mu] = grad_unary[j * L + mu] + sg;
                         for (int d = 0; d < R; ++d)
                             G[((size_t)d * N + j) * L + mu] = G[((size_t)d * N + j) * L + mu] + sg;
