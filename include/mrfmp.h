@@ -84,9 +84,14 @@ typedef struct {
     const float *pairwise;      /* DEVICE [L][L] */
     const float *edge_weight;   /* DEVICE [R][B][H][W], or NULL => edge_weight_scalar on every edge */
     float edge_weight_scalar;
-    const float *rho;           /* HOST  [R] rho_{i-r,i} per direction; TRWP only, ignored by ISGMR */
+    const float *rho;           /* HOST  [R] rho_{i-r,i} per direction; TRWP only, ignored by ISGMR;
+                                   may be NULL if rho_edge is given */
     int32_t pairwise_kind;      /* MRF_PAIRWISE_* */
     float trunc, scale;         /* parameters of kinds 1, 2 and 3 (trunc > 0) */
+    const float *rho_edge;      /* DEVICE [R][B][H][W] or NULL: rho_{i-r,i} per directed edge as Eq. trwp
+                                   writes it, entry (r,i) like edge_weight (first-node entries are never
+                                   read); takes the place of rho[]; TRWP only.  Such problems run
+                                   through the one-wavefront-per-scanline sweeps. */
 } mrf_problem;
 
 /* Bytes of DEVICE workspace (256-byte aligned base required) that the forward

@@ -41,6 +41,7 @@ class Problem:
     trunc: float = 0.0
     scale: float = 1.0
     meta: dict = field(default_factory=dict)
+    rho_edge: Optional[np.ndarray] = None      # [R,B,H,W] float32 (TRWP): rho per directed edge, or None
 
     @property
     def shape(self):

@@ -38,7 +38,7 @@ int check_problem(const mrf_problem *pr, int algo, bool forward)
     if (N > 0x7fffffffLL) return MRF_ERR_BAD_SHAPE;
     if (!pr->pairwise) return MRF_ERR_NULL_POINTER;
     if (forward && !pr->unary) return MRF_ERR_NULL_POINTER;
-    if (algo == MRF_TRWP && !pr->rho) return MRF_ERR_NULL_POINTER;
+    if (algo == MRF_TRWP && !pr->rho && !pr->rho_edge) return MRF_ERR_NULL_POINTER;
     if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && pr->pairwise_kind != MRF_PAIRWISE_TRUNC_LINEAR &&
         pr->pairwise_kind != MRF_PAIRWISE_TRUNC_QUADRATIC && pr->pairwise_kind != MRF_PAIRWISE_DISTANCE)
         return MRF_ERR_BAD_PAIRWISE_KIND;
@@ -266,7 +266,9 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
 {
     // few labels: several scanlines per wavefront (dense evaluation), unless the launch is so
     // small that it is latency bound and a truncated model can use the shorter window step
-    if (P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
+    // (TRW coefficients per edge: the two one-wavefront-per-scanline sweeps read them)
+    const bool generic = P.rho_e != nullptr;
+    if (!generic && P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
         int ms = 0;
         for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
             if (P.n_src[r] > ms) ms = P.n_src[r];
@@ -282,7 +284,7 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         // few scanlines in the launch and many labels: spread each node step over one
         // wavefront per 64 labels
         // (wide windows over many labels only: otherwise the value/index pair below is faster)
-        const bool split = LPw > 1 && g_tune_split != 1 &&
+        const bool split = !generic && LPw > 1 && g_tune_split != 1 &&
                            (g_tune_split == 2 || (LPw >= 3 && tw >= 8 && blocks * LPw <= 4096));
         if (ms + 1 <= 8 && split && g_tune_squad != 1 && (g_tune_squad == 2 || blocks <= 512)) {
             // the value wavefronts of the split layout, with the index work on wavefronts of their own
@@ -304,7 +306,7 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
             const long long st = ((long long)mrf_iabs(P.g.dh[r]) * P.g.W + mrf_iabs(P.g.dw[r])) * P.g.L;
             if (st > 0x7fffffffLL) step_fits = false;
         }
-        const bool duo = step_fits && g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= 4096);
+        const bool duo = !generic && step_fits && g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= 4096);
         if (ms + 1 <= 8 && duo) {
             P.NW = 1;
             // two index wavefronts while the launch is far from filling the machine
@@ -396,7 +398,8 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     const long long N = P.g.N;
     const int R = pr->R, L = pr->L, K = pr->K;
     P.unary = pr->unary; P.V = pr->pairwise;
-    for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP) ? pr->rho[r] : 1.0f;
+    for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP && pr->rho) ? pr->rho[r] : 1.0f;
+    P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
 
     // workspace: [scalars 256 B][messages A][messages B (ISGMR only)]
     float *scal = (float *)workspace;
@@ -467,7 +470,11 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
 {
     g_last_sweep[1] = "mrf_bwd_sweep";
     const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_WAVES);
-    if (P.gw && P.v_mode == 0)
+    if (P.rho_e && P.gw && P.v_mode == 0)
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false, true>), grid, block, lds, st, P);
+    else if (P.rho_e)
+        hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, false, true>), grid, block, lds, st, P);
+    else if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false>), grid, block, lds, st, P);
     else if (P.hot_label)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true>), grid, block, lds, st, P);
@@ -590,12 +597,13 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
     while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > chain_lds_cap(P.total_scanlines) ||
                       (gv && P.total_scanlines * ni > grad_slots(L)))) ni -= 2;
-    const bool chain_fits = step_fits && ns <= 8 && g_tune_chain != 1 &&
+    const bool generic = P.rho_e != nullptr;   // TRW coefficients per edge: mrf_bwd_sweep reads them
+    const bool chain_fits = !generic && step_fits && ns <= 8 && g_tune_chain != 1 &&
                             (!gv || (L <= 32 && P.total_scanlines * ni <= grad_slots(L))) &&
                             mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512));
     // few labels: several scanlines per wavefront, once there are enough of them
-    if (L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
+    if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
         !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= 1024)))
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
     if (chain) {
@@ -612,7 +620,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
 #undef MRF_CCASE
     }
     // few scanlines and many labels: one wavefront per 64 labels
-    const bool split = LP >= 3 && g_tune_split != 1 && ns <= 8 &&
+    const bool split = !generic && LP >= 3 && g_tune_split != 1 && ns <= 8 &&
                        (g_tune_split == 2 || (P.total_scanlines < 1024 && P.total_scanlines * LP <= 4096));
     if (split) {
         long long sblocks = P.total_scanlines;
@@ -673,6 +681,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     P.gc = grad_cost;
     P.gunary = grad_unary;
     P.unary_dir = -1;
+    P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
 
     // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots]
@@ -753,12 +762,13 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
                 for (int r = 0; r < R; ++r) {
                     if (r == d || (k == K - 1 && r < d)) continue;
                     P.src_dir[d][n] = (signed char)r;
-                    P.coefG[d][n] = pr->rho[r] - (r == P.g.opp[d] ? 1.0f : 0.0f);
-                    P.coefT[d][n] = pr->rho[r];
+                    const float rho_r = pr->rho ? pr->rho[r] : 1.0f;   // (not read when rho_edge is given)
+                    P.coefG[d][n] = rho_r - (r == P.g.opp[d] ? 1.0f : 0.0f);
+                    P.coefT[d][n] = rho_r;
                     ++n;
                 }
                 P.n_src[d] = (signed char)n;
-                P.carry_scale[d] = pr->rho[d];
+                P.carry_scale[d] = pr->rho ? pr->rho[d] : 1.0f;
                 P.use_gc = (k == K - 1);
                 P.unary_init = (k == K - 1);
                 P.p = p + (size_t)k * pk;

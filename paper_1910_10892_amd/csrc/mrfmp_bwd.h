@@ -69,6 +69,8 @@ struct MrfBwdParams {
     int v_mode;                            // V for grad w: 0 global, 1 copy in LDS, 2 first row in LDS
     int hot_label;                         // pre-reduce the most popular scatter target (truncated models)
     float carry_scale[MRF_MAXR];           // rho_d (TRWP) or 1 (ISGMR)
+    const float *rho_e;                    // [R][N] rho of edge (i-r, i) at node i (TRWP), or NULL: then
+                                           // coefG / coefT / carry_scale hold the per-direction values
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
@@ -85,8 +87,9 @@ __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L,
 
 // LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
 // gradient is gathered from global memory (it fits neither LDS layout), HOT: pre-reduce the
-// most popular scatter target
-template <int LP, int NS, int D, bool VG, bool HOT>
+// most popular scatter target, RHOE: TRW coefficients per edge (P.rho_e) instead of per direction:
+// what direction c scattered to node i came over the edge (i, i+c) and carries that edge's rho
+template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false>
 __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
@@ -144,6 +147,19 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             cG[c] = live ? (double)P.coefG[r][c] : (isgc ? 1.0 : 0.0);
             cT[c] = live ? (double)P.coefT[r][c] : (isgc ? 1.0 : 0.0);
         }
+        // per-edge rho: where to find the rho of the edge that source slot c used at a node
+        const float *rsrc[NS];
+        long long rstep[NS];
+        double ropp[NS];
+        bool rlive[NS];
+#pragma unroll
+        for (int c = 0; c < NS; ++c) {
+            const int sd = (RHOE && c < nsrc) ? P.src_dir[r][c] : r;
+            rlive[c] = RHOE && c < nsrc;
+            rsrc[c] = RHOE ? P.rho_e + (size_t)sd * N : nullptr;
+            rstep[c] = (long long)P.g.dh[sd] * P.g.W + P.g.dw[sd];
+            ropp[c] = (sd == P.g.opp[r]) ? 1.0 : 0.0;
+        }
 
         // the last node of the scanline has no successor in direction r
         {
@@ -161,10 +177,23 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
         int pcur[D][LP], pnxt[D][LP];
         int qcur[D], qnxt[D];
         float wcur[D], wnxt[D];
-        auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, float &wdst, int tt) {
+        float rcur[D][NS + 1], rnxt[D][NS + 1];   // RHOE: rho of each source slot's edge, then of this direction's own edge
+        auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, float &wdst,
+                            float (&rdst)[NS + 1], int tt) {
             int n = len - 1 - tt;
             n = n > 0 ? n : 0;
             const long long i = head + (long long)n * nstep;
+            if (RHOE) {
+                // (a node without successor in direction c got zeros from that direction: any
+                // finite coefficient will do, so the index is only kept inside the array)
+#pragma unroll
+                for (int c = 0; c < NS; ++c) {
+                    long long e = i + rstep[c];
+                    e = e < 0 ? 0 : (e > N - 1 ? N - 1 : e);
+                    rdst[c] = rsrc[c][(size_t)e + vzero];
+                }
+                rdst[NS] = P.rho_e[(size_t)r * N + i + vzero];
+            }
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 const int lam = lane + 64 * s;
@@ -178,7 +207,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             wdst = wbase[(size_t)(i * P.w_mul) + vzero];
         };
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], rcur[u], u);
 
         double carry[LP];   // what node i+r of this direction passed back to node i
 #pragma unroll
@@ -187,7 +216,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 
         for (int t0 = 0; t0 < len; t0 += D) {
 #pragma unroll
-            for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], t0 + D + u);
+            for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], rnxt[u], t0 + D + u);
 #pragma unroll
             for (int u = 0; u < D; ++u) {
                 // Steps past the first node (last group only) and the first node itself run the
@@ -199,12 +228,21 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 const bool update = !past && n > 0;      // node i has a predecessor: replay its update
                 const long long i = head + (long long)n * nstep;
                 const long long j = i - nstep;
+                double cGn[NS], cTn[NS];
+#pragma unroll
+                for (int c = 0; c < NS; ++c) {
+                    // Alg. 4 lines 9-11 with the rho of the edge (i, i+c): rho s to every direction
+                    // and to grad theta, minus s to the opposite direction
+                    cGn[c] = rlive[c] ? (double)rcur[u][c] - ropp[c] : cG[c];
+                    cTn[c] = rlive[c] ? (double)rcur[u][c] : cT[c];
+                }
+                const double cscale_n = RHOE ? (double)rcur[u][NS] : cscale;
                 double g[LP];
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     double acc = carry[s];
 #pragma unroll
-                    for (int c = 0; c < NS; ++c) acc = __builtin_fma(cG[c], (double)cur[u][c][s], acc);
+                    for (int c = 0; c < NS; ++c) acc = __builtin_fma(cGn[c], (double)cur[u][c][s], acc);
                     g[s] = (lane + 64 * s < L) ? acc : 0.0;
                 }
                 if (own_unary) {
@@ -213,7 +251,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     for (int s = 0; s < LP; ++s) {
                         double accT = carry[s];
 #pragma unroll
-                        for (int c = 0; c < NS; ++c) accT = __builtin_fma(cT[c], (double)cur[u][c][s], accT);
+                        for (int c = 0; c < NS; ++c) accT = __builtin_fma(cTn[c], (double)cur[u][c][s], accT);
                         accT += unary_old ? (double)ucur[u][s] : 0.0;   // (the buffer may hold anything at first)
                         if (!past && lane + 64 * s < L) P.gunary[(size_t)i * L + lane + 64 * s] = (float)accT;
                     }
@@ -287,7 +325,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
                     if (update && lam < L) P.S[((size_t)r * N + j) * L + lam] = (float)sv[s];
-                    carry[s] = cscale * sv[s];
+                    carry[s] = cscale_n * sv[s];
                 }
 
                 // pairwise gradients (off the node-to-node chain)
@@ -332,6 +370,8 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             for (int u = 0; u < D; ++u) {
                 qcur[u] = qnxt[u];
                 wcur[u] = wnxt[u];
+#pragma unroll
+                for (int c = 0; c <= NS; ++c) rcur[u][c] = rnxt[u][c];
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     ucur[u][s] = unxt[u][s];

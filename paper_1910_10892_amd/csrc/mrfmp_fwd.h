@@ -40,6 +40,8 @@ struct MrfFwdParams {
     float *m_out;                          // [R][N][L] messages written (TRWP: same array)
     uint8_t *p, *q;                        // [R][N][L], [R][N] of this iteration
     float rho[MRF_MAXR];
+    const float *rho_e;                    // [R][N] rho of edge (i-r, i) at node i (TRWP), or NULL: then rho[] applies
+                                           // (read by mrf_fwd_sweep and mrf_fwd_sweep_window only)
     // per swept direction r: the message arrays that enter h, in summation order.  The first
     // n_pre[r] are added before this direction's own running message, the rest after it.
     signed char src_dir[MRF_MAXR][MRF_MAXR];
@@ -138,7 +140,9 @@ mrf_fwd_sweep(const MrfFwdParams P)
     const int lastsrc = len - 2;           // last node that is a predecessor
     float cur[D][RMAX][LP], nxt[D][RMAX][LP];
     float wcur[D], wnxt[D];
-    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, int nj) {   // inputs of the update nj -> nj+1
+    float rcur[D], rnxt[D];                // rho of the edge (i-r, i): per edge if P.rho_e is given
+    const float *rbase = P.rho_e ? P.rho_e + (size_t)r * N : nullptr;
+    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, float &rdst, int nj) {   // inputs of the update nj -> nj+1
         nj = nj < lastsrc ? nj : lastsrc;  // past the end: reload the last one, never used
         const long long j = head + (long long)nj * nstep;
 #pragma unroll
@@ -149,10 +153,12 @@ mrf_fwd_sweep(const MrfFwdParams P)
                 dst[c][s] = src[c][(size_t)j * L + (lam < L ? lam : 0)];
             }
         wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+        rdst = rho;
+        if (TRWP && rbase) rdst = rbase[(size_t)(j + nstep) + vzero];
     };
     if (len >= 2) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], rcur[u], u);
     }
 
     float carry[LP];   // normalised message of this direction at the previous node
@@ -162,7 +168,7 @@ mrf_fwd_sweep(const MrfFwdParams P)
 
     for (int n0 = 1; n0 < len; n0 += D) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], rnxt[u], n0 - 1 + D + u);
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             // node index of i on the scanline; i-r is node n-1.  The last group may run past
@@ -187,7 +193,7 @@ mrf_fwd_sweep(const MrfFwdParams P)
                         mrm = __builtin_fmaf(is_rm[c], cur[u][c][s], mrm);
                     }
                     v = __builtin_fmaf(carry_at[RMAX], carry[s], v);
-                    v = rho * v;
+                    v = rcur[u] * v;
                     v = v - mrm;
                 } else {
                     // Eq. isgmr: theta_{i-r} + m-hat^r_{i-r} + sum_{d not in {r, r-}} m^d_{i-r}
@@ -287,6 +293,7 @@ mrf_fwd_sweep(const MrfFwdParams P)
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             wcur[u] = wnxt[u];
+            rcur[u] = rnxt[u];
 #pragma unroll
             for (int c = 0; c < RMAX; ++c)
 #pragma unroll
@@ -419,7 +426,9 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
     const int lastsrc = len - 2;
     float cur[D][RMAX][LP], nxt[D][RMAX][LP];
     float wcur[D], wnxt[D];
-    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, int nj) {
+    float rcur[D], rnxt[D];                // rho of the edge (i-r, i): per edge if P.rho_e is given
+    const float *rbase = P.rho_e ? P.rho_e + (size_t)r * N : nullptr;
+    auto prefetch = [&](float (&dst)[RMAX][LP], float &wdst, float &rdst, int nj) {
         nj = nj < lastsrc ? nj : lastsrc;
         const long long j = head + (long long)nj * nstep;
 #pragma unroll
@@ -430,10 +439,12 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                 dst[c][s] = src[c][(size_t)j * L + (lam < L ? lam : 0)];
             }
         wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+        rdst = rho;
+        if (TRWP && rbase) rdst = rbase[(size_t)(j + nstep) + vzero];
     };
     if (len >= 2) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], rcur[u], u);
     }
 
     float carry[LP];
@@ -442,7 +453,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
 
     for (int n0 = 1; n0 < len; n0 += D) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], rnxt[u], n0 - 1 + D + u);
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             const int nn = n0 + u;
@@ -465,7 +476,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                         mrm = __builtin_fmaf(is_rm[c], cur[u][c][s], mrm);
                     }
                     v = __builtin_fmaf(carry_at[RMAX], carry[s], v);
-                    v = rho * v;
+                    v = rcur[u] * v;
                     v = v - mrm;
                 } else {
                     v = v + carry[s];
@@ -577,6 +588,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             wcur[u] = wnxt[u];
+            rcur[u] = rnxt[u];
 #pragma unroll
             for (int c = 0; c < RMAX; ++c)
 #pragma unroll

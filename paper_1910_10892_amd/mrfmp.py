@@ -40,6 +40,7 @@ class _CProblem(ctypes.Structure):
         ("rho", ctypes.c_void_p),
         ("pairwise_kind", ctypes.c_int32),
         ("trunc", ctypes.c_float), ("scale", ctypes.c_float),
+        ("rho_edge", ctypes.c_void_p),
     ]
 
 
@@ -130,6 +131,7 @@ class MrfProblem:
     trunc: float = 0.0
     scale: float = 1.0
     shape: Optional[tuple] = None  # (B,H,W,L); taken from unary when given
+    rho_edge: object = None       # [R,B,H,W] float32 GPU tensor or None (TRWP: rho per directed edge)
 
     def __post_init__(self):
         if self.shape is None:
@@ -154,6 +156,7 @@ class MrfProblem:
         c.rho = None if self._rho is None else self._rho.ctypes.data
         c.pairwise_kind = int(self.pairwise_kind)
         c.trunc, c.scale = float(self.trunc), float(self.scale)
+        c.rho_edge = _dev_ptr(self.rho_edge, "float32")
         return c
 
 

@@ -32,8 +32,10 @@ class GpuProblem:
         self.unary, self.pairwise, self.edge_weight = t(pr.unary), t(pr.pairwise), t(pr.edge_weight)
         self.grad_cost = t(pr.grad_cost)
         self.algo = mrf.MRF_ISGMR if pr.algo == "isgmr" else mrf.MRF_TRWP
+        self.rho_edge = t(getattr(pr, "rho_edge", None))
         self.prob = mrf.MrfProblem(self.unary, self.pairwise, pr.dirs, K, self.edge_weight,
-                                   pr.edge_weight_scalar, pr.rho, pr.pairwise_kind, pr.trunc, pr.scale)
+                                   pr.edge_weight_scalar, pr.rho, pr.pairwise_kind, pr.trunc, pr.scale,
+                                   rho_edge=self.rho_edge)
         self.cost = torch.empty((B, H, W, L), dtype=torch.float32, device=dev)
         self.labels = torch.empty((B, H, W), dtype=torch.uint8, device=dev)
         self.p = torch.empty((K, R, B, H, W, L), dtype=torch.uint8, device=dev)

@@ -65,6 +65,7 @@ def test_validation_codes_without_gpu():
     assert V(_cprob(unary=None)) == -1
     assert V(_cprob(pairwise=None)) == -1
     assert V(_cprob(rho=None), 1) == -1 and V(_cprob(rho=None), 0) == 0
+    assert V(_cprob(rho=None, rho_edge=0x1000), 1) == 0      # per-edge coefficients stand in for rho[]
     assert V(_cprob(pairwise_kind=9)) == -7
     assert V(_cprob(pairwise_kind=1, trunc=0.0)) == -7
     assert lib.mrf_validate(None, 0) == -1

@@ -19,14 +19,15 @@ RTOL, ATOL = 1e-5, 1e-4
 
 def oracle_forward(oracle, pr, threads=False):
     return oracle.forward(pr.algo, pr.unary, pr.pairwise, pr.dirs, pr.K, edge_weight=pr.edge_weight,
-                          edge_weight_scalar=pr.edge_weight_scalar, rho=pr.rho, threads=threads)
+                          edge_weight_scalar=pr.edge_weight_scalar, rho=pr.rho, threads=threads,
+                          rho_edge=pr.rho_edge)
 
 
 def oracle_backward(oracle, pr, p, q, dtype=np.float32):
     c = lambda a: None if a is None else a.astype(dtype)
     return oracle.backward(pr.algo, pr.shape, c(pr.pairwise), pr.dirs, pr.K, c(pr.grad_cost), p, q,
                            edge_weight=c(pr.edge_weight), edge_weight_scalar=pr.edge_weight_scalar,
-                           rho=pr.rho, dtype=dtype)
+                           rho=pr.rho, dtype=dtype, rho_edge=c(pr.rho_edge))
 
 
 def check_forward(g, f):
@@ -581,3 +582,45 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     finally:
         for k in knobs:
             mrf.mrf_tune(k, 0)
+
+
+RHO_EDGE_CASES = [
+    # seed, B, H, W, L, dirs, K, kind, trunc, integer_valued, per_edge weights
+    (201, 2, 6, 9, 21, DIRS4, 2, 0, 0.0, False, True),
+    (202, 1, 5, 11, 96, DIRS8, 2, 1, 8.0, False, True),
+    (203, 1, 4, 7, 130, DIRS4, 3, 0, 0.0, True, False),
+    (204, 1, 3, 9, 200, DIRS4, 2, 2, 30.0, False, True),
+    (205, 1, 6, 6, 3, DIRS16, 2, 0, 0.0, False, True),
+    (206, 1, 1, 12, 40, [(0, 1), (0, -1), (1, 1)], 2, 3, 2.0, False, True),
+    (207, 1, 8, 3, 256, DIRS4, 1, 1, 2.0, True, True),
+]
+
+
+@pytest.mark.parametrize("case", RHO_EDGE_CASES, ids=lambda c: "seed%d" % c[0])
+def test_trwp_with_one_rho_per_edge(oracle, case):
+    """TRWP with the TRW coefficient of Eq. trwp given per directed edge (an [R,B,H,W] array like
+    the edge weights) instead of per direction: forward and backward against the oracle, with and
+    without grad_pairwise; and an array that repeats one value per direction gives the forward
+    results of the per-direction path bit for bit."""
+    from mrf_inputs import truncated_linear, truncated_quadratic, sgm_penalties
+    print("case per-edge rho", case, flush=True)
+    seed, B, H, W, L, dirs, K, kind, trunc, iv, pe = case
+    R = len(dirs)
+    pr = random_problem(seed, "trwp", B, H, W, L, dirs, K, integer_valued=iv, per_edge=pe,
+                        rho=np.linspace(0.3, 0.9, R))
+    if kind:
+        scale = 1.0 if iv else 0.37
+        pr.pairwise = (truncated_linear(L, trunc, scale) if kind == 1 else
+                       truncated_quadratic(L, trunc, scale) if kind == 2 else sgm_penalties(L, 0.5, 2.0))
+        pr.pairwise_kind, pr.trunc, pr.scale = kind, trunc, scale
+    rng = np.random.default_rng(7000 + seed)
+    base = full_check(oracle, pr, want_V=False)
+    pr.rho_edge = np.broadcast_to(pr.rho[:, None, None, None], (R, B, H, W)).astype(np.float32).copy()
+    same = full_check(oracle, pr, want_V=False)
+    for name in ("p", "q", "labels", "cost", "messages"):
+        np.testing.assert_array_equal(getattr(base, name), getattr(same, name), err_msg=name)
+    np.testing.assert_allclose(same.grad_unary, base.grad_unary, rtol=1e-5, atol=1e-4)
+    pr.rho_edge = (rng.integers(1, 4, (R, B, H, W)) / 4.0 if iv else rng.uniform(0.2, 0.9, (R, B, H, W))).astype(np.float32)
+    pr.rho = None
+    full_check(oracle, pr, want_V=False)
+    full_check(oracle, pr, want_V=True)
