@@ -64,6 +64,7 @@ class BackwardResult:
     grad_unary: np.ndarray        # [B,H,W,L]
     grad_edge_weight: np.ndarray  # [R,B,H,W]
     grad_pairwise: np.ndarray     # [L,L]
+    grad_pairwise_edge: np.ndarray = None   # [R,B,H,W,L,L] (problems with per-edge pairwise potentials)
 
 
 def _real(dtype):
@@ -93,13 +94,19 @@ def _rho_args(rho, rho_edge, R, shape, dtype):
 
 
 def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_weight_scalar=1.0,
-            rho=None, dtype=np.float32, threads: bool = False, rho_edge=None) -> ForwardResult:
-    """Alg. 1 (algo='isgmr') or Alg. 2 (algo='trwp')."""
+            rho=None, dtype=np.float32, threads: bool = False, rho_edge=None,
+            pairwise_edge=None) -> ForwardResult:
+    """Alg. 1 (algo='isgmr') or Alg. 2 (algo='trwp').  pairwise_edge [R,B,H,W,L,L]: pairwise
+    potentials theta_{i-r,i}(mu,lambda) given per edge; pairwise and the edge weights are then
+    not used."""
     sfx, creal = _real(dtype)
     unary = np.ascontiguousarray(unary, dtype=dtype)
     B, H, W, L, dirs, R = _common(unary.shape, dirs, dtype)
-    V = np.ascontiguousarray(pairwise, dtype=dtype)
-    assert V.shape == (L, L)
+    Te = None if pairwise_edge is None else np.ascontiguousarray(pairwise_edge, dtype=dtype)
+    if Te is not None:
+        assert Te.shape == (R, B, H, W, L, L)
+    V = None if (pairwise is None and Te is not None) else np.ascontiguousarray(pairwise, dtype=dtype)
+    assert V is None or V.shape == (L, L)
     w = None if edge_weight is None else np.ascontiguousarray(edge_weight, dtype=dtype)
     if w is not None:
         assert w.shape == (R, B, H, W)
@@ -114,11 +121,11 @@ def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_wei
     tail = [_ptr(cost), _ptr(labels), _ptr(p), _ptr(q), _ptr(msg)]
     if algo == "isgmr":
         fn = getattr(lib, "mrfo_isgmr_forward_" + sfx)
-        rc = fn(*head, *tail)
+        rc = fn(*head, _ptr(Te), *tail)
     elif algo == "trwp":
         rho_a, rho_e = _rho_args(rho, rho_edge, R, (B, H, W), dtype)
         fn = getattr(lib, "mrfo_trwp_forward_" + sfx)
-        rc = fn(*head, _ptr(rho_a), _ptr(rho_e), *tail)
+        rc = fn(*head, _ptr(rho_a), _ptr(rho_e), _ptr(Te), *tail)
     else:
         raise ValueError(algo)
     if rc != 0:
@@ -127,11 +134,14 @@ def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_wei
 
 
 def backward(algo: str, shape, pairwise, dirs, K: int, grad_cost, p, q, edge_weight=None,
-             edge_weight_scalar=1.0, rho=None, dtype=np.float32, rho_edge=None) -> BackwardResult:
-    """Alg. 3 (algo='isgmr') or Alg. 4 (algo='trwp'); shape = (B,H,W,L)."""
+             edge_weight_scalar=1.0, rho=None, dtype=np.float32, rho_edge=None,
+             per_edge_pairwise: bool = False) -> BackwardResult:
+    """Alg. 3 (algo='isgmr') or Alg. 4 (algo='trwp'); shape = (B,H,W,L).  per_edge_pairwise: the
+    problem gave its pairwise potentials per edge; then the gradient of those [R,B,H,W,L,L]
+    (Eq. supp-gradient-pairwise) is returned instead of the gradients of edge weights and V."""
     sfx, creal = _real(dtype)
     B, H, W, L, dirs, R = _common(shape, dirs, dtype)
-    V = np.ascontiguousarray(pairwise, dtype=dtype)
+    V = None if per_edge_pairwise else np.ascontiguousarray(pairwise, dtype=dtype)
     w = None if edge_weight is None else np.ascontiguousarray(edge_weight, dtype=dtype)
     gc = np.ascontiguousarray(grad_cost, dtype=dtype)
     assert gc.shape == (B, H, W, L)
@@ -139,12 +149,13 @@ def backward(algo: str, shape, pairwise, dirs, K: int, grad_cost, p, q, edge_wei
     q = np.ascontiguousarray(q, dtype=np.uint8)
     assert p.shape == (K, R, B, H, W, L) and q.shape == (K, R, B, H, W)
     gu = np.empty((B, H, W, L), dtype)
-    gw = np.empty((R, B, H, W), dtype)
-    gV = np.empty((L, L), dtype)
+    gw = None if per_edge_pairwise else np.empty((R, B, H, W), dtype)
+    gV = None if per_edge_pairwise else np.empty((L, L), dtype)
+    gTe = np.empty((R, B, H, W, L, L), dtype) if per_edge_pairwise else None
     lib = _lib(False)
     head = [ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(W), ctypes.c_int(L), ctypes.c_int(R),
             _ptr(dirs), ctypes.c_int(K), _ptr(V), _ptr(w), creal(edge_weight_scalar)]
-    tail = [_ptr(gc), _ptr(p), _ptr(q), _ptr(gu), _ptr(gw), _ptr(gV)]
+    tail = [_ptr(gc), _ptr(p), _ptr(q), _ptr(gu), _ptr(gw), _ptr(gV), _ptr(gTe)]
     if algo == "isgmr":
         rc = getattr(lib, "mrfo_isgmr_backward_" + sfx)(*head, *tail)
     elif algo == "trwp":
@@ -154,7 +165,7 @@ def backward(algo: str, shape, pairwise, dirs, K: int, grad_cost, p, q, edge_wei
         raise ValueError(algo)
     if rc != 0:
         raise ValueError("oracle rejected the problem (rc=%d)" % rc)
-    return BackwardResult(gu, gw, gV)
+    return BackwardResult(gu, gw, gV, gTe)
 
 
 def count_scanlines(H: int, W: int, dh: int, dw: int) -> int:

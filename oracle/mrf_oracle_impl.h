@@ -19,6 +19,9 @@
  *   messages                             [R][B][H][W][L]
  *   p                                    [K][R][B][H][W][L]  uint8
  *   q                                    [K][R][B][H][W]     uint8
+ *   theta_e, grad_theta_e (optional)     [R][B][H][W][L][L]  entry (r,i,mu,lambda) =
+ *                                        theta_{i-r,i}(mu,lambda): pairwise potentials given per
+ *                                        edge as in Eq. isgmr / Eq. trwp, instead of w and V
  * A node whose predecessor i-r lies outside the grid is the first node of its
  * scanline: its message in direction r is 0 for ever and its p, q entries are 0.
  *
@@ -33,16 +36,20 @@
 /* ---- one message update: Alg. 1 lines 6-13 / Alg. 2 lines 6-13 ------------------
  * h[mu]  : everything inside the min that does not depend on lambda
  * wgt    : edge weight theta_{i-r,i}
+ * Te     : the edge's own table theta_{i-r,i}(mu,lambda) [L][L] where the problem gives
+ *          pairwise potentials per edge (Eq. isgmr as written), else NULL and the
+ *          potential is wgt * V(mu,lambda)
  * out    : normalised message (Eq. isgmr-norm), pidx[lambda] = argmin_mu (lowest
  *          index on ties), returns q = argmin_lambda (lowest index on ties).      */
-static int NAME(node_update)(int L, const REAL *h, REAL wgt, const REAL *V,
+static int NAME(node_update)(int L, const REAL *h, REAL wgt, const REAL *V, const REAL *Te,
                              REAL *out, uint8_t *pidx)
 {
     for (int lam = 0; lam < L; ++lam) {
         REAL best = (REAL)INFINITY;
         int arg = 0;
         for (int mu = 0; mu < L; ++mu) {
-            REAL delta = REAL_FMA(wgt, V[(size_t)mu * L + lam], h[mu]);
+            REAL delta = Te ? h[mu] + Te[(size_t)mu * L + lam]
+                            : REAL_FMA(wgt, V[(size_t)mu * L + lam], h[mu]);
             if (delta < best) { best = delta; arg = mu; }
         }
         out[lam] = best;
@@ -80,6 +87,7 @@ static void NAME(aggregate)(const grid_t *g, const REAL *unary, const REAL *m,
 /* ================================ Alg. 1 ======================================= */
 int NAME(mrfo_isgmr_forward)(int B, int H, int W, int L, int R, const int *dirs, int K,
                              const REAL *unary, const REAL *V, const REAL *w, REAL w_scalar,
+                             const REAL *theta_e,
                              REAL *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
                              REAL *messages)
 {
@@ -114,7 +122,8 @@ int NAME(mrfo_isgmr_forward)(int B, int H, int W, int L, int R, const int *dirs,
                         h[mu] = a;
                     }
                     REAL wgt = w ? w[(size_t)r * N + i] : w_scalar;
-                    int qq = NAME(node_update)(L, h, wgt, V, &mhat[((size_t)r * N + i) * L],
+                    const REAL *Te = theta_e ? theta_e + ((size_t)r * N + i) * L * L : NULL;
+                    int qq = NAME(node_update)(L, h, wgt, V, Te, &mhat[((size_t)r * N + i) * L],
                                                &p[(((size_t)k * R + r) * N + i) * L]);
                     q[((size_t)k * R + r) * N + i] = (uint8_t)qq;
                     y = yn; x = xn;
@@ -134,7 +143,7 @@ int NAME(mrfo_isgmr_forward)(int B, int H, int W, int L, int R, const int *dirs,
 /* ================================ Alg. 2 ======================================= */
 int NAME(mrfo_trwp_forward)(int B, int H, int W, int L, int R, const int *dirs, int K,
                             const REAL *unary, const REAL *V, const REAL *w, REAL w_scalar,
-                            const REAL *rho, const REAL *rho_edge,
+                            const REAL *rho, const REAL *rho_edge, const REAL *theta_e,
                             REAL *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
                             REAL *messages)
 {
@@ -170,7 +179,8 @@ int NAME(mrfo_trwp_forward)(int B, int H, int W, int L, int R, const int *dirs, 
                         h[mu] = a;
                     }
                     REAL wgt = w ? w[(size_t)r * N + i] : w_scalar;
-                    int qq = NAME(node_update)(L, h, wgt, V, &m[((size_t)r * N + i) * L],
+                    const REAL *Te = theta_e ? theta_e + ((size_t)r * N + i) * L * L : NULL;
+                    int qq = NAME(node_update)(L, h, wgt, V, Te, &m[((size_t)r * N + i) * L],
                                                &p[(((size_t)k * R + r) * N + i) * L]);
                     q[((size_t)k * R + r) * N + i] = (uint8_t)qq;
                     y = yn; x = xn;
@@ -190,9 +200,12 @@ int NAME(mrfo_trwp_forward)(int B, int H, int W, int L, int R, const int *dirs, 
  * g[lambda] is the gradient of the normalised message at node i; it is modified in
  * place by the reparametrisation step (Eq. supp-isgmr-back-norm).  Also accumulates the
  * edge-weight gradient (Eq. supp-gradient-edge) and the V gradient
- * (Eq. supp-gradient-smoothness); neither carries rho (Alg. 4 line 12).            */
+ * (Eq. supp-gradient-smoothness); neither carries rho (Alg. 4 line 12).  Where the
+ * problem gives pairwise potentials per edge, gTe is the edge's gradient table and
+ * receives g(lambda) at (p(lambda), lambda) (Eq. supp-gradient-pairwise).            */
 static void NAME(norm_backward_and_pairwise)(int L, REAL *g, int qstar, const uint8_t *pidx,
-                                             REAL wgt, const REAL *V, REAL *gw_entry, REAL *gV)
+                                             REAL wgt, const REAL *V, REAL *gw_entry, REAL *gV,
+                                             REAL *gTe)
 {
     REAL tot = (REAL)0;
     for (int lam = 0; lam < L; ++lam) tot = tot + g[lam];
@@ -205,13 +218,16 @@ static void NAME(norm_backward_and_pairwise)(int L, REAL *g, int qstar, const ui
     if (gV)
         for (int lam = 0; lam < L; ++lam)
             gV[(size_t)pidx[lam] * L + lam] = gV[(size_t)pidx[lam] * L + lam] + wgt * g[lam];
+    if (gTe)
+        for (int lam = 0; lam < L; ++lam)
+            gTe[(size_t)pidx[lam] * L + lam] = gTe[(size_t)pidx[lam] * L + lam] + g[lam];
 }
 
 /* ================================ Alg. 3 ======================================= */
 int NAME(mrfo_isgmr_backward)(int B, int H, int W, int L, int R, const int *dirs, int K,
                               const REAL *V, const REAL *w, REAL w_scalar,
                               const REAL *grad_cost, const uint8_t *p, const uint8_t *q,
-                              REAL *grad_unary, REAL *grad_w, REAL *grad_V)
+                              REAL *grad_unary, REAL *grad_w, REAL *grad_V, REAL *grad_theta_e)
 {
     grid_t g;
     if (grid_init(&g, B, H, W, L, R, dirs, K)) return -1;
@@ -225,6 +241,7 @@ int NAME(mrfo_isgmr_backward)(int B, int H, int W, int L, int R, const int *dirs
     memcpy(grad_unary, grad_cost, sizeof(REAL) * NL);
     if (grad_w) memset(grad_w, 0, sizeof(REAL) * (size_t)R * N);
     if (grad_V) memset(grad_V, 0, sizeof(REAL) * (size_t)L * L);
+    if (grad_theta_e) memset(grad_theta_e, 0, sizeof(REAL) * (size_t)R * N * L * L);
 
     for (int k = K - 1; k >= 0; --k) {
         memset(G, 0, sizeof(REAL) * (size_t)R * NL);                      /* zero-out */
@@ -244,7 +261,8 @@ int NAME(mrfo_isgmr_backward)(int B, int H, int W, int L, int R, const int *dirs
                     for (int lam = 0; lam < L; ++lam) gl[lam] = Ghat[((size_t)r * N + i) * L + lam];
                     NAME(norm_backward_and_pairwise)(L, gl, q[((size_t)k * R + r) * N + i], pidx,
                                                      wgt, V, grad_w ? &grad_w[(size_t)r * N + i] : NULL,
-                                                     grad_V);
+                                                     grad_V,
+                                                     grad_theta_e ? grad_theta_e + ((size_t)r * N + i) * L * L : NULL);
                     for (int lam = 0; lam < L; ++lam) {
                         int mu = pidx[lam];
                         grad_unary[j * L + mu] = grad_unary[j * L + mu] + gl[lam];
@@ -270,7 +288,7 @@ int NAME(mrfo_isgmr_backward)(int B, int H, int W, int L, int R, const int *dirs
 int NAME(mrfo_trwp_backward)(int B, int H, int W, int L, int R, const int *dirs, int K,
                              const REAL *V, const REAL *w, REAL w_scalar, const REAL *rho,
                              const REAL *rho_edge, const REAL *grad_cost, const uint8_t *p, const uint8_t *q,
-                             REAL *grad_unary, REAL *grad_w, REAL *grad_V)
+                             REAL *grad_unary, REAL *grad_w, REAL *grad_V, REAL *grad_theta_e)
 {
     grid_t g;
     if (grid_init(&g, B, H, W, L, R, dirs, K)) return -1;
@@ -282,6 +300,7 @@ int NAME(mrfo_trwp_backward)(int B, int H, int W, int L, int R, const int *dirs,
     memcpy(grad_unary, grad_cost, sizeof(REAL) * NL);
     if (grad_w) memset(grad_w, 0, sizeof(REAL) * (size_t)R * N);
     if (grad_V) memset(grad_V, 0, sizeof(REAL) * (size_t)L * L);
+    if (grad_theta_e) memset(grad_theta_e, 0, sizeof(REAL) * (size_t)R * N * L * L);
 
     for (int k = K - 1; k >= 0; --k) {
         for (int r = R - 1; r >= 0; --r) {       /* reverse of the forward direction order */
@@ -299,7 +318,8 @@ int NAME(mrfo_trwp_backward)(int B, int H, int W, int L, int R, const int *dirs,
                     for (int lam = 0; lam < L; ++lam) gl[lam] = G[((size_t)r * N + i) * L + lam];
                     NAME(norm_backward_and_pairwise)(L, gl, q[((size_t)k * R + r) * N + i], pidx,
                                                      wgt, V, grad_w ? &grad_w[(size_t)r * N + i] : NULL,
-                                                     grad_V);
+                                                     grad_V,
+                                                     grad_theta_e ? grad_theta_e + ((size_t)r * N + i) * L * L : NULL);
                     for (int lam = 0; lam < L; ++lam) {
                         int mu = pidx[lam];
                         REAL sg = (rho_edge ? rho_edge[(size_t)r * N + i] : rho[r]) * gl[lam];
