@@ -92,6 +92,14 @@ typedef struct {
                                    writes it, entry (r,i) like edge_weight (first-node entries are never
                                    read); takes the place of rho[]; TRWP only.  Such problems run
                                    through the one-wavefront-per-scanline sweeps. */
+    const float *pairwise_edge; /* DEVICE [R][B][H][W][L][L] or NULL: pairwise potentials given per edge,
+                                   entry (r,i,mu,lambda) = theta_{i-r,i}(mu,lambda) as Eq. isgmr and Eq. trwp
+                                   write them (tables of first nodes are never read).  Then pairwise (may be
+                                   NULL), edge_weight and edge_weight_scalar are not used, L <= 64 and
+                                   pairwise_kind = MRF_PAIRWISE_DENSE are required, and the backward entry
+                                   points take grad_edge_weight = NULL and write to grad_pairwise, if given,
+                                   the gradient of these tables, [R][B][H][W][L][L]
+                                   (Eq. supp-gradient-pairwise; tables of first nodes get 0). */
 } mrf_problem;
 
 /* Bytes of DEVICE workspace (256-byte aligned base required) that the forward

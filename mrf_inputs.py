@@ -42,6 +42,7 @@ class Problem:
     scale: float = 1.0
     meta: dict = field(default_factory=dict)
     rho_edge: Optional[np.ndarray] = None      # [R,B,H,W] float32 (TRWP): rho per directed edge, or None
+    pairwise_edge: Optional[np.ndarray] = None # [R,B,H,W,L,L] float32: pairwise potentials per edge, or None
 
     @property
     def shape(self):

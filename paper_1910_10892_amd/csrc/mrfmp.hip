@@ -36,7 +36,13 @@ int check_problem(const mrf_problem *pr, int algo, bool forward)
     }
     const long long N = (long long)pr->B * pr->H * pr->W;
     if (N > 0x7fffffffLL) return MRF_ERR_BAD_SHAPE;
-    if (!pr->pairwise) return MRF_ERR_NULL_POINTER;
+    if (!pr->pairwise && !pr->pairwise_edge) return MRF_ERR_NULL_POINTER;
+    if (pr->pairwise_edge) {
+        // one table per edge: few labels only, and no promise about V applies
+        if (pr->L > 64) return MRF_ERR_BAD_LABELS;
+        if (pr->pairwise_kind != MRF_PAIRWISE_DENSE) return MRF_ERR_BAD_PAIRWISE_KIND;
+        if ((long long)pr->R * N * pr->L > 0x7fffffffLL) return MRF_ERR_BAD_SHAPE;
+    }
     if (forward && !pr->unary) return MRF_ERR_NULL_POINTER;
     if (algo == MRF_TRWP && !pr->rho && !pr->rho_edge) return MRF_ERR_NULL_POINTER;
     if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && pr->pairwise_kind != MRF_PAIRWISE_TRUNC_LINEAR &&
@@ -135,6 +141,30 @@ int pick_mch(int L, int LP, bool many_sources)
         if (best == 0 || mrf_iabs(m - want) < mrf_iabs(best - want)) best = m;
     }
     return best;
+}
+
+// pairwise potentials per edge (L <= 64): the table is fetched in two halves of ceil(L/2) rows
+hipError_t launch_edge(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
+{
+    g_last_sweep[0] = "mrf_fwd_sweep_edge";
+    int ms = 0;
+    for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
+        if (P.n_src[r] > ms) ms = P.n_src[r];
+    const int rmax = (ms + 1 <= 4) ? 4 : ((ms + 1 <= 8) ? 8 : 16);
+    const int L = P.g.L;
+    if (L > 64) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(64);
+#define MRF_E(half, rm) \
+    if (L <= 2 * half && rmax == rm) { \
+        if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_edge<half, rm, true>), grid, block, 0, st, P); \
+        else hipLaunchKernelGGL((mrf_fwd_sweep_edge<half, rm, false>), grid, block, 0, st, P); \
+        return hipGetLastError(); \
+    }
+#define MRF_EH(half) MRF_E(half, 4) MRF_E(half, 8) MRF_E(half, 16)
+    MRF_EH(4) MRF_EH(8) MRF_EH(16) MRF_EH(32)
+#undef MRF_EH
+#undef MRF_E
+    return hipErrorInvalidValue;
 }
 
 template <int LP, int RMAX, int D>
@@ -266,6 +296,7 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
 {
     // few labels: several scanlines per wavefront (dense evaluation), unless the launch is so
     // small that it is latency bound and a truncated model can use the shorter window step
+    if (P.Te) return launch_edge(P, algo, blocks, st);
     // (TRW coefficients per edge: the two one-wavefront-per-scanline sweeps read them)
     const bool generic = P.rho_e != nullptr;
     if (!generic && P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
@@ -400,6 +431,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     P.unary = pr->unary; P.V = pr->pairwise;
     for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP && pr->rho) ? pr->rho[r] : 1.0f;
     P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
+    P.Te = pr->pairwise_edge;
 
     // workspace: [scalars 256 B][messages A][messages B (ISGMR only)]
     float *scal = (float *)workspace;
@@ -472,7 +504,7 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
     const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_WAVES);
     if (P.rho_e && P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false, true>), grid, block, lds, st, P);
-    else if (P.rho_e)
+    else if (P.rho_e || P.gE)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, false, true>), grid, block, lds, st, P);
     else if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false>), grid, block, lds, st, P);
@@ -597,7 +629,9 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
     while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > chain_lds_cap(P.total_scanlines) ||
                       (gv && P.total_scanlines * ni > grad_slots(L)))) ni -= 2;
-    const bool generic = P.rho_e != nullptr;   // TRW coefficients per edge: mrf_bwd_sweep reads them
+    // TRW coefficients or pairwise tables per edge: mrf_bwd_sweep handles them (and is the one
+    // sweep that never touches V when no edge-weight gradient is asked for)
+    const bool generic = P.rho_e != nullptr || P.force_plain;
     const bool chain_fits = !generic && step_fits && ns <= 8 && g_tune_chain != 1 &&
                             (!gv || (L <= 32 && P.total_scanlines * ni <= grad_slots(L))) &&
                             mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
@@ -665,6 +699,10 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     int rc = check_problem(pr, algo, false);
     if (rc != MRF_OK) return rc;
     if (!grad_cost || !p || !q || !grad_unary) return MRF_ERR_NULL_POINTER;
+    // pairwise potentials per edge: grad_V is their gradient [R][B][H][W][L][L]; there are no
+    // edge weights to differentiate
+    const bool edge_tables = pr->pairwise_edge != nullptr;
+    if (edge_tables && grad_w) return MRF_ERR_BAD_PAIRWISE_KIND;
     const size_t need = mrf_workspace_bytes(pr, algo, 1);
     if (!workspace) return MRF_ERR_NULL_POINTER;
     if (workspace_bytes < need) return MRF_ERR_WORKSPACE_TOO_SMALL;
@@ -700,7 +738,11 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         const hipError_t e_ = fill(grad_w, (long long)R * N, 0.0f, st);
         if (e_ != hipSuccess) return hip_fail(e_, "fill");
     }
-    if (grad_V) {
+    P.force_plain = edge_tables ? 1 : 0;
+    if (edge_tables && grad_V) {
+        P.gE = grad_V;
+        { const hipError_t e_ = fill(grad_V, (long long)R * N * L * L, 0.0f, st); if (e_ != hipSuccess) return hip_fail(e_, "fill"); }
+    } else if (grad_V) {
         P.gV = gvslots;
         { const hipError_t e_ = fill64(gvslots, grad_slots(L) * L * L, st); if (e_ != hipSuccess) return hip_fail(e_, "fill64"); }
     }
@@ -778,7 +820,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         }
     }
     mark(g_ev_stop, st);
-    if (grad_V) {
+    if (grad_V && !edge_tables) {
         const long long n = (long long)L * L;
         const long long slots = grad_slots(L), chunk = 128;
         const unsigned eb = (unsigned)((n + 255) / 256);

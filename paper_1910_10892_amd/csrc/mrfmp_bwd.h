@@ -71,6 +71,9 @@ struct MrfBwdParams {
     float carry_scale[MRF_MAXR];           // rho_d (TRWP) or 1 (ISGMR)
     const float *rho_e;                    // [R][N] rho of edge (i-r, i) at node i (TRWP), or NULL: then
                                            // coefG / coefT / carry_scale hold the per-direction values
+    float *gE;                             // [R][N][L][L] gradient of per-edge pairwise tables (zeroed by the host,
+                                           // accumulated over iterations), or NULL; mrf_bwd_sweep<..., RHOE> only
+    int force_plain;                       // the problem has no V: only mrf_bwd_sweep may run
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
@@ -87,8 +90,10 @@ __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L,
 
 // LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
 // gradient is gathered from global memory (it fits neither LDS layout), HOT: pre-reduce the
-// most popular scatter target, RHOE: TRW coefficients per edge (P.rho_e) instead of per direction:
-// what direction c scattered to node i came over the edge (i, i+c) and carries that edge's rho
+// most popular scatter target, RHOE: the per-edge extras.  TRW coefficients per edge (P.rho_e)
+// instead of per direction: what direction c scattered to node i came over the edge (i, i+c)
+// and carries that edge's rho.  Gradient of per-edge pairwise tables (P.gE): entry
+// (p(lambda), lambda) of the edge's table receives g(lambda) (Eq. supp-gradient-pairwise).
 template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false>
 __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
@@ -155,8 +160,8 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 #pragma unroll
         for (int c = 0; c < NS; ++c) {
             const int sd = (RHOE && c < nsrc) ? P.src_dir[r][c] : r;
-            rlive[c] = RHOE && c < nsrc;
-            rsrc[c] = RHOE ? P.rho_e + (size_t)sd * N : nullptr;
+            rlive[c] = RHOE && P.rho_e && c < nsrc;
+            rsrc[c] = (RHOE && P.rho_e) ? P.rho_e + (size_t)sd * N : nullptr;
             rstep[c] = (long long)P.g.dh[sd] * P.g.W + P.g.dw[sd];
             ropp[c] = (sd == P.g.opp[r]) ? 1.0 : 0.0;
         }
@@ -183,7 +188,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             int n = len - 1 - tt;
             n = n > 0 ? n : 0;
             const long long i = head + (long long)n * nstep;
-            if (RHOE) {
+            if (RHOE && P.rho_e) {
                 // (a node without successor in direction c got zeros from that direction: any
                 // finite coefficient will do, so the index is only kept inside the array)
 #pragma unroll
@@ -236,7 +241,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     cGn[c] = rlive[c] ? (double)rcur[u][c] - ropp[c] : cG[c];
                     cTn[c] = rlive[c] ? (double)rcur[u][c] : cT[c];
                 }
-                const double cscale_n = RHOE ? (double)rcur[u][NS] : cscale;
+                const double cscale_n = (RHOE && P.rho_e) ? (double)rcur[u][NS] : cscale;
                 double g[LP];
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
@@ -352,6 +357,17 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     if (update && lane == 0)
                         __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (RHOE && P.gE) {
+                    // one writer per table and launch: plain read-modify-write
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) {
+                        const int lam = lane + 64 * s;
+                        if (update && lam < L) {
+                            float *e = P.gE + (((size_t)r * N + i) * L + pv[s]) * L + lam;
+                            *e = *e + (float)g[s];
+                        }
+                    }
                 }
                 if (gVs) {
                     // lane lambda owns column lambda of the wavefront's private accumulator

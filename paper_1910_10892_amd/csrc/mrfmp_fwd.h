@@ -18,6 +18,7 @@
 // Kernels in this file, all computing the same update in the same rounding order:
 //   mrf_fwd_sweep               dense O(L^2), NW wavefronts per scanline split the source labels
 //   mrf_fwd_sweep_packed        dense, L <= 32: several scanlines per wavefront
+//   mrf_fwd_sweep_edge          pairwise potentials given per edge (L <= 64)
 //   mrf_aggregate               final costs and labels
 //   mrf_fwd_sweep_window        truncated models: window of 2 TW - 1 source labels per label
 //   mrf_fwd_sweep_window_duo    the same with the dependency chain (values) on one wavefront and
@@ -41,7 +42,8 @@ struct MrfFwdParams {
     uint8_t *p, *q;                        // [R][N][L], [R][N] of this iteration
     float rho[MRF_MAXR];
     const float *rho_e;                    // [R][N] rho of edge (i-r, i) at node i (TRWP), or NULL: then rho[] applies
-                                           // (read by mrf_fwd_sweep and mrf_fwd_sweep_window only)
+                                           // (read by mrf_fwd_sweep, mrf_fwd_sweep_window and mrf_fwd_sweep_edge only)
+    const float *Te;                       // [R][N][L][L] pairwise potentials per edge (mrf_fwd_sweep_edge), or NULL
     // per swept direction r: the message arrays that enter h, in summation order.  The first
     // n_pre[r] are added before this direction's own running message, the rest after it.
     signed char src_dir[MRF_MAXR][MRF_MAXR];
@@ -299,6 +301,151 @@ mrf_fwd_sweep(const MrfFwdParams P)
 #pragma unroll
                 for (int s = 0; s < LP; ++s) cur[u][c][s] = nxt[u][c][s];
         }
+    }
+}
+
+// ---- sweep for pairwise potentials given per edge ---------------------------------------------
+//
+// theta_{i-r,i}(mu,lambda) read from a table of its own per edge, [R][N][L][L] with entry
+// (r, i) the edge that arrives at node i (Eq. isgmr / Eq. trwp as written, before the
+// decomposition into edge weight times V); for L <= 64.  One wavefront per scanline, lanes
+// over lambda.  Row mu of a node's table is one coalesced load of L floats; the table is
+// fetched in two halves of HALF = 4, 8, 16 or 32 rows into two register sets, each reloaded
+// for the next node as soon as the current node is done with it, so that one half is always
+// in flight behind the evaluation of the other.  h(mu) comes from the lane that owns mu
+// (v_readlane with a constant lane).  The candidate is the plain sum h(mu) + theta(mu,lambda).
+template <int HALF, int RMAX, bool TRWP>
+__global__ void __launch_bounds__(64)
+mrf_fwd_sweep_edge(const MrfFwdParams P)
+{
+    const int L = P.g.L;
+    const int lane = threadIdx.x & 63;
+    const bool valid = lane < L;
+    const int lamc = valid ? lane : 0;
+
+    const long long blk = blockIdx.x;
+    int ri = 0;
+    while (ri + 1 < P.r_count && blk >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = blk - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long N = P.g.N;
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+
+    // sources of h as in mrf_fwd_sweep: unused slots read the unary with factor 0
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = (c <= n_src) ? 1.0f : 0.0f;
+        is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = (c == n_pre + 1) ? 1.0f : 0.0f;
+
+    if (valid) {
+        P.m_out[((size_t)r * N + head) * L + lane] = 0.0f;
+        P.p[((size_t)r * N + head) * L + lane] = 0;
+    }
+    if (lane == 0) P.q[(size_t)r * N + head] = 0;
+    if (len < 2) return;
+
+    const int vzero = mrf_opaque_zero();
+    const float *rbase = P.rho_e ? P.rho_e + (size_t)r * N : nullptr;
+    const float *tbase = P.Te + (size_t)r * N * L * L;
+    // rows mu0 .. mu0 + HALF - 1 of the table of the edge that arrives at node n of the scanline
+    // (rows past L - 1 repeat the last row and are masked at use; a node past the end repeats the last)
+    auto load_half = [&](float (&dst)[HALF], int n, int mu0) {
+        n = n < len ? n : len - 1;
+        const float *tb = tbase + (size_t)(head + (long long)n * nstep) * L * L + lamc;
+#pragma unroll
+        for (int m = 0; m < HALF; ++m) {
+            const int mu = mu0 + m < L ? mu0 + m : L - 1;
+            dst[m] = tb[(size_t)mu * L];
+        }
+    };
+    float ta[HALF], tb2[HALF];
+    float cur[RMAX], nxt[RMAX];
+    float rcur = rho, rnxt = rho;
+    auto prefetch = [&](float (&dst)[RMAX], float &rdst, int nj) {      // inputs of the update nj -> nj+1
+        nj = nj < len - 2 ? nj : len - 2;
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][(size_t)j * L + lamc];
+        rdst = rho;
+        if (TRWP && rbase) rdst = rbase[(size_t)(j + nstep) + vzero];
+    };
+    prefetch(cur, rcur, 0);
+    load_half(ta, 1, 0);
+    load_half(tb2, 1, HALF);
+
+    float carry = 0.0f;
+    for (int n = 1; n < len; ++n) {
+        prefetch(nxt, rnxt, n);
+        const long long i = head + (long long)n * nstep;
+
+        float v = cur[0];
+        if (TRWP) {
+            float mrm = 0.0f;
+#pragma unroll
+            for (int c = 1; c < RMAX; ++c) {
+                v = __builtin_fmaf(carry_at[c], carry, v);
+                v = __builtin_fmaf(use[c], cur[c], v);
+                mrm = __builtin_fmaf(is_rm[c], cur[c], mrm);
+            }
+            v = __builtin_fmaf(carry_at[RMAX], carry, v);
+            v = rcur * v;
+            v = v - mrm;
+        } else {
+            v = v + carry;
+#pragma unroll
+            for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[c], v);
+        }
+
+        // ascending mu with a strict '<': the lowest minimiser survives
+        float best = INFINITY;
+        int arg = 0;
+#pragma unroll
+        for (int m = 0; m < HALF; ++m) {
+            const float hm = mrf_readlane_f32(v, m);
+            const float dl = (m < L) ? hm + ta[m] : INFINITY;
+            if (dl < best) { best = dl; arg = m; }
+        }
+        load_half(ta, n + 1, 0);
+#pragma unroll
+        for (int m = 0; m < HALF; ++m) {
+            const float hm = mrf_readlane_f32(v, (HALF + m) & 63);
+            const float dl = (HALF + m < L) ? hm + tb2[m] : INFINITY;
+            if (dl < best) { best = dl; arg = HALF + m; }
+        }
+        load_half(tb2, n + 1, HALF);
+
+        const float tv = valid ? best : INFINITY;
+        const float tq = mrf_wave_min(tv);
+        const unsigned long long bal = __ballot(tv == tq);
+        const int qidx = __ffsll((long long)bal) - 1;
+        carry = valid ? tv - tq : 0.0f;
+        if (valid) {
+            P.m_out[((size_t)r * N + i) * L + lane] = carry;
+            P.p[((size_t)r * N + i) * L + lane] = (uint8_t)arg;
+        }
+        if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+
+        rcur = rnxt;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c) cur[c] = nxt[c];
     }
 }
 

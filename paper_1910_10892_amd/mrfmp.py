@@ -41,6 +41,7 @@ class _CProblem(ctypes.Structure):
         ("pairwise_kind", ctypes.c_int32),
         ("trunc", ctypes.c_float), ("scale", ctypes.c_float),
         ("rho_edge", ctypes.c_void_p),
+        ("pairwise_edge", ctypes.c_void_p),
     ]
 
 
@@ -132,6 +133,7 @@ class MrfProblem:
     scale: float = 1.0
     shape: Optional[tuple] = None  # (B,H,W,L); taken from unary when given
     rho_edge: object = None       # [R,B,H,W] float32 GPU tensor or None (TRWP: rho per directed edge)
+    pairwise_edge: object = None  # [R,B,H,W,L,L] float32 GPU tensor or None (pairwise potentials per edge)
 
     def __post_init__(self):
         if self.shape is None:
@@ -157,6 +159,7 @@ class MrfProblem:
         c.pairwise_kind = int(self.pairwise_kind)
         c.trunc, c.scale = float(self.trunc), float(self.scale)
         c.rho_edge = _dev_ptr(self.rho_edge, "float32")
+        c.pairwise_edge = _dev_ptr(self.pairwise_edge, "float32")
         return c
 
 

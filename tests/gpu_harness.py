@@ -29,13 +29,16 @@ class GpuProblem:
         B, H, W, L = pr.shape
         R, K = pr.R, pr.K
         t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-        self.unary, self.pairwise, self.edge_weight = t(pr.unary), t(pr.pairwise), t(pr.edge_weight)
+        self.pairwise_edge = t(getattr(pr, "pairwise_edge", None))
+        self.edge_tables = self.pairwise_edge is not None     # then V and the edge weights are not used
+        self.unary, self.edge_weight = t(pr.unary), t(pr.edge_weight)
+        self.pairwise = None if self.edge_tables else t(pr.pairwise)
         self.grad_cost = t(pr.grad_cost)
         self.algo = mrf.MRF_ISGMR if pr.algo == "isgmr" else mrf.MRF_TRWP
         self.rho_edge = t(getattr(pr, "rho_edge", None))
         self.prob = mrf.MrfProblem(self.unary, self.pairwise, pr.dirs, K, self.edge_weight,
                                    pr.edge_weight_scalar, pr.rho, pr.pairwise_kind, pr.trunc, pr.scale,
-                                   rho_edge=self.rho_edge)
+                                   rho_edge=self.rho_edge, pairwise_edge=self.pairwise_edge)
         self.cost = torch.empty((B, H, W, L), dtype=torch.float32, device=dev)
         self.labels = torch.empty((B, H, W), dtype=torch.uint8, device=dev)
         self.p = torch.empty((K, R, B, H, W, L), dtype=torch.uint8, device=dev)
@@ -43,7 +46,8 @@ class GpuProblem:
         self.messages = torch.empty((R, B, H, W, L), dtype=torch.float32, device=dev) if want_messages else None
         self.grad_unary = torch.empty((B, H, W, L), dtype=torch.float32, device=dev)
         self.grad_edge_weight = torch.empty((R, B, H, W), dtype=torch.float32, device=dev)
-        self.grad_pairwise = torch.empty((L, L), dtype=torch.float32, device=dev)
+        self.grad_pairwise = torch.empty((R, B, H, W, L, L) if self.edge_tables else (L, L),
+                                         dtype=torch.float32, device=dev)
         nbytes = max(mrf.mrf_workspace_bytes(self.prob, self.algo, False),
                      mrf.mrf_workspace_bytes(self.prob, self.algo, True))
         assert nbytes > 0
@@ -56,7 +60,8 @@ class GpuProblem:
     def backward(self, want_w=True, want_V=True):
         fn = mrf.mrf_isgmr_backward if self.algo == mrf.MRF_ISGMR else mrf.mrf_trwp_backward
         fn(self.prob, self.grad_cost, self.p, self.q, self.grad_unary,
-           self.grad_edge_weight if want_w else None, self.grad_pairwise if want_V else None, self.workspace)
+           self.grad_edge_weight if (want_w and not self.edge_tables) else None,
+           self.grad_pairwise if want_V else None, self.workspace)
 
     def poison_outputs(self):
         """Outputs must be fully overwritten: fill them with garbage first."""

@@ -624,3 +624,74 @@ def test_trwp_with_one_rho_per_edge(oracle, case):
     pr.rho = None
     full_check(oracle, pr, want_V=False)
     full_check(oracle, pr, want_V=True)
+
+
+EDGE_TABLE_CASES = [
+    # seed, algo, B, H, W, L, dirs, K, integer_valued
+    (301, "isgmr", 2, 5, 7, 21, DIRS4, 2, False),
+    (302, "trwp", 1, 6, 5, 21, DIRS4, 3, False),
+    (303, "isgmr", 1, 4, 6, 64, DIRS8, 2, False),
+    (304, "trwp", 1, 3, 9, 33, DIRS8, 2, True),
+    (305, "isgmr", 1, 4, 4, 5, DIRS16, 2, True),
+    (306, "trwp", 1, 7, 1, 9, [(1, 0), (-1, 0), (0, 1)], 2, False),
+    (307, "trwp", 1, 2, 8, 1, DIRS4, 2, False),
+    (308, "isgmr", 1, 3, 5, 16, DIRS4, 1, False),
+    (309, "trwp", 1, 3, 5, 17, DIRS4, 2, False),
+]
+
+
+@pytest.mark.parametrize("case", EDGE_TABLE_CASES, ids=lambda c: "seed%d" % c[0])
+def test_pairwise_potentials_given_per_edge(oracle, case):
+    """Pairwise potentials as one L x L table per directed edge (Eq. isgmr / Eq. trwp as written)
+    and the gradient of those tables (Eq. supp-gradient-pairwise): forward and backward against the
+    oracle, with and without the table gradient; for TRWP also with one rho per edge."""
+    print("case per-edge tables", case, flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv = case
+    R = len(dirs)
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=False,
+                        rho=np.linspace(0.3, 0.9, R))
+    rng = np.random.default_rng(8000 + seed)
+    Te = rng.integers(0, 3, (R, B, H, W, L, L)) if iv else rng.random((R, B, H, W, L, L))
+    pr.pairwise_edge = Te.astype(np.float32)
+
+    def check(want_V):
+        from gpu_harness import run_gpu
+        g = run_gpu(pr, want_V=want_V)
+        f = oracle.forward(pr.algo, pr.unary, None, pr.dirs, pr.K, rho=pr.rho, rho_edge=pr.rho_edge,
+                           pairwise_edge=pr.pairwise_edge)
+        check_forward(g, f)
+        b = {}
+        for dt in (np.float32, np.float64):
+            b[dt] = oracle.backward(pr.algo, pr.shape, None, pr.dirs, pr.K, pr.grad_cost.astype(dt), f.p, f.q,
+                                    rho=pr.rho, dtype=dt, per_edge_pairwise=True,
+                                    rho_edge=None if pr.rho_edge is None else pr.rho_edge.astype(dt))
+        check_grad("grad_unary", g.grad_unary, b[np.float32].grad_unary, b[np.float64].grad_unary)
+        if want_V:
+            check_grad("grad_pairwise_edge", g.grad_pairwise, b[np.float32].grad_pairwise_edge,
+                       b[np.float64].grad_pairwise_edge)
+        return g
+
+    a = check(True)
+    c = check(False)
+    np.testing.assert_allclose(c.grad_unary, a.grad_unary, rtol=1e-5, atol=1e-4)
+    if algo == "trwp":
+        pr.rho_edge = rng.uniform(0.2, 0.9, (R, B, H, W)).astype(np.float32)
+        pr.rho = None
+        check(True)
+
+
+def test_per_edge_tables_argument_errors():
+    import torch
+    import paper_1910_10892_amd as mrf
+    dev = torch.device("cuda:0")
+    L = 70
+    z = lambda *s: torch.zeros(s, dtype=torch.float32, device=dev)
+    prob = mrf.MrfProblem(z(1, 2, 2, L), None, DIRS4, 1, pairwise_edge=z(4, 1, 2, 2, L, L))
+    assert mrf.mrf_workspace_bytes(prob, mrf.MRF_ISGMR, False) == 0          # more than 64 labels
+    L = 4
+    prob = mrf.MrfProblem(z(1, 2, 2, L), None, DIRS4, 1, pairwise_edge=z(4, 1, 2, 2, L, L))
+    ws = torch.empty(max(mrf.mrf_workspace_bytes(prob, mrf.MRF_ISGMR, True), 256), dtype=torch.uint8, device=dev)
+    p = torch.zeros((1, 4, 1, 2, 2, L), dtype=torch.uint8, device=dev)
+    q = torch.zeros((1, 4, 1, 2, 2), dtype=torch.uint8, device=dev)
+    with pytest.raises(mrf.MrfError):      # there are no edge weights to differentiate
+        mrf.mrf_isgmr_backward(prob, z(1, 2, 2, L), p, q, z(1, 2, 2, L), z(4, 1, 2, 2), None, ws)
