@@ -120,3 +120,34 @@ def test_autograd_wrapper_returns_the_library_gradients(algo):
     np.testing.assert_allclose(unary.grad.cpu().numpy(), b.grad_unary, rtol=1e-4, atol=1e-6)
     np.testing.assert_allclose(w.grad.cpu().numpy(), b.grad_edge_weight, rtol=1e-4, atol=1e-6)
     np.testing.assert_allclose(V.grad.cpu().numpy(), b.grad_pairwise, rtol=1e-4, atol=1e-6)
+
+
+@pytest.mark.parametrize("algo", ["isgmr", "trwp"])
+def test_autograd_wrapper_for_per_edge_tables(algo):
+    """The same composite with pairwise potentials given per edge: gradients of unary and of the
+    tables equal the oracle's."""
+    import torch
+    from oracle import mrf_oracle, mrf_heads_oracle as ho
+    from paper_1910_10892_amd.autograd import message_passing_edge_tables
+    import paper_1910_10892_amd as mrf
+    print("case autograd, per-edge tables", algo, flush=True)
+    pr = random_problem(34, algo, 1, 5, 6, 9, DIRS4, 2, rho=np.linspace(0.4, 0.8, 4))
+    rng = np.random.default_rng(78)
+    Te = rng.random((4, 1, 5, 6, 9, 9)).astype(np.float32)
+    target = rng.uniform(0, 8, (1, 5, 6)).astype(np.float32)
+    unary = torch.from_numpy(pr.unary).cuda().requires_grad_(True)
+    tab = torch.from_numpy(Te).cuda().requires_grad_(True)
+    cost, labels = message_passing_edge_tables(unary, tab, algo=algo, dirs=pr.dirs, K=pr.K, rho=pr.rho)
+    ws = torch.empty(mrf.mrf_softmin_l1_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
+    loss = torch.empty((1,), dtype=torch.float64, device="cuda:0")
+    gcost = torch.empty_like(cost)
+    mrf.mrf_softmin_l1(cost.detach(), torch.from_numpy(target).cuda(), None, None, loss, gcost, ws)
+    cost.backward(gcost)
+    f = mrf_oracle.forward(pr.algo, pr.unary, None, pr.dirs, pr.K, rho=pr.rho, pairwise_edge=Te)
+    assert (labels.cpu().numpy() == f.labels).all()
+    _, l_ref, g_ref = ho.softmin_l1(f.cost, target)
+    b = mrf_oracle.backward(pr.algo, pr.shape, None, pr.dirs, pr.K, g_ref.astype(np.float32), f.p, f.q, rho=pr.rho,
+                            dtype=np.float64, per_edge_pairwise=True)
+    assert loss.cpu().numpy()[0] == pytest.approx(l_ref, rel=1e-6)
+    np.testing.assert_allclose(unary.grad.cpu().numpy(), b.grad_unary, rtol=1e-4, atol=1e-6)
+    np.testing.assert_allclose(tab.grad.cpu().numpy(), b.grad_pairwise_edge, rtol=1e-4, atol=1e-6)
