@@ -1143,16 +1143,18 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    float dl[2 * TW - 1];
+                    // The two candidates at distance d share f(d), and a correctly rounded fma is
+                    // non-decreasing in its addend: the smaller of the two comes from the smaller h.
+                    float dl[TW];
+                    dl[0] = __builtin_fmaf(wgt, f[0], nb[s][TW - 1]);
 #pragma unroll
-                    for (int o = 0; o < 2 * TW - 1; ++o) {
-                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
-                        dl[o] = __builtin_fmaf(wgt, f[dist], nb[s][o]);
-                    }
-                    float W = dl[0];
+                    for (int d = 1; d < TW; ++d)
+                        dl[d] = __builtin_fmaf(wgt, f[d], mrf_min(nb[s][TW - 1 - d], nb[s][TW - 1 + d]));
+                    float W = mrf_min(dl[0], gmin);
 #pragma unroll
-                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
-                    tv[s] = (lam < L) ? mrf_min(W, gmin) : INFINITY;
+                    for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
+                    if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
+                    tv[s] = (lam < L) ? W : INFINITY;
                 }
                 if (f0zero) {
                     tq = hmin;
@@ -1273,16 +1275,18 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    float dl[2 * TW - 1];
+                    // The two candidates at distance d share f(d), and a correctly rounded fma is
+                    // non-decreasing in its addend: the smaller of the two comes from the smaller h.
+                    float dl[TW];
+                    dl[0] = __builtin_fmaf(wgt, f[0], nb[s][TW - 1]);
 #pragma unroll
-                    for (int o = 0; o < 2 * TW - 1; ++o) {
-                        const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
-                        dl[o] = __builtin_fmaf(wgt, f[dist], nb[s][o]);
-                    }
-                    float W = dl[0];
+                    for (int d = 1; d < TW; ++d)
+                        dl[d] = __builtin_fmaf(wgt, f[d], mrf_min(nb[s][TW - 1 - d], nb[s][TW - 1 + d]));
+                    float W = mrf_min(dl[0], gmin);
 #pragma unroll
-                    for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
-                    tv[s] = (lam < L) ? mrf_min(W, gmin) : INFINITY;
+                    for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
+                    if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
+                    tv[s] = (lam < L) ? W : INFINITY;
                 }
                 if (f0zero) {
                     tq = hmin;
@@ -1862,17 +1866,18 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
             float tv;
             if (wpos) {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
-                float dl[2 * TW - 1];
+                // The two candidates at distance d share f(d), and a correctly rounded fma is
+                // non-decreasing in its addend: the smaller of the two comes from the smaller h.
+                float dl[TW];
+                dl[0] = __builtin_fmaf(wgt, f[0], v);
 #pragma unroll
-                for (int o = 0; o < 2 * TW - 1; ++o) {
-                    const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
-                    const float hvv = (o == TW - 1) ? v : hb[lam + o - (TW - 1)];
-                    dl[o] = __builtin_fmaf(wgt, f[dist], hvv);
-                }
-                float W = dl[0];
+                for (int d = 1; d < TW; ++d)
+                    dl[d] = __builtin_fmaf(wgt, f[d], mrf_min(hb[lam - d], hb[lam + d]));
+                float W = mrf_min(dl[0], gmin);
 #pragma unroll
-                for (int o = 1; o + 1 < 2 * TW - 1; o += 2) W = mrf_min3(W, dl[o], dl[o + 1]);
-                tv = valid ? mrf_min(W, gmin) : INFINITY;
+                for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
+                if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
+                tv = valid ? W : INFINITY;
             } else {
                 float best = INFINITY;
                 for (int mu = 0; mu < L; ++mu) {
