@@ -1119,10 +1119,14 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             float nwgt = lw[lsn];
 
             const float hmin = mrf_wave_min(hm);
-            if (lane == 0) { ringw[slot] = wgt; ringhm[slot] = hmin; }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-            __builtin_amdgcn_wave_barrier();
-            if (lane == 0) __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            // LDS executes a wavefront's operations in order: whoever sees the counter also sees the
+            // node's ring entries written before it, so no wait is needed in between
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 0) {
+                ringw[slot] = wgt;
+                ringhm[slot] = hmin;
+                __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (ask) {
                 lseen = __builtin_amdgcn_readfirstlane(flag);
@@ -1261,10 +1265,14 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 for (int o = 0; o < 2 * TW - 1; ++o)
                     nb[s][o] = (o == TW - 1) ? a[s] : hbuf[lane + 64 * s + o - (TW - 1)];
             const float hmin = mrf_wave_min(hm);
-            if (lane == 0 && !past) { ringw[slot] = wgt; ringhm[slot] = hmin; }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-            __builtin_amdgcn_wave_barrier();
-            if (lane == 0 && !past) __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            // LDS executes a wavefront's operations in order: whoever sees the counter also sees the
+            // node's ring entries written before it, so no wait is needed in between
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane == 0 && !past) {
+                ringw[slot] = wgt;
+                ringhm[slot] = hmin;
+                __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
             // a past step re-reads the slot of an earlier step: its result is never used
