@@ -720,8 +720,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     const int lam = lane + 64 * s;
                     a_ext[slot * LL + lam] = (lam == qv) ? ev[s] - tot : ev[s];
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-                __builtin_amdgcn_wave_barrier();
+                // (LDS keeps a wavefront's operations in order: the counter lands behind the entries)
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 if (lane == 0) __hip_atomic_store(&pre_done[jw], tt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             const int tp = tt - NI;

@@ -2144,8 +2144,8 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
                 for (int c = 0; c < 4; ++c) dl[m4 + c] = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
             }
             if (IDX) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-                __builtin_amdgcn_wave_barrier();
+                // (LDS keeps a wavefront's operations in order: the counter lands behind the entries)
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 if (lane == 0) __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             } else {
                 mrf_wave_lds_fence();
