@@ -773,18 +773,32 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     constexpr int NW0 = LOADER ? 2 : 1;           // wavefronts in front of the index wavefronts
     constexpr int NRL = 8;                        // slots of the loader's ring (a power of two, >= D)
     constexpr int LL = 64 * LP;
-    __shared__ float lring[LOADER ? NRL : 1][5][LOADER ? LL : 1];   // partial sum, 3 messages, r- vector
-    __shared__ float lw[NRL];
-    __shared__ int loaded;                        // last step the loader has published
     constexpr int HB = 64 * LP + 2 * TW;          // h with TW entries of padding on both sides
     constexpr int NR = 8;                         // ring slots (a power of two, >= D)
     static_assert(NR >= D && (NR & (NR - 1)) == 0 && NI <= 4, "ring depth");
     constexpr int NT = 64 * (NW0 + NI);
-    __shared__ float ring[NR][HB];
-    __shared__ float ringw[NR], ringhm[NR];
-    __shared__ float ftab[TW + 1];
-    __shared__ int produced;                      // last step published
-    __shared__ __align__(16) int consumed[4];     // per index wavefront: last step finished
+    // One block with the h ring at LDS address 0: the value wavefront's fifteen neighbour reads per
+    // label slot then fit the 8-bit offsets of ds_read2_b32 and need no address arithmetic.
+    struct Shared {
+        float ring[NR][HB];
+        float ringw[NR], ringhm[NR];
+        float ftab[TW + 1];
+        int produced;                             // last step published
+        int loaded;                               // last step the loader has published
+        alignas(16) int consumed[4];              // per index wavefront: last step finished
+        float lw[NRL];
+        alignas(16) float lring[LOADER ? NRL : 1][5][LOADER ? LL : 1];   // partial sum, 3 messages, r- vector
+    };
+    __shared__ Shared sm;
+    auto &ring = sm.ring;
+    auto &ringw = sm.ringw;
+    auto &ringhm = sm.ringhm;
+    auto &ftab = sm.ftab;
+    int &produced = sm.produced;
+    int &loaded = sm.loaded;
+    auto &consumed = sm.consumed;
+    auto &lw = sm.lw;
+    auto &lring = sm.lring;
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -1082,7 +1096,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
             float a[LP];
-            float hm = INFINITY;
+            float hm = 0.0f;
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 float v = in[0][s] + carry[s];
@@ -1091,9 +1105,11 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 v = rho * v;
                 v = v - in[4][s];
                 const int lam = lane + 64 * s;
-                if (lam < L) hbuf[lam] = v;
+                // (lanes past L rewrite the +inf their ring entries hold anyway: no divergence; what
+                // they carry from node to node is never looked at)
                 a[s] = lam < L ? v : INFINITY;
-                hm = mrf_min(hm, a[s]);
+                hbuf[lam] = a[s];
+                hm = s == 0 ? a[s] : mrf_min(hm, a[s]);
             }
             mrf_wave_lds_fence();
             float nb[LP][2 * TW - 1];
@@ -1106,10 +1122,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             // (read first: the LDS queue keeps the order) does not cover them yet, they are read
             // again after waiting
             const bool more = nn + 1 < len;
-            const bool ask = more && lseen < nn + 1;
             const int lsn = (nn + 1) & (NRL - 1);
-            int flag = lseen;
-            if (ask) flag = __hip_atomic_load(&loaded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const int flag = __hip_atomic_load(&loaded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             float nin[5][LP];
 #pragma unroll
@@ -1128,7 +1142,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (ask) {
+            if (more) {
                 lseen = __builtin_amdgcn_readfirstlane(flag);
                 if (lseen < nn + 1) {
                     lseen = await_loader(nn + 1);
@@ -1146,7 +1160,6 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
-                    const int lam = lane + 64 * s;
                     // The two candidates at distance d share f(d), and a correctly rounded fma is
                     // non-decreasing in its addend: the smaller of the two comes from the smaller h.
                     float dl[TW];
@@ -1158,14 +1171,14 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                     for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
                     if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
-                    tv[s] = (lam < L) ? W : INFINITY;
+                    tv[s] = W;
                 }
                 if (f0zero) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
 #pragma unroll
-                    for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, (lane + 64 * s < L) ? tv[s] : INFINITY);
                     tq = mrf_wave_min(mn);
                 }
             } else {
@@ -1187,7 +1200,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 tq = mrf_wave_min(mn);
             }
 #pragma unroll
-            for (int s = 0; s < LP; ++s) carry[s] = (lane + 64 * s < L) ? tv[s] - tq : 0.0f;
+            for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
             wgt = nwgt;
 #pragma unroll
             for (int c = 0; c < 5; ++c)
