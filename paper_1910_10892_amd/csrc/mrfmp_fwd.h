@@ -1243,7 +1243,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
             float a[LP];
-            float hm = INFINITY;
+            float hm = 0.0f;
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 float v = cur[u][0][s];
@@ -1264,9 +1264,11 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
                 }
                 const int lam = lane + 64 * s;
-                if (lam < L && !past) hbuf[lam] = v;
+                // (lanes past L rewrite the +inf their ring entries hold anyway: no divergence; what
+                // they carry from node to node is never looked at)
                 a[s] = lam < L ? v : INFINITY;
-                hm = mrf_min(hm, a[s]);
+                if (!past) hbuf[lam] = a[s];
+                hm = s == 0 ? a[s] : mrf_min(hm, a[s]);
             }
             // the neighbours' h for the window, requested before the reduction so that the LDS
             // latency passes behind it (the LDS queue keeps the order: writes above, then reads)
@@ -1295,7 +1297,6 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
-                    const int lam = lane + 64 * s;
                     // The two candidates at distance d share f(d), and a correctly rounded fma is
                     // non-decreasing in its addend: the smaller of the two comes from the smaller h.
                     float dl[TW];
@@ -1307,14 +1308,14 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                     for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
                     if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
-                    tv[s] = (lam < L) ? W : INFINITY;
+                    tv[s] = W;
                 }
                 if (f0zero) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
 #pragma unroll
-                    for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, (lane + 64 * s < L) ? tv[s] : INFINITY);
                     tq = mrf_wave_min(mn);
                 }
             } else {
@@ -1336,7 +1337,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 tq = mrf_wave_min(mn);
             }
 #pragma unroll
-            for (int s = 0; s < LP; ++s) carry[s] = (lane + 64 * s < L) ? tv[s] - tq : 0.0f;
+            for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
         }
 #pragma unroll
         for (int u = 0; u < D; ++u) {
