@@ -228,7 +228,7 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           index wavefronts of their own do the argmin tables and the stores: 0 = by launch size,
  *           1 = never, 2 = always
  *   knob 10: index wavefronts per scanline in that layout: 0 = default, 4, 8
- *   knob 11: index wavefront next to the value wavefront in the sweep of knob 3: 0 = by launch size,
+ *   knob 11: two index wavefronts next to the value wavefront in the sweep of knob 3: 0 = by launch size,
  *           1 = never, 2 = always
  *   knob 8: loader wavefront in front of the value wavefront (TRWP, window sweep, two index
  *           wavefronts): 0 = by launch size, 1 = never, 2 = whenever it applies

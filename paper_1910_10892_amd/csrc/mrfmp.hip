@@ -262,16 +262,17 @@ template <int SEG, int MU>
 hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((scanlines + 64 / SEG - 1) / (64 / SEG));
-    // few wavefronts in the launch: a second one per workgroup for the argmin tables and the stores
+    // few wavefronts in the launch: further ones per workgroup for the argmin tables and the stores
+    // (two of them: an index wavefront has more to do per node than the value wavefront)
     const bool idx = g_tune_pack_idx != 1 && (g_tune_pack_idx == 2 || blocks <= 1024);
 #define MRF_P(rm, d) \
     if (rmax == rm) { \
         if (idx) { \
-            if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true, true>), dim3(blocks), dim3(128), 0, st, P); \
-            else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false, true>), dim3(blocks), dim3(128), 0, st, P); \
+            if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true, 2>), dim3(blocks), dim3(192), 0, st, P); \
+            else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false, 2>), dim3(blocks), dim3(192), 0, st, P); \
         } else { \
-            if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true, false>), dim3(blocks), dim3(64), 0, st, P); \
-            else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false, false>), dim3(blocks), dim3(64), 0, st, P); \
+            if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, true, 0>), dim3(blocks), dim3(64), 0, st, P); \
+            else hipLaunchKernelGGL((mrf_fwd_sweep_packed<SEG, MU, rm, d, false, 0>), dim3(blocks), dim3(64), 0, st, P); \
         } \
         return hipGetLastError(); \
     }

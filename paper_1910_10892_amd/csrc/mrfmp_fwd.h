@@ -1950,11 +1950,12 @@ __device__ inline float mrf_segment_min(float v)
 }
 
 // MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG).
-// IDX: a second wavefront per workgroup takes the argmin tables and the stores (as in
+// IDX = 1, 2: that many further wavefronts per workgroup take the argmin tables and the stores (as in
 // mrf_fwd_sweep_window_duo): the first computes values only and hands each node's h and
-// weights over through a ring in LDS.  For launches that leave most issue slots idle.
-template <int SEG, int MU, int RMAX, int D, bool TRWP, bool IDX>
-__global__ void __launch_bounds__(IDX ? 128 : 64)
+// weights over through a ring in LDS.  For launches that leave most issue slots idle; the host
+// uses two, because an index wavefront has more to do per node than the value wavefront.
+template <int SEG, int MU, int RMAX, int D, bool TRWP, int IDX>
+__global__ void __launch_bounds__(64 * (1 + IDX))
 mrf_fwd_sweep_packed(const MrfFwdParams P)
 {
     static_assert(MU % 4 == 0 && MU <= SEG, "source label count");
@@ -1964,10 +1965,12 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     static_assert(NR >= D || !IDX, "ring depth");
     __shared__ __align__(16) float hring[NR][NSEG][SEGP];
     __shared__ float wring[NR][64];
-    __shared__ int produced, consumed;
+    __shared__ int produced;
+    __shared__ int consumed[2];                   // per index wavefront: last step finished
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
-    const bool index_wave = IDX && __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) > 0;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const bool index_wave = IDX && wave > 0;
     const int seg = lane / SEG, lam = lane % SEG;
     const bool valid = lam < L;
     const int lamc = valid ? lam : 0;
@@ -2026,11 +2029,11 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             hring[sl2][seg][lam] = INFINITY;      // entries mu >= L stay +inf: they never win
             if (lam < 4) hring[sl2][seg][SEG + lam] = INFINITY;
         }
-        if (lane == 0) { produced = 0; consumed = 0; }
+        if (lane == 0) { produced = 0; consumed[0] = 1 - IDX; consumed[1] = 0; }   // "finished" starts one turn before
     }
     __syncthreads();
 
-    if ((!IDX || index_wave) && act_seg && valid) {
+    if ((!IDX || wave == 1) && act_seg && valid) {
         P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
         P.p[((size_t)r * N + head) * L + lam] = 0;
         if (lam == 0) P.q[(size_t)r * N + head] = 0;
@@ -2046,8 +2049,10 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 
     if (index_wave) {
         // ---- p, q and all stores, one node behind or more ----------------------------------
+        // index wavefront jw takes steps 1 + jw, 1 + jw + IDX, ...
+        const int jw = wave - 1;
         int seen = 0;
-        for (int nn = 1; nn < maxlen; ++nn) {
+        for (int nn = 1 + jw; nn < maxlen; nn += (IDX > 0 ? IDX : 1)) {
             while (seen < nn) {
                 seen = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
@@ -2067,7 +2072,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
                 for (int c = 0; c < 4; ++c) dl[m4 + c] = __builtin_fmaf(wgt, Vr[m4 + c], hq[c]);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-            if (lane == 0) __hip_atomic_store(&consumed, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (lane == 0) __hip_atomic_store(&consumed[jw], nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             float best = mrf_min(dl[0], dl[1]);
 #pragma unroll
             for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
@@ -2137,8 +2142,16 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             if (IDX) {
                 // the slot was last used by step nn - NR
                 while (freed < nn - NR) {
-                    freed = __builtin_amdgcn_readfirstlane(
-                        __hip_atomic_load(&consumed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    // the index wavefronts take the steps in turn: behind the slowest one's last
+                    // step, the others have finished theirs
+                    int lo = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    if (IDX > 1) {
+                        const int c1 = __builtin_amdgcn_readfirstlane(
+                            __hip_atomic_load(&consumed[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                        lo = c1 < lo ? c1 : lo;
+                    }
+                    freed = lo + IDX - 1;
                     if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
                 }
