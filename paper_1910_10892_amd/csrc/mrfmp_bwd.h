@@ -1113,6 +1113,20 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
         for (int t0 = 0; t0 < maxlen; t0 += D) {
 #pragma unroll
             for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], t0 + D + u);
+            // What arrives from elsewhere, and its label sums, for the D nodes of the group at once
+            // (independent reductions overlap).  The label sum of g = carry + ext is the label sum
+            // of ext: the scattered vector of a node sums to zero, because the reparametrisation took
+            // exactly its sum off one entry, hence so does the carry (up to double rounding).
+            double ext[D], tot[D];
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                double e = 0.0;
+#pragma unroll
+                for (int c = 0; c < NS; ++c) e = __builtin_fma(cG[c], (double)cur[u][c], e);
+                ext[u] = valid ? e : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < D; ++u) tot[u] = mrf_segment_sum_f64<SEG>(ext[u]);
 #pragma unroll
             for (int u = 0; u < D; ++u) {
                 const int tt = t0 + u;
@@ -1122,10 +1136,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
                 const long long i = head + (long long)n * nstep;
                 const long long j = i - nstep;
 
-                double g = carry;
-#pragma unroll
-                for (int c = 0; c < NS; ++c) g = __builtin_fma(cG[c], (double)cur[u][c], g);
-                g = valid ? g : 0.0;
+                double g = valid ? carry + ext[u] : 0.0;
                 if (any_unary) {        // (uniform) some scanline of this launch forms grad theta
                     double accT = carry;
 #pragma unroll
@@ -1136,8 +1147,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
                 const int pv = pcur[u] < L ? pcur[u] : L - 1;
                 const int qv = qcur[u] < L ? qcur[u] : L - 1;
                 // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
-                const double tot = mrf_segment_sum_f64<SEG>(g);
-                if (lam == qv) g = g - tot;
+                if (lam == qv) g = g - tot[u];
 
                 if (valid) __hip_atomic_fetch_add(&sbuf[pv], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 mrf_wave_lds_fence();
