@@ -1814,15 +1814,18 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
         float m;
         bool all;
         do {
+            // all four posts in one batch of LDS reads (those of absent wavefronts are ignored)
+            unsigned long long e[4];
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2)
+                e[w2] = __hip_atomic_load(&box[par][w2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             m = INFINITY;
             all = true;
 #pragma unroll
             for (int w2 = 0; w2 < 4; ++w2) {
-                if (w2 < NWV) {
-                    const unsigned long long e = __hip_atomic_load(&box[par][w2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    all = all && (int)(e >> 32) == step;
-                    m = fminf(m, __int_as_float((int)(unsigned)e));
-                }
+                const bool here = w2 < NWV;
+                all = all && (!here || (int)(e[w2] >> 32) == step);
+                m = mrf_min(m, here ? __int_as_float((int)(unsigned)e[w2]) : INFINITY);
             }
             all = __builtin_amdgcn_readfirstlane((int)all) != 0;
         } while (!all);
@@ -1876,8 +1879,11 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
 #pragma unroll
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
             }
-            if (valid && !past) hb[lam] = v;
-            const float hloc = mrf_wave_min(valid ? v : INFINITY);
+            // (lanes past L rewrite the +inf their ring entries hold anyway: no divergence; what
+            // they carry from node to node is never looked at)
+            const float av = valid ? v : INFINITY;
+            if (!past) hb[lam] = av;
+            const float hloc = mrf_wave_min(av);
             if (threadIdx.x == 0 && !past) ringw[slot] = wgt;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             const float hmin = exchange_min(hmx, par, nn, hloc);
@@ -1899,7 +1905,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
 #pragma unroll
                 for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
                 if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
-                tv = valid ? W : INFINITY;
+                tv = W;
             } else {
                 float best = INFINITY;
                 for (int mu = 0; mu < L; ++mu) {
@@ -1908,15 +1914,15 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                     const float dlt = __builtin_fmaf(wgt, ftab[dist], hb[mu]);
                     if (dlt < best) best = dlt;
                 }
-                tv = valid ? best : INFINITY;
+                tv = best;
             }
             float tq = hmin;
             if (!(wpos && f0zero)) {
                 // general case: the minimum of the new message needs its own exchange
-                const float tloc = mrf_wave_min(tv);
+                const float tloc = mrf_wave_min(valid ? tv : INFINITY);
                 tq = exchange_min(tmx, par, nn, tloc);
             }
-            carry = valid ? tv - tq : 0.0f;
+            carry = tv - tq;
             par ^= 1;
         }
 #pragma unroll
