@@ -2163,7 +2163,9 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
                 }
                 wring[slot][lane] = wgt;
             }
-            if (valid) hring[slot][seg][lam] = v;
+            // (lanes past L rewrite the +inf their entries hold anyway: no divergence; what they
+            // carry from node to node is never looked at)
+            hring[slot][seg][lam] = valid ? v : INFINITY;
             mrf_wave_lds_fence();
 
             // all candidates, their minimum with three-operand minima, then the lowest index
@@ -2188,7 +2190,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
             const float tv = valid ? best : INFINITY;
             const float tq = mrf_segment_min<SEG>(tv);
-            carry = valid ? tv - tq : 0.0f;
+            carry = tv - tq;
             if (IDX) continue;                    // the index wavefront does the rest
 
             int bidx = MU - 1;
