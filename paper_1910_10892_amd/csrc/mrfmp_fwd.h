@@ -1955,6 +1955,30 @@ __device__ inline float mrf_segment_min(float v)
     return v;
 }
 
+// The same minimum for 32-lane segments without the trip through the LDS crossbar that the
+// swizzle costs: five in-place DPP minima leave the minimum of lanes 0..31 in lane 31 and that of
+// lanes 32..63 in lane 63; two v_readlane and a select hand them back.  For the value wavefront
+// of latency-bound launches.  All 64 lanes must be active.
+__device__ inline float mrf_segment_min32_regs(float v, int lane)
+{
+    float a, b;
+    asm("s_nop 1\n\t"
+        "v_min_f32_dpp %2, %2, %2 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %2, %2, %2 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %2, %2, %2 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %2, %2, %2 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %2, %2, %2 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_readlane_b32 %0, %2, 31\n\t"
+        "v_readlane_b32 %1, %2, 63"
+        : "=s"(a), "=s"(b), "+v"(v));
+    return lane < 32 ? a : b;
+}
+
 // MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG).
 // IDX = 1, 2: that many further wavefronts per workgroup take the argmin tables and the stores (as in
 // mrf_fwd_sweep_window_duo): the first computes values only and hands each node's h and
@@ -2189,7 +2213,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 #pragma unroll
             for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
             const float tv = valid ? best : INFINITY;
-            const float tq = mrf_segment_min<SEG>(tv);
+            const float tq = (IDX && SEG == 32) ? mrf_segment_min32_regs(tv, lane) : mrf_segment_min<SEG>(tv);
             carry = tv - tq;
             if (IDX) continue;                    // the index wavefront does the rest
 
