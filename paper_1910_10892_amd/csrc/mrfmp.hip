@@ -144,6 +144,7 @@ int pick_mch(int L, int LP, bool many_sources)
 }
 
 // pairwise potentials per edge (L <= 64): the table is fetched in two halves of ceil(L/2) rows
+// (rounded up to a multiple of four)
 hipError_t launch_edge(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
     g_last_sweep[0] = "mrf_fwd_sweep_edge";
@@ -161,7 +162,7 @@ hipError_t launch_edge(const MrfFwdParams &P, int algo, long long blocks, hipStr
         return hipGetLastError(); \
     }
 #define MRF_EH(half) MRF_E(half, 4) MRF_E(half, 8) MRF_E(half, 16)
-    MRF_EH(4) MRF_EH(8) MRF_EH(16) MRF_EH(32)
+    MRF_EH(4) MRF_EH(8) MRF_EH(12) MRF_EH(16) MRF_EH(20) MRF_EH(24) MRF_EH(28) MRF_EH(32)
 #undef MRF_EH
 #undef MRF_E
     return hipErrorInvalidValue;

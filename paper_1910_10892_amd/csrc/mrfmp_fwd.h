@@ -310,7 +310,7 @@ mrf_fwd_sweep(const MrfFwdParams P)
 // (r, i) the edge that arrives at node i (Eq. isgmr / Eq. trwp as written, before the
 // decomposition into edge weight times V); for L <= 64.  One wavefront per scanline, lanes
 // over lambda.  Row mu of a node's table is one coalesced load of L floats; the table is
-// fetched in two halves of HALF = 4, 8, 16 or 32 rows into two register sets, each reloaded
+// fetched in two halves of HALF = 4, 8, ..., 32 rows into two register sets, each reloaded
 // for the next node as soon as the current node is done with it, so that one half is always
 // in flight behind the evaluation of the other.  h(mu) comes from the lane that owns mu
 // (v_readlane with a constant lane).  The candidate is the plain sum h(mu) + theta(mu,lambda).
