@@ -1,16 +1,34 @@
 // libmrfmp host side: argument checks, workspace layout and launch schedules of the
 // ISGMR / TRWP forward and backward passes (Alg. 1-4).  Allocates nothing.
+//
+// One source, up to three translation units: compiled as it stands it holds everything; with
+// -DMRF_PART=1 / 2 / 3 it holds the forward pass, the backward pass, or the entry points and
+// the heads, so that the build can compile the three in parallel and link them.
 #include "../../include/mrfmp.h"
 #include "mrfmp_device.h"
+
+#ifndef MRF_PART
+#define MRF_PART 0
+#endif
+#define MRF_HAS_FWD (MRF_PART == 0 || MRF_PART == 1)
+#define MRF_HAS_BWD (MRF_PART == 0 || MRF_PART == 2)
+#define MRF_HAS_API (MRF_PART == 0 || MRF_PART == 3)
+
+#if MRF_HAS_FWD
 #include "mrfmp_fwd.h"
+#endif
+#if MRF_HAS_BWD
 #include "mrfmp_bwd.h"
+#endif
+#if MRF_HAS_API
 #include "mrfmp_head.h"
+#endif
 
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
 
-namespace {
+namespace mrf_host {
 
 constexpr size_t kAlign = 256;
 // wavefront-private V-gradient accumulators: many small ones (flushed from LDS once per
@@ -19,7 +37,7 @@ inline long long grad_slots(int L) { return L <= 32 ? 16384 : 1024; }
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-int check_problem(const mrf_problem *pr, int algo, bool forward)
+inline int check_problem(const mrf_problem *pr, int algo, bool forward)
 {
     if (!pr) return MRF_ERR_NULL_POINTER;
     if (algo != MRF_ISGMR && algo != MRF_TRWP) return MRF_ERR_BAD_ALGORITHM;
@@ -52,7 +70,7 @@ int check_problem(const mrf_problem *pr, int algo, bool forward)
     return MRF_OK;
 }
 
-void fill_geom(const mrf_problem *pr, MrfGeom &g)
+inline void fill_geom(const mrf_problem *pr, MrfGeom &g)
 {
     memset(&g, 0, sizeof(g));
     g.B = pr->B; g.H = pr->H; g.W = pr->W; g.L = pr->L; g.R = pr->R;
@@ -69,38 +87,49 @@ void fill_geom(const mrf_problem *pr, MrfGeom &g)
     }
 }
 
-size_t msg_bytes(const mrf_problem *pr)
+inline size_t msg_bytes(const mrf_problem *pr)
 {
     return align_up((size_t)pr->R * pr->B * pr->H * pr->W * pr->L * sizeof(float));
 }
 
-size_t gradv_bytes(const mrf_problem *pr)
+inline size_t gradv_bytes(const mrf_problem *pr)
 {
     return align_up((size_t)grad_slots(pr->L) * pr->L * pr->L * sizeof(double));
 }
 
-// ---- forward sweep dispatch -------------------------------------------------------------
+// ---- process-global state: defined in the translation unit of the entry points ----------
 // tuning knobs (0 = heuristic)
-int g_tune_mch = 0;
-int g_tune_no_window = 0;
-int g_tune_split = 0;      // 0 auto, 1 never, 2 whenever L > 64
-int g_tune_pack = 0;       // 0 auto, 1 never, 2 whenever L <= 32
-int g_tune_duo = 0;        // 0 auto, 1 never, 2 whenever the window applies
-int g_tune_duo_ni = 0;     // index wavefronts per scanline: 0 auto, 1, 2
-int g_tune_loader = 0;     // loader wavefront in the window sweep: 0 auto, 1 never, 2 whenever possible
-int g_tune_squad = 0;      // index wavefronts next to the split layout: 0 by launch size, 1 never, 2 always
-int g_tune_squad_ni = 0;   // how many: 0 auto, 4, 8
-int g_tune_pack_idx = 0;   // index wavefront in the packed dense sweep: 0 by launch size, 1 never, 2 always
-int g_tune_chain = 0;      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
-int g_tune_chain_hot = 0;  // its pre-reduction of the most popular scatter target: 0 auto, 1 never, 2 whenever V is no dense table
-int g_tune_chain_ni = 0;   // its helpers per scanline: 0 auto, 2, 4, 6, 8
-hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-
+#if MRF_HAS_API
+#define MRF_G(decl, init) decl = init
+#else
+#define MRF_G(decl, init) extern decl
+#endif
+MRF_G(int g_tune_mch, 0);
+MRF_G(int g_tune_no_window, 0);
+MRF_G(int g_tune_split, 0);      // 0 auto, 1 never, 2 whenever L > 64
+MRF_G(int g_tune_pack, 0);       // 0 auto, 1 never, 2 whenever L <= 32
+MRF_G(int g_tune_duo, 0);        // 0 auto, 1 never, 2 whenever the window applies
+MRF_G(int g_tune_duo_ni, 0);     // index wavefronts per scanline: 0 auto, 1, 2
+MRF_G(int g_tune_loader, 0);     // loader wavefront in the window sweep: 0 auto, 1 never, 2 whenever possible
+MRF_G(int g_tune_squad, 0);      // index wavefronts next to the split layout: 0 by launch size, 1 never, 2 always
+MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
+MRF_G(int g_tune_pack_idx, 0);   // index wavefronts in the packed dense sweep: 0 by launch size, 1 never, 2 always
+MRF_G(int g_tune_chain, 0);      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
+MRF_G(int g_tune_chain_hot, 0);  // its pre-reduction of the most popular scatter target: 0 auto, 1 never, 2 whenever V is no dense table
+MRF_G(int g_tune_chain_ni, 0);   // its helpers per scanline: 0 auto, 2, 4, 6, 8
+MRF_G(hipEvent_t g_ev_start, nullptr);
+MRF_G(hipEvent_t g_ev_stop, nullptr);
+#undef MRF_G
+#if MRF_HAS_API
 char g_error_detail[256] = "";
 const char *g_last_sweep[2] = {"", ""};      // kernel of the last forward / backward sweep launch
+#else
+extern char g_error_detail[256];
+extern const char *g_last_sweep[2];
+#endif
 
 // records which call failed and how, for mrf_last_error_detail
-int hip_fail(hipError_t e, const char *what)
+inline int hip_fail(hipError_t e, const char *what)
 {
     snprintf(g_error_detail, sizeof(g_error_detail), "%s: %s", what, hipGetErrorString(e));
     return MRF_ERR_HIP;
@@ -111,6 +140,28 @@ inline void mark(hipEvent_t ev, hipStream_t st)
     if (g_ev_start && g_ev_stop) (void)hipEventRecord(ev, st);
 }
 
+// truncation distance that the forward pass rounds up to one of its window kernels, or 0
+inline int window_width(const mrf_problem *pr)
+{
+    if (g_tune_no_window || pr->pairwise_kind == MRF_PAIRWISE_DENSE) return 0;
+    double t = pr->trunc;
+    if (pr->pairwise_kind == MRF_PAIRWISE_TRUNC_QUADRATIC) t = sqrt(t);
+    if (!(t > 0.0) || t > 16.0) return 0;
+    int ti = (int)ceil(t);
+    if (ti < 1) ti = 1;
+    if (ti >= pr->L) return 0;
+    return ti <= 2 ? 2 : (ti <= 8 ? 8 : 16);
+}
+
+// the three parts
+hipError_t fill(float *dst, long long n, float v, hipStream_t st);
+int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                float *messages, void *workspace, size_t workspace_bytes, void *hip_stream);
+int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const uint8_t *p, const uint8_t *q,
+                 float *grad_unary, float *grad_w, float *grad_V, void *workspace, size_t workspace_bytes,
+                 void *hip_stream);
+
+#if MRF_HAS_FWD
 template <int LP, int MCH, int RMAX, int D>
 hipError_t launch_fwd(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
@@ -247,17 +298,6 @@ hipError_t launch_window_squad(const MrfFwdParams &P, int algo, int tw, int ni, 
 
 // Distance from which a truncated pairwise function is constant, or 0 if the window
 // kernel does not apply (dense kind, no truncation inside the label range, wide window).
-int window_width(const mrf_problem *pr)
-{
-    if (g_tune_no_window || pr->pairwise_kind == MRF_PAIRWISE_DENSE) return 0;
-    double t = pr->trunc;
-    if (pr->pairwise_kind == MRF_PAIRWISE_TRUNC_QUADRATIC) t = sqrt(t);
-    if (!(t > 0.0) || t > 16.0) return 0;
-    int ti = (int)ceil(t);
-    if (ti < 1) ti = 1;
-    if (ti >= pr->L) return 0;
-    return ti <= 2 ? 2 : (ti <= 8 ? 8 : 16);
-}
 
 template <int SEG, int MU>
 hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
@@ -499,6 +539,9 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     return MRF_OK;
 }
 
+#endif  // MRF_HAS_FWD
+
+#if MRF_HAS_BWD
 template <int LP, int NS, int D>
 hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
@@ -835,7 +878,12 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     return MRF_OK;
 }
 
-}  // namespace
+#endif  // MRF_HAS_BWD
+
+}  // namespace mrf_host
+
+#if MRF_HAS_API
+using namespace mrf_host;
 
 extern "C" {
 
@@ -1028,3 +1076,4 @@ int mrf_tune(int knob, int value)
 }
 
 }  // extern "C"
+#endif  // MRF_HAS_API
