@@ -695,3 +695,52 @@ def test_per_edge_tables_argument_errors():
     q = torch.zeros((1, 4, 1, 2, 2), dtype=torch.uint8, device=dev)
     with pytest.raises(mrf.MrfError):      # there are no edge weights to differentiate
         mrf.mrf_isgmr_backward(prob, z(1, 2, 2, L), p, q, z(1, 2, 2, L), z(4, 1, 2, 2), None, ws)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_drawn_medium_problems_forced_layouts(oracle, seed):
+    """Random problems whose scanlines are several times longer than the LDS rings of the
+    taken-apart layouts (20..69 nodes), with the kernel-choice knobs drawn at random."""
+    import paper_1910_10892_amd as mrf
+    from mrf_inputs import truncated_linear, truncated_quadratic, sgm_penalties
+    rng = np.random.default_rng(77000 + seed)
+    algo = ("isgmr", "trwp")[int(rng.integers(0, 2))]
+    B, H, W = int(rng.integers(1, 3)), int(rng.integers(20, 70)), int(rng.integers(20, 70))
+    L = int(rng.choice([5, 16, 21, 32, 40, 64, 96, 130, 192, 256]))
+    dirs = [DIRS4, DIRS8][int(rng.integers(0, 2))]
+    K = int(rng.integers(1, 3))
+    iv = bool(rng.integers(0, 2))
+    pr = random_problem(88000 + seed, algo, B, H, W, L, dirs, K, integer_valued=iv, per_edge=bool(rng.integers(0, 2)),
+                        rho=rng.uniform(0.2, 1.0, len(dirs)))
+    kind = int(rng.integers(0, 4))
+    if kind:
+        scale = 1.0 if iv else 0.41
+        if kind == 1:
+            trunc = float(rng.choice([2.0, 8.0, 16.0]))
+            pr.pairwise = truncated_linear(L, trunc, scale)
+        elif kind == 2:
+            trunc = float(rng.choice([4.0, 30.0, 200.0]))
+            pr.pairwise = truncated_quadratic(L, trunc, scale)
+        else:
+            trunc = 2.0
+            pr.pairwise = sgm_penalties(L, 0.5 if not iv else 1.0, 2.0)
+        pr.pairwise_kind, pr.trunc, pr.scale = kind, trunc, scale
+    want_V = bool(rng.integers(0, 2))
+    knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
+             5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8])),
+             8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3))}
+    print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
+    f = oracle_forward(oracle, pr, threads=True)
+    b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
+    big = max(float(np.abs(b.grad_unary).max()), float(np.abs(b.grad_pairwise).max()),
+              float(np.abs(b.grad_edge_weight).max()) if b.grad_edge_weight is not None else 0.0)
+    if big > 10.0:
+        pr.grad_cost = (pr.grad_cost * np.float32(10.0 / big)).astype(np.float32)
+    try:
+        for k, v in knobs.items():
+            assert mrf.mrf_tune(k, v) == 0
+        full_check(oracle, pr, threads=True, want_V=want_V)
+    finally:
+        for k in knobs:
+            mrf.mrf_tune(k, 0)
