@@ -223,7 +223,7 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 5: index wavefronts per scanline in that sweep: 0 = by launch size, 1, 2
  *   knob 6: backward sweep with the node-to-node chain on its own wavefront: 0 = by launch size,
  *           1 = never, 2 = whenever it applies (no grad_pairwise asked for)
- *   knob 7: helper wavefronts per scanline in that sweep: 0 = by launch size, 2, 4, 6, 8
+ *   knob 7: helper wavefronts per scanline in that sweep: 0 = by launch size, 2, 4, 6, 8, 12
  *   knob 9: where knob 2 picks one wavefront per 64 labels, those wavefronts compute values only and
  *           index wavefronts of their own do the argmin tables and the stores: 0 = by launch size,
  *           1 = never, 2 = always

@@ -613,7 +613,7 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
         else MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, false, false, false>); \
         return hipGetLastError(); \
     }
-    MRF_CH(2) MRF_CH(4) MRF_CH(6) MRF_CH(8)
+    MRF_CH(2) MRF_CH(4) MRF_CH(6) MRF_CH(8) MRF_CH(12)
 #undef MRF_CH
 #undef MRF_CH_GO
     return hipErrorInvalidValue;
@@ -668,12 +668,15 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     }
     const bool gv = P.gV != nullptr;
     // as many helpers as keep up with the chain while the machine and the LDS have room
+    // (measured per launch shape at L = 96: 256 scanlines 165 / 121 / 98 / 90 us with 4 / 6 / 8 / 12
+    // helpers; 512 scanlines, two workgroups per compute unit, 94 / 78 / 98 us with 4 / 6 / 8)
     int ni = g_tune_chain_ni ? g_tune_chain_ni
-                             : (P.total_scanlines <= 512 ? 8 : (P.total_scanlines <= 1024 ? 6 : 4));
+                             : (P.total_scanlines <= 256 ? 12
+                                : (P.total_scanlines <= 512 ? (LP >= 2 ? 6 : 8) : (P.total_scanlines <= 1024 ? 6 : 4)));
     if (!g_tune_chain_ni && gv && P.total_scanlines > 384 && ni > 6) ni = 6;   // (the accumulators take LDS)
     const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
     while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > chain_lds_cap(P.total_scanlines) ||
-                      (gv && P.total_scanlines * ni > grad_slots(L)))) ni -= 2;
+                      (gv && P.total_scanlines * ni > grad_slots(L)))) ni = (ni == 12) ? 8 : ni - 2;
     // TRW coefficients or pairwise tables per edge: mrf_bwd_sweep handles them (and is the one
     // sweep that never touches V when no edge-weight gradient is asked for)
     const bool generic = P.rho_e != nullptr || P.force_plain;
@@ -1071,7 +1074,7 @@ int mrf_tune(int knob, int value)
     if (knob == 9) { g_tune_squad = value; return MRF_OK; }
     if (knob == 11) { g_tune_pack_idx = value; return MRF_OK; }
     if (knob == 10) { g_tune_squad_ni = value; return MRF_OK; }
-    if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8) ? value : 0; return MRF_OK; }
+    if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }
 

@@ -77,7 +77,7 @@ struct MrfBwdParams {
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
-#define MRF_CHAIN_MAX_HELPERS 8
+#define MRF_CHAIN_MAX_HELPERS 12
 
 // dynamic LDS of mrf_bwd_sweep_chain (host and device agree through this one expression)
 __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L, bool with_theta, bool vg, bool gv)

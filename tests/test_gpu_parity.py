@@ -236,13 +236,13 @@ def test_chain_wavefront_backward_layout(oracle, case):
         assert mrf.mrf_tune(6, 1) == 0
         got[0] = full_check(oracle, pr, want_V=False)
         assert mrf.mrf_tune(6, 2) == 0
-        for ni in (2, 4, 6, 8):
+        for ni in (2, 4, 6, 8, 12):
             assert mrf.mrf_tune(7, ni) == 0
             got[ni] = full_check(oracle, pr, want_V=False)
     finally:
         mrf.mrf_tune(6, 0)
         mrf.mrf_tune(7, 0)
-    for ni in (2, 4, 6, 8):
+    for ni in (2, 4, 6, 8, 12):
         for name in ("grad_unary", "grad_edge_weight"):
             np.testing.assert_allclose(getattr(got[ni], name), getattr(got[0], name), rtol=1e-5, atol=1e-4,
                                        err_msg="%d helpers, %s" % (ni, name))
@@ -278,7 +278,7 @@ def test_chain_wavefront_backward_hot_label(oracle, case):
     try:
         assert mrf.mrf_tune(6, 2) == 0
         for hot in (1, 2):
-            for ni in (2, 8):
+            for ni in (2, 8, 12):
                 assert mrf.mrf_tune(12, hot) == 0 and mrf.mrf_tune(7, ni) == 0
                 got[hot, ni] = full_check(oracle, pr, want_V=False)
                 assert mrf.mrf_last_sweep_kernel(1) == "mrf_bwd_sweep_chain"
@@ -319,7 +319,7 @@ def test_chain_wavefront_backward_with_pairwise_gradient(oracle, case):
         got[0] = full_check(oracle, pr, want_V=True)
         assert mrf.mrf_last_sweep_kernel(1) == "mrf_bwd_sweep"
         assert mrf.mrf_tune(6, 2) == 0
-        for ni in (2, 4, 6, 8):
+        for ni in (2, 4, 6, 8, 12):
             assert mrf.mrf_tune(7, ni) == 0
             got[ni] = full_check(oracle, pr, want_V=True)
             assert mrf.mrf_last_sweep_kernel(1) == "mrf_bwd_sweep_chain"
@@ -327,7 +327,7 @@ def test_chain_wavefront_backward_with_pairwise_gradient(oracle, case):
         mrf.mrf_tune(3, 0)
         mrf.mrf_tune(6, 0)
         mrf.mrf_tune(7, 0)
-    for ni in (2, 4, 6, 8):
+    for ni in (2, 4, 6, 8, 12):
         for name in ("grad_unary", "grad_edge_weight", "grad_pairwise"):
             np.testing.assert_allclose(getattr(got[ni], name), getattr(got[0], name), rtol=1e-5, atol=1e-4,
                                        err_msg="%d helpers, %s" % (ni, name))
@@ -564,7 +564,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     pr, want_V = _drawn_problem(1000 + seed)
     rng = np.random.default_rng(9000 + seed)
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
-             5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8])),
+             5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
              11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
@@ -727,7 +727,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
         pr.pairwise_kind, pr.trunc, pr.scale = kind, trunc, scale
     want_V = bool(rng.integers(0, 2))
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
-             5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8])),
+             5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
              11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
