@@ -587,7 +587,7 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
     g_last_sweep[1] = "mrf_bwd_sweep_chain";
     const dim3 grid((unsigned)P.total_scanlines);
     const bool gv = P.gV != nullptr;
-    if (gv && (LP != 1 || P.g.L > 32 || P.total_scanlines * ni > grad_slots(P.g.L))) return hipErrorInvalidValue;
+    if (gv && (LP != 1 || P.total_scanlines * ni > grad_slots(P.g.L))) return hipErrorInvalidValue;
     const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg, gv);
     if (lds > chain_lds_cap(P.total_scanlines)) return hipErrorInvalidValue;
     // (more than 64 KB of dynamic LDS has to be announced per kernel)
@@ -659,7 +659,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         if (P.n_src[r] + (P.use_gc ? 1 : 0) > need) need = P.n_src[r] + (P.use_gc ? 1 : 0);
     const int ns = need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 8 ? 8 : 16));
     // few scanlines: the node-to-node chain on a wavefront of its own, helpers around it
-    // (its addressing wants a node step times L in 32 bits; with the V gradient, L <= 32 and
+    // (its addressing wants a node step times L in 32 bits; with the V gradient, L <= 64, room in LDS and
     // a slot per helper)
     bool step_fits = true;
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r) {
@@ -681,7 +681,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     // sweep that never touches V when no edge-weight gradient is asked for)
     const bool generic = P.rho_e != nullptr || P.force_plain;
     const bool chain_fits = !generic && step_fits && ns <= 8 && g_tune_chain != 1 &&
-                            (!gv || (L <= 32 && P.total_scanlines * ni <= grad_slots(L))) &&
+                            (!gv || (LP == 1 && P.total_scanlines * ni <= grad_slots(L))) &&
                             mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512));
     // few labels: several scanlines per wavefront, once there are enough of them

@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 // step late; with NI >= 2 no wait can depend on itself: post(t - 2 NI), which precedes
 // pre(t) in its helper, needs the chain to have passed step t - 2 NI + 1 only.
 //
-// GV (L <= 32): the launch also wants the V gradient; every helper keeps an accumulator of
+// GV (L <= 64, as far as LDS has room): the launch also wants the V gradient; every helper keeps an accumulator of
 // its own in LDS, lane lambda owning column lambda, and adds it to its own slot at the end.
 // HOT: truncated models send most labels to one source label, and the chain wavefront's LDS
 // adds would queue at that one word; the helpers guess it (as in mrf_bwd_sweep) and the chain

@@ -299,6 +299,8 @@ CHAIN_GV_CASES = [
     (93, "trwp", 1, 9, 4, 2, DIRS4, 3, False, False),
     (94, "trwp", 1, 1, 13, 17, DIRS8, 2, True, True),       # one row: most scanlines have one node
     (95, "isgmr", 3, 4, 7, 1, DIRS4, 2, False, True),
+    (96, "trwp", 1, 5, 30, 48, DIRS4, 2, False, True),      # more than 32 labels: fewer helpers fit
+    (97, "isgmr", 1, 4, 21, 64, DIRS4, 2, True, True),
 ]
 
 
