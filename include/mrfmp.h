@@ -22,7 +22,9 @@
  *    weight is never read and its edge-weight gradient is 0.
  *  - Ties in every argmin go to the lowest label.
  *  - Ownership: the caller owns every buffer, including the workspace; the library
- *    allocates no device memory and keeps no state between calls.  Outputs are fully
+ *    allocates no device memory and keeps no problem data between calls (the only state is
+ *    the process-global settings of mrf_tune, mrf_set_sweep_events and the two report
+ *    strings below).  Outputs are fully
  *    overwritten (gradients are assigned, not accumulated into what the caller passed).
  *  - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and return
  *    without synchronising.  Calls that share a workspace must be ordered by the caller.
@@ -222,16 +224,16 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           2 = whenever the window sweep applies (knob 2 = 2 takes precedence for L > 64)
  *   knob 5: index wavefronts per scanline in that sweep: 0 = by launch size, 1, 2
  *   knob 6: backward sweep with the node-to-node chain on its own wavefront: 0 = by launch size,
- *           1 = never, 2 = whenever it applies (no grad_pairwise asked for)
+ *           1 = never, 2 = whenever it applies (grad_pairwise only for L <= 64)
  *   knob 7: helper wavefronts per scanline in that sweep: 0 = by launch size, 2, 4, 6, 8, 12
+ *   knob 8: loader wavefront in front of the value wavefront (TRWP, window sweep, two index
+ *           wavefronts): 0 = by launch size, 1 = never, 2 = whenever it applies
  *   knob 9: where knob 2 picks one wavefront per 64 labels, those wavefronts compute values only and
  *           index wavefronts of their own do the argmin tables and the stores: 0 = by launch size,
  *           1 = never, 2 = always
  *   knob 10: index wavefronts per scanline in that layout: 0 = default, 4, 8
  *   knob 11: two index wavefronts next to the value wavefront in the sweep of knob 3: 0 = by launch size,
  *           1 = never, 2 = always
- *   knob 8: loader wavefront in front of the value wavefront (TRWP, window sweep, two index
- *           wavefronts): 0 = by launch size, 1 = never, 2 = whenever it applies
  *   knob 12: in the sweep of knob 6, sum the lanes of the most popular scatter target in registers
  *           (truncated models): 0 = by launch shape, 1 = never, 2 = whenever V is not a dense table
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
