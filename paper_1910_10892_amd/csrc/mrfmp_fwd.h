@@ -1055,6 +1055,27 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 
     if (LOADER) {
         // ---- values, fed by the loader -------------------------------------------------------
+        // With two labels per lane a lane holds two ADJACENT labels: its h pair is one 8-byte LDS
+        // write, the windows of both labels come out of the same 2 TW + 2 neighbours (TW 8-byte
+        // reads instead of 4 TW - 2 single ones), and a ring entry of the loader is one 8-byte read
+        // per vector.  The rings are indexed by label, so the other wavefronts keep their own mapping.
+        constexpr bool PAIR = LP == 2 && (TW % 2) == 0;
+        auto lab = [&](int s) { return PAIR ? 2 * lane + s : lane + 64 * s; };
+        auto read_entry = [&](float (&dst)[5][LP], int ls) {
+            if constexpr (PAIR) {
+#pragma unroll
+                for (int c = 0; c < 5; ++c) {
+                    const float2 t = *reinterpret_cast<const float2 *>(&lring[ls][c][2 * lane]);
+                    dst[c][0] = t.x;
+                    dst[c][LP - 1] = t.y;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 5; ++c)
+#pragma unroll
+                    for (int s = 0; s < LP; ++s) dst[c][s] = lring[ls][c][lane + 64 * s];
+            }
+        };
         float after[RMAX];                    // sources summed after the running message
 #pragma unroll
         for (int c = 1; c < RMAX; ++c) after[c] = ((c > n_pre && c <= n_src) ? 1.0f : 0.0f) + vz;
@@ -1072,10 +1093,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
         int lseen = 0;
         if (len >= 2) {
             lseen = await_loader(1);
-#pragma unroll
-            for (int c = 0; c < 5; ++c)
-#pragma unroll
-                for (int s = 0; s < LP; ++s) in[c][s] = lring[1][c][lane + 64 * s];
+            read_entry(in, 1);
             wgt = lw[1];
         }
         for (int nn = 1; nn < len; ++nn) {
@@ -1104,20 +1122,41 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(after[c], in[c][s], v);
                 v = rho * v;
                 v = v - in[4][s];
-                const int lam = lane + 64 * s;
+                const int lam = lab(s);
                 // (lanes past L rewrite the +inf their ring entries hold anyway: no divergence; what
                 // they carry from node to node is never looked at)
                 a[s] = lam < L ? v : INFINITY;
-                hbuf[lam] = a[s];
+                if (!PAIR) hbuf[lam] = a[s];
                 hm = s == 0 ? a[s] : mrf_min(hm, a[s]);
             }
+            if constexpr (PAIR) *reinterpret_cast<float2 *>(&hbuf[2 * lane]) = make_float2(a[0], a[LP - 1]);
             mrf_wave_lds_fence();
             float nb[LP][2 * TW - 1];
+            if constexpr (PAIR) {
+                // hn[k] = h(2 lane - TW + k), k = 0 .. 2 TW + 1; label 2 lane + s looks at hn[s + 1 ..]
+                float hn[2 * TW + 2];
 #pragma unroll
-            for (int s = 0; s < LP; ++s)
+                for (int j = 0; j <= TW; ++j) {
+                    if (j == TW / 2) {
+                        hn[2 * j] = a[0];
+                        hn[2 * j + 1] = a[LP - 1];
+                    } else {
+                        const float2 t = *reinterpret_cast<const float2 *>(&ring[slot][2 * lane + 2 * j]);
+                        hn[2 * j] = t.x;
+                        hn[2 * j + 1] = t.y;
+                    }
+                }
 #pragma unroll
-                for (int o = 0; o < 2 * TW - 1; ++o)
-                    nb[s][o] = (o == TW - 1) ? a[s] : hbuf[lane + 64 * s + o - (TW - 1)];
+                for (int s = 0; s < LP; ++s)
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o) nb[s][o] = hn[o + 1 + s];
+            } else {
+#pragma unroll
+                for (int s = 0; s < LP; ++s)
+#pragma unroll
+                    for (int o = 0; o < 2 * TW - 1; ++o)
+                        nb[s][o] = (o == TW - 1) ? a[s] : hbuf[lane + 64 * s + o - (TW - 1)];
+            }
             // the next node's entries, in the same batch of LDS reads; if the loader's counter
             // (read first: the LDS queue keeps the order) does not cover them yet, they are read
             // again after waiting
@@ -1126,10 +1165,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             const int flag = __hip_atomic_load(&loaded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             float nin[5][LP];
-#pragma unroll
-            for (int c = 0; c < 5; ++c)
-#pragma unroll
-                for (int s = 0; s < LP; ++s) nin[c][s] = lring[lsn][c][lane + 64 * s];
+            read_entry(nin, lsn);
             float nwgt = lw[lsn];
 
             const float hmin = mrf_wave_min(hm);
@@ -1146,10 +1182,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 lseen = __builtin_amdgcn_readfirstlane(flag);
                 if (lseen < nn + 1) {
                     lseen = await_loader(nn + 1);
-#pragma unroll
-                    for (int c = 0; c < 5; ++c)
-#pragma unroll
-                        for (int s = 0; s < LP; ++s) nin[c][s] = lring[lsn][c][lane + 64 * s];
+                    read_entry(nin, lsn);
                     nwgt = lw[lsn];
                 }
             }
@@ -1178,13 +1211,13 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 } else {
                     float mn = INFINITY;
 #pragma unroll
-                    for (int s = 0; s < LP; ++s) mn = fminf(mn, (lane + 64 * s < L) ? tv[s] : INFINITY);
+                    for (int s = 0; s < LP; ++s) mn = fminf(mn, (lab(s) < L) ? tv[s] : INFINITY);
                     tq = mrf_wave_min(mn);
                 }
             } else {
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
-                    const int lam = lane + 64 * s;
+                    const int lam = lab(s);
                     float best = INFINITY;
                     for (int mu = 0; mu < L; ++mu) {
                         int dist = mu > lam ? mu - lam : lam - mu;

@@ -171,6 +171,13 @@ WINDOW_CASES = [
     (53, "trwp", 1, 12, 40, DIRS8, 2, 1, 2.0, False, "pos"),       # one row: vertical and diagonal scanlines of one node
     (54, "trwp", 5, 6, 96, [(0, 1), (1, 0), (-1, 0)], 3, 1, 8.0, False, "pos"),   # a direction without its opposite
     (55, "isgmr", 6, 1, 33, DIRS4, 2, 1, 4.0, True, "zero_mix"),   # one column
+    # 65 .. 128 labels, TRWP: the loader-fed value wavefront holds two adjacent labels per lane
+    (56, "trwp", 4, 19, 65, DIRS4, 2, 1, 8.0, False, "pos"),       # one label in the second half of a pair
+    (57, "trwp", 5, 13, 75, DIRS4, 3, 1, 2.0, True, "zero_mix"),   # odd label count, narrowest window
+    (58, "trwp", 3, 21, 127, DIRS4, 2, 2, 200.0, False, "pos"),    # widest window, last lane half used
+    (59, "trwp", 4, 11, 128, DIRS4, 2, 1, 8.0, True, "neg_mix"),   # every lane full; negative weights
+    (60, "trwp", 6, 10, 100, [(0, 1), (0, -1), (1, 0)], 3, 2, 30.0, False, "pos"),
+    (61, "trwp", 2, 40, 97, DIRS4, 2, 1, 16.0, True, "pos"),
 ]
 
 
