@@ -550,7 +550,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     }
                     double hsum = 0.0;
                     if (HOT) hsum = mrf_wave_sum_f64(hpart);
-                    if (more && __builtin_amdgcn_readfirstlane(flag) < tt + 1) {
+                    if (__builtin_expect(more && __builtin_amdgcn_readfirstlane(flag) < tt + 1, 0)) {
                         await(un, tt + 1);
                         if (HOT) hotn = a_hot[slotn];
 #pragma unroll

@@ -643,7 +643,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
             int qidx = -1;
             float tq;
             // (the weight is wave-uniform: take the branch on a scalar copy of its sign)
-            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
                 // One reduction serves the whole node.  g is a non-decreasing function of h, so
                 // gmin = fma(w, fT, hmin).  If moreover f(0) = 0, every candidate is >= its h(mu)
                 // >= hmin and the candidate (lambda = mu = argmin h) equals hmin, so the minimum
@@ -680,7 +680,7 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                     const int tie = pW < mug ? pW : mug;
                     tp[s] = wlt ? pW : (wgt_ ? mug : tie);
                 }
-                if (f0zero) {
+                if (__builtin_expect(f0zero, 1)) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
@@ -866,7 +866,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             float tv[LP];
             int tp[LP];
             float tq;
-            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
                 int mug = 0;
                 bool found = false;
@@ -898,7 +898,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     const int tie = pW < mug ? pW : mug;
                     tp[s] = wlt ? pW : (wgt_ ? mug : tie);
                 }
-                if (f0zero) {
+                if (__builtin_expect(f0zero, 1)) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
@@ -1099,7 +1099,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
         for (int nn = 1; nn < len; ++nn) {
             const int slot = nn & (NR - 1);
             float *hbuf = &ring[slot][TW];
-            while (freed < nn - NR) {
+            while (__builtin_expect(freed < nn - NR, 0)) {
                 int lo = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
 #pragma unroll
@@ -1180,7 +1180,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (more) {
                 lseen = __builtin_amdgcn_readfirstlane(flag);
-                if (lseen < nn + 1) {
+                if (__builtin_expect(lseen < nn + 1, 0)) {
                     lseen = await_loader(nn + 1);
                     read_entry(nin, lsn);
                     nwgt = lw[lsn];
@@ -1189,7 +1189,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 
             float tv[LP];
             float tq;
-            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
@@ -1206,7 +1206,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
                     tv[s] = W;
                 }
-                if (f0zero) {
+                if (__builtin_expect(f0zero, 1)) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
@@ -1261,7 +1261,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 
             // the slot was last used by step nn - NR (steps past the end publish nothing
             // and write nothing)
-            while (!past && freed < nn - NR) {
+            while (__builtin_expect(!past && freed < nn - NR, 0)) {
                 int lo = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
 #pragma unroll
@@ -1326,7 +1326,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             // a past step re-reads the slot of an earlier step: its result is never used
             float tv[LP];
             float tq;
-            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
@@ -1343,7 +1343,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
                     tv[s] = W;
                 }
-                if (f0zero) {
+                if (__builtin_expect(f0zero, 1)) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
@@ -1714,7 +1714,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
             float tv[LPI];
             int tp[LPI];
             float tq;
-            if (__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0) {
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
                 int mug = 0;
                 bool found = false;
@@ -1746,7 +1746,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                     const int tie = pW < mug ? pW : mug;
                     tp[s] = wlt ? pW : (wgt_ ? mug : tie);
                 }
-                if (f0zero) {
+                if (__builtin_expect(f0zero, 1)) {
                     tq = hmin;
                 } else {
                     float mn = INFINITY;
@@ -1881,7 +1881,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
             float *hb = &ring[slot][TW];
 
             // the slot was last used by step nn - NR
-            while (!past && freed < nn - NR) {
+            while (__builtin_expect(!past && freed < nn - NR, 0)) {
                 int lo = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
 #pragma unroll
@@ -2204,7 +2204,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             const int slot = IDX ? (nn & (NR - 1)) : 0;
             if (IDX) {
                 // the slot was last used by step nn - NR
-                while (freed < nn - NR) {
+                while (__builtin_expect(freed < nn - NR, 0)) {
                     // the index wavefronts take the steps in turn: behind the slowest one's last
                     // step, the others have finished theirs
                     int lo = __builtin_amdgcn_readfirstlane(
