@@ -562,7 +562,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     // everything this wavefront sent to LDS before the reads above has landed
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
                     __builtin_amdgcn_wave_barrier();
-                    if (lane == 0 && tt > 0)
+                    // (written by every lane: the same word, and no exec-mask juggling in the step)
+                    if (tt > 0)
                         __hip_atomic_store(chain_done, tt - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {

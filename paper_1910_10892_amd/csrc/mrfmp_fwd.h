@@ -862,18 +862,27 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             const float wgt = ringw[slot];
             const float hmin = ringhm[slot];
             const long long i = head + (long long)n * nstep;
+            // the window's h in one batch of LDS reads behind the two words above (entries of labels
+            // >= L and the padding hold +inf, so no lane needs a condition)
+            float hv[LP][2 * TW - 1];
+#pragma unroll
+            for (int s = 0; s < LP; ++s)
+#pragma unroll
+                for (int o = 0; o < 2 * TW - 1; ++o) hv[s][o] = hbuf[lane + 64 * s + o - (TW - 1)];
 
             float tv[LP];
             int tp[LP];
             float tq;
-            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
+            // The window evaluation runs for every node, so that the usual case is straight-line
+            // code; for a negative weight its results are replaced below.
+            {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
                 int mug = 0;
                 bool found = false;
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
-                    const float gfar = lam < L ? __builtin_fmaf(wgt, fT, hbuf[lam]) : INFINITY;
+                    const float gfar = lam < L ? __builtin_fmaf(wgt, fT, hv[s][TW - 1]) : INFINITY;
                     const unsigned long long bal = __ballot(gfar == gmin);
                     if (!found && bal != 0ull) { found = true; mug = 64 * s + __ffsll((long long)bal) - 1; }
                 }
@@ -884,7 +893,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                     for (int o = 0; o < 2 * TW - 1; ++o) {
                         const int dist = o < TW - 1 ? TW - 1 - o : o - (TW - 1);
-                        dl[o] = __builtin_fmaf(wgt, f[dist], hbuf[lam + o - (TW - 1)]);
+                        dl[o] = __builtin_fmaf(wgt, f[dist], hv[s][o]);
                     }
                     float W = dl[0];
 #pragma unroll
@@ -906,7 +915,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
                     tq = mrf_wave_min(mn);
                 }
-            } else {
+            }
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) < 0, 0)) {
                 // negative weight: the ordering argument does not hold, evaluate every mu
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
@@ -940,7 +950,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
             for (int s = 0; s < LP; ++s) {
                 const int lam = lane + 64 * s;
-                if (lam < L) {
+                if (__builtin_expect(lam < L, 1)) {
                     P.m_out[((size_t)r * N + i) * L + lam] = tv[s] - tq;
                     P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
                 }
@@ -1172,24 +1182,17 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             // LDS executes a wavefront's operations in order: whoever sees the counter also sees the
             // node's ring entries written before it, so no wait is needed in between
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            if (lane == 0) {
-                ringw[slot] = wgt;
-                ringhm[slot] = hmin;
-                __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
+            // (every lane writes the same three words: no divergent branch in the node step)
+            ringw[slot] = wgt;
+            ringhm[slot] = hmin;
+            __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (more) {
-                lseen = __builtin_amdgcn_readfirstlane(flag);
-                if (__builtin_expect(lseen < nn + 1, 0)) {
-                    lseen = await_loader(nn + 1);
-                    read_entry(nin, lsn);
-                    nwgt = lw[lsn];
-                }
-            }
 
             float tv[LP];
             float tq;
-            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
+            // (evaluated for every node, so that the usual case is straight-line code; replaced
+            // below for a negative weight)
+            {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
@@ -1214,7 +1217,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     for (int s = 0; s < LP; ++s) mn = fminf(mn, (lab(s) < L) ? tv[s] : INFINITY);
                     tq = mrf_wave_min(mn);
                 }
-            } else {
+            }
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) < 0, 0)) {
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lab(s);
@@ -1231,6 +1235,16 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 #pragma unroll
                 for (int s = 0; s < LP; ++s) mn = fminf(mn, tv[s]);
                 tq = mrf_wave_min(mn);
+            }
+            // the next node's entries were read above with the loader's counter in front of them;
+            // looked at only now, so that everything before is one straight block
+            if (more) {
+                lseen = __builtin_amdgcn_readfirstlane(flag);
+                if (__builtin_expect(lseen < nn + 1, 0)) {
+                    lseen = await_loader(nn + 1);
+                    read_entry(nin, lsn);
+                    nwgt = lw[lsn];
+                }
             }
 #pragma unroll
             for (int s = 0; s < LP; ++s) carry[s] = tv[s] - tq;
@@ -1316,7 +1330,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             // LDS executes a wavefront's operations in order: whoever sees the counter also sees the
             // node's ring entries written before it, so no wait is needed in between
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            if (lane == 0 && !past) {
+            // (every lane writes the same three words: no divergent branch in the node step)
+            if (!past) {
                 ringw[slot] = wgt;
                 ringhm[slot] = hmin;
                 __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1326,7 +1341,9 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             // a past step re-reads the slot of an earlier step: its result is never used
             float tv[LP];
             float tq;
-            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0, 1)) {
+            // (evaluated for every node, so that the usual case is straight-line code; replaced
+            // below for a negative weight)
+            {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
@@ -1351,7 +1368,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     for (int s = 0; s < LP; ++s) mn = fminf(mn, (lane + 64 * s < L) ? tv[s] : INFINITY);
                     tq = mrf_wave_min(mn);
                 }
-            } else {
+            }
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane(__float_as_int(wgt)) < 0, 0)) {
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
                     const int lam = lane + 64 * s;
