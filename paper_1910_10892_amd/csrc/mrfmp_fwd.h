@@ -849,6 +849,12 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             if (lane == 0) P.q[(size_t)r * N + head] = 0;
         }
 
+        // stores relative to the head of the scanline (the host has checked that a node step
+        // times L fits 32 bits)
+        float *const mrow = P.m_out + ((size_t)r * N + head) * L;
+        uint8_t *const prow = P.p + ((size_t)r * N + head) * L;
+        uint8_t *const qrow = P.q + (size_t)r * N + head;
+        const int istep_l = (int)nstep * L;
         int seen = 0;
         for (int n = 1 + jw; n < len; n += NI) {
             while (seen < n) {
@@ -861,7 +867,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             const float *hbuf = &ring[slot][TW];
             const float wgt = ringw[slot];
             const float hmin = ringhm[slot];
-            const long long i = head + (long long)n * nstep;
+            const long long ol = (long long)n * istep_l;
             // the window's h in one batch of LDS reads behind the two words above (entries of labels
             // >= L and the padding hold +inf, so no lane needs a condition)
             float hv[LP][2 * TW - 1];
@@ -951,11 +957,11 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
             for (int s = 0; s < LP; ++s) {
                 const int lam = lane + 64 * s;
                 if (__builtin_expect(lam < L, 1)) {
-                    P.m_out[((size_t)r * N + i) * L + lam] = tv[s] - tq;
-                    P.p[((size_t)r * N + i) * L + lam] = (uint8_t)tp[s];
+                    mrow[ol + lam] = tv[s] - tq;
+                    prow[ol + lam] = (uint8_t)tp[s];
                 }
             }
-            if (lane == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+            if (lane == 0) qrow[(long long)n * nstep] = (uint8_t)qidx;
         }
         return;
     }
