@@ -1941,15 +1941,18 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
             const float av = valid ? v : INFINITY;
             if (!past) hb[lam] = av;
             const float hloc = mrf_wave_min(av);
-            if (threadIdx.x == 0 && !past) ringw[slot] = wgt;
+            // (written by every lane of the first value wavefront: no divergent branch in the step)
+            if (wv == 0 && !past) ringw[slot] = wgt;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             const float hmin = exchange_min(hmx, par, nn, hloc);
             // every entry of the node is in the ring: let the index wavefronts have it
-            if (threadIdx.x == 0 && !past)
+            if (wv == 0 && !past)
                 __hip_atomic_store(&produced, nn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             const bool wpos = __builtin_amdgcn_readfirstlane(__float_as_int(wgt)) >= 0;
             float tv;
-            if (wpos) {
+            // (evaluated for every node, so that the usual case is straight-line code; replaced
+            // below for a negative weight)
+            {
                 const float gmin = __builtin_fmaf(wgt, fT, hmin);
                 // The two candidates at distance d share f(d), and a correctly rounded fma is
                 // non-decreasing in its addend: the smaller of the two comes from the smaller h.
@@ -1963,7 +1966,8 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                 for (int d = 1; d + 1 < TW; d += 2) W = mrf_min3(W, dl[d], dl[d + 1]);
                 if ((TW & 1) == 0) W = mrf_min(W, dl[TW - 1]);
                 tv = W;
-            } else {
+            }
+            if (__builtin_expect(!wpos, 0)) {
                 float best = INFINITY;
                 for (int mu = 0; mu < L; ++mu) {
                     int dist = mu > lam ? mu - lam : lam - mu;
@@ -1974,7 +1978,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                 tv = best;
             }
             float tq = hmin;
-            if (!(wpos && f0zero)) {
+            if (__builtin_expect(!(wpos && f0zero), 0)) {
                 // general case: the minimum of the new message needs its own exchange
                 const float tloc = mrf_wave_min(valid ? tv : INFINITY);
                 tq = exchange_min(tmx, par, nn, tloc);
