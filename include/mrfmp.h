@@ -55,7 +55,7 @@ typedef enum {
     MRF_ERR_BAD_ITERATIONS = -4,    /* K < 1 */
     MRF_ERR_BAD_DIRECTIONS = -5,    /* R outside [1, 16], a zero step, or a repeated direction */
     MRF_ERR_WORKSPACE_TOO_SMALL = -6,
-    MRF_ERR_BAD_PAIRWISE_KIND = -7, /* unknown pairwise_kind, or trunc/scale invalid for it */
+    MRF_ERR_BAD_PAIRWISE_KIND = -7, /* unknown pairwise_kind, trunc <= 0 for kinds 1-3, or scale < 0 for kinds 1, 2 */
     MRF_ERR_BAD_ALGORITHM = -8,     /* algo argument is neither MRF_ISGMR nor MRF_TRWP */
     MRF_ERR_HIP = -9                /* a HIP runtime call or kernel launch failed */
 } mrf_status;
@@ -113,10 +113,13 @@ size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward);
 /* Checks a problem description the way the entry points do; no GPU work. */
 int mrf_validate(const mrf_problem *prob, int algo);
 
-/* Which forward kernel the problem's pairwise_kind selects: 0 = the dense O(L^2) sweep,
- * w > 0 = the window sweep that evaluates 2w - 1 source labels per label (truncated models
- * whose truncation distance is at most 16 and below L).  Results are identical either way.
- * Negative mrf_status for an invalid problem.  Host arithmetic. */
+/* Which forward kernel the sweeps of the second and later iterations get: 0 = the dense O(L^2)
+ * sweep, w > 0 = the window sweep that evaluates 2w - 1 source labels per label (truncated models
+ * whose truncation distance is at most 16 and below L, and whose update reads at most seven message
+ * arrays: up to 9 directions in opposite pairs for ISGMR, 8 for TRWP).  The choice is made per
+ * launch: where this returns 0 for a truncated model, the early TRWP launches of the first
+ * iteration, which read fewer arrays, may still take the window sweep.  Results are identical
+ * either way.  Negative mrf_status for an invalid problem.  Host arithmetic. */
 int mrf_forward_window(const mrf_problem *prob, int algo);
 
 /* Forward propagation of ISGMR (Alg. 1; update Eq. isgmr, reparametrisation
@@ -165,7 +168,9 @@ int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
  *   energy[b] = sum_i theta_i(x_i) + sum over edges (i-r, i) of theta_{i-r,i} V(x_{i-r}, x_i)
  * for every batch image b.  The edge set holds every undirected neighbour pair once: the
  * edges of the first direction of each opposite pair in prob->dirs (and of every direction
- * without an opposite), with that direction's weights.  prob->K and prob->rho are not used.
+ * without an opposite), with that direction's weights -- or, where prob->pairwise_edge is
+ * given, with that direction's tables theta_{i-r,i}(x_{i-r}, x_i) (prob->pairwise may then be
+ * NULL).  prob->K and prob->rho are not used.
  *   labels   DEVICE [B][H][W] uint8 (values >= L are read as L-1)
  *   energy   DEVICE [B] double, assigned
  *   workspace DEVICE, at least mrf_energy_workspace_bytes(prob), 256-byte aligned

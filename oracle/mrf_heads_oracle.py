@@ -30,11 +30,13 @@ def energy_directions(dirs):
     return keep
 
 
-def energy(unary, pairwise, dirs, labels, edge_weight=None, edge_weight_scalar=1.0):
+def energy(unary, pairwise, dirs, labels, edge_weight=None, edge_weight_scalar=1.0, pairwise_edge=None):
     """E(x | Theta) per batch image, float64 [B].  unary [B,H,W,L], pairwise V[mu at i-r][lambda
-    at i], labels [B,H,W] integer, edge_weight [R,B,H,W] stored at the destination node i."""
+    at i], labels [B,H,W] integer, edge_weight [R,B,H,W] stored at the destination node i.
+    pairwise_edge [R,B,H,W,L,L], if given, holds theta_{i-r,i}(mu,lambda) per edge (stored at the
+    destination node i like the weights) and takes the place of edge_weight * pairwise."""
     unary = np.asarray(unary, np.float64)
-    V = np.asarray(pairwise, np.float64)
+    V = None if pairwise is None else np.asarray(pairwise, np.float64)
     x = np.asarray(labels).astype(np.int64)
     B, H, W, _ = unary.shape
     dirs = np.asarray(dirs).reshape(-1, 2)
@@ -50,6 +52,9 @@ def energy(unary, pairwise, dirs, labels, edge_weight=None, edge_weight_scalar=1
                 for xx in range(W):
                     ys, xs = y - dh, xx - dw
                     if 0 <= ys < H and 0 <= xs < W:
+                        if pairwise_edge is not None:
+                            e += float(pairwise_edge[r, b, y, xx, x[b, ys, xs], x[b, y, xx]])
+                            continue
                         w = float(edge_weight[r, b, y, xx]) if edge_weight is not None else float(edge_weight_scalar)
                         e += w * V[x[b, ys, xs], x[b, y, xx]]
         out[b] = e

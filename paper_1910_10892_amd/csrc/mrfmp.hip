@@ -67,6 +67,9 @@ inline int check_problem(const mrf_problem *pr, int algo, bool forward)
         pr->pairwise_kind != MRF_PAIRWISE_TRUNC_QUADRATIC && pr->pairwise_kind != MRF_PAIRWISE_DISTANCE)
         return MRF_ERR_BAD_PAIRWISE_KIND;
     if (pr->pairwise_kind != MRF_PAIRWISE_DENSE && !(pr->trunc > 0.0f)) return MRF_ERR_BAD_PAIRWISE_KIND;
+    // the window sweeps need V non-decreasing in the label distance: a negative scale turns it round
+    if ((pr->pairwise_kind == MRF_PAIRWISE_TRUNC_LINEAR || pr->pairwise_kind == MRF_PAIRWISE_TRUNC_QUADRATIC) &&
+        !(pr->scale >= 0.0f)) return MRF_ERR_BAD_PAIRWISE_KIND;
     return MRF_OK;
 }
 
@@ -903,7 +906,17 @@ int mrf_forward_window(const mrf_problem *prob, int algo)
 {
     const int rc = check_problem(prob, algo, false);
     if (rc != MRF_OK) return rc;
-    if (prob->R > 8) return 0;
+    // the window sweeps take up to seven message arrays next to the unary (as dispatch_fwd decides per
+    // launch); count what a launch of the later iterations reads
+    int most = 0;
+    for (int r = 0; r < prob->R; ++r) {
+        bool has_opp = false;
+        for (int d = 0; d < prob->R; ++d)
+            if (prob->dirs[2 * d] == -prob->dirs[2 * r] && prob->dirs[2 * d + 1] == -prob->dirs[2 * r + 1]) has_opp = true;
+        const int n = prob->R - 1 - ((algo == MRF_ISGMR && has_opp) ? 1 : 0);
+        if (n > most) most = n;
+    }
+    if (most + 1 > 8) return 0;
     return window_width(prob);
 }
 
@@ -965,7 +978,7 @@ const char *mrf_strerror(int status)
     case MRF_ERR_BAD_ITERATIONS: return "K must be >= 1";
     case MRF_ERR_BAD_DIRECTIONS: return "R must be in [1, 16], steps non-zero and distinct";
     case MRF_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than mrf_workspace_bytes()";
-    case MRF_ERR_BAD_PAIRWISE_KIND: return "unknown pairwise_kind or invalid trunc";
+    case MRF_ERR_BAD_PAIRWISE_KIND: return "unknown pairwise_kind, invalid trunc or negative scale";
     case MRF_ERR_BAD_ALGORITHM: return "algo must be MRF_ISGMR or MRF_TRWP";
     case MRF_ERR_HIP: return "HIP runtime call or kernel launch failed";
     default: return "unknown status";
@@ -978,19 +991,15 @@ size_t mrf_energy_workspace_bytes(const mrf_problem *prob)
     return sizeof(double) * (size_t)prob->B * MRF_HEAD_BLOCKS;
 }
 
-int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, void *workspace,
-               size_t workspace_bytes, void *hip_stream)
+// launches of mrf_energy on `partial`, which holds B * MRF_HEAD_BLOCKS doubles
+static int energy_launch(const mrf_problem *prob, const uint8_t *labels, double *energy, double *partial,
+                         hipStream_t st)
 {
-    const int rc = check_problem(prob, MRF_ISGMR, true);
-    if (rc != MRF_OK) return rc;
-    if (!labels || !energy || !workspace) return MRF_ERR_NULL_POINTER;
-    if (workspace_bytes < mrf_energy_workspace_bytes(prob)) return MRF_ERR_WORKSPACE_TOO_SMALL;
-    hipStream_t st = (hipStream_t)hip_stream;
     MrfEnergyParams E;
     memset(&E, 0, sizeof(E));
     fill_geom(prob, E.g);
-    E.unary = prob->unary; E.V = prob->pairwise; E.labels = labels;
-    E.partial = (double *)workspace;
+    E.unary = prob->unary; E.V = prob->pairwise; E.Te = prob->pairwise_edge; E.labels = labels;
+    E.partial = partial;
     if (prob->edge_weight) { E.w = prob->edge_weight; E.w_mul = 1; }
     else { E.w = nullptr; E.w_mul = 0; }
     for (int r = 0; r < prob->R; ++r)
@@ -1005,6 +1014,16 @@ int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, v
                        energy, (const long long *)nullptr);
     { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "mrf_sum_partials"); }
     return MRF_OK;
+}
+
+int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, void *workspace,
+               size_t workspace_bytes, void *hip_stream)
+{
+    const int rc = check_problem(prob, MRF_ISGMR, true);
+    if (rc != MRF_OK) return rc;
+    if (!labels || !energy || !workspace) return MRF_ERR_NULL_POINTER;
+    if (workspace_bytes < mrf_energy_workspace_bytes(prob)) return MRF_ERR_WORKSPACE_TOO_SMALL;
+    return energy_launch(prob, labels, energy, (double *)workspace, (hipStream_t)hip_stream);
 }
 
 size_t mrf_softmin_l1_workspace_bytes(void)

@@ -18,8 +18,9 @@ struct MrfGeom {
     long long N;            // B*H*W nodes
 };
 
-// Scanlines of direction (dh,dw) are the maximal in-grid chains i, i+r, i+2r, ...
-// ("each tree is headed by its first node", Sec. 3.5).  First nodes are the nodes whose
+// Scanlines of direction (dh,dw) are the maximal in-grid chains i, i+r, i+2r, ...; each is one
+// tree of the tree parallelisation and starts at its first node (Sec. 3.5, Appendix C).
+// First nodes are the nodes whose
 // predecessor is off the grid: the |dh| boundary rows on the side the sweep starts from,
 // then |dw| boundary columns in every other row.  For |dh| = 1 the count is
 // W + (H-1)|dw| (Eq. supp-wide).

@@ -17,6 +17,7 @@ struct MrfEnergyParams {
     MrfGeom g;
     const float *unary;      // [B][H][W][L]
     const float *V;          // [L][L], V[x at i-r][x at i]
+    const float *Te;         // [R][N][L][L] pairwise potentials per edge, or NULL: then w * V applies
     const float *w;          // [R][N], or NULL with w_mul == 0: w_scalar for every edge
     int w_mul;
     float w_scalar;
@@ -60,8 +61,13 @@ __global__ void __launch_bounds__(256) mrf_energy_partial(const MrfEnergyParams 
             if (ys >= 0 && ys < H && xs >= 0 && xs < W) {
                 int xj = P.labels[(long long)b * HW + (long long)ys * W + xs];
                 xj = xj < L ? xj : L - 1;
-                const float wgt = P.w_mul ? P.w[(size_t)r * P.g.N + i] : P.w_scalar;
-                acc += (double)wgt * (double)P.V[(size_t)xj * L + xi];
+                if (P.Te) {
+                    // the edge's own table theta_{i-r,i}(x_{i-r}, x_i)
+                    acc += (double)P.Te[(((size_t)r * P.g.N + i) * L + xj) * L + xi];
+                } else {
+                    const float wgt = P.w_mul ? P.w[(size_t)r * P.g.N + i] : P.w_scalar;
+                    acc += (double)wgt * (double)P.V[(size_t)xj * L + xi];
+                }
             }
         }
     }

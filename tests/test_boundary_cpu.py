@@ -68,6 +68,11 @@ def test_validation_codes_without_gpu():
     assert V(_cprob(rho=None, rho_edge=0x1000), 1) == 0      # per-edge coefficients stand in for rho[]
     assert V(_cprob(pairwise_kind=9)) == -7
     assert V(_cprob(pairwise_kind=1, trunc=0.0)) == -7
+    # kinds 1 and 2 promise a non-decreasing function of the label distance: no negative scale
+    assert V(_cprob(pairwise_kind=1, trunc=2.0, scale=-1.0)) == -7
+    assert V(_cprob(pairwise_kind=2, trunc=2.0, scale=float("nan"))) == -7
+    assert V(_cprob(pairwise_kind=1, trunc=2.0, scale=0.0)) == 0
+    assert V(_cprob(pairwise_kind=3, trunc=2.0, scale=-1.0)) == 0     # kind 3 does not use scale
     assert lib.mrf_validate(None, 0) == -1
     for code in range(0, -10, -1):
         assert mrf.mrf_strerror(code) != "unknown status"
@@ -88,6 +93,13 @@ def test_forward_kernel_choice_is_host_arithmetic():
     assert W(L=64, pairwise_kind=3, trunc=5.0) == 8
     assert W(L=64, pairwise_kind=4, trunc=2.0) == -7          # unknown kind
     assert W(L=0, pairwise_kind=1, trunc=4.0) == -3
+    # the window sweeps take at most seven message arrays per update
+    d8 = [(0, 1), (0, -1), (1, 0), (-1, 0), (1, 1), (-1, -1), (1, -1), (-1, 1)]
+    d10 = d8 + [(1, 2), (-1, -2)]
+    T = lambda dirs, algo: lib.mrf_forward_window(ctypes.byref(_cprob(dirs=dirs, L=96, pairwise_kind=1, trunc=8.0)), algo)
+    assert T(d8, 0) == 8 and T(d8, 1) == 8
+    assert T(d8 + [(1, 2)], 0) == 0          # ISGMR: the direction without an opposite reads 8 arrays
+    assert T(d10, 0) == 0 and T(d10, 1) == 0
 
 
 def test_entry_points_reject_before_any_gpu_work():

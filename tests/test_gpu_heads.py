@@ -35,6 +35,29 @@ def test_energy_matches_oracle(case):
     np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-12, atol=1e-9)
 
 
+@pytest.mark.parametrize("case", [(11, 2, 5, 7, 9, DIRS4), (12, 1, 6, 4, 21, DIRS8), (13, 1, 3, 5, 64, [(0, 1), (1, 0), (-1, 0)])],
+                         ids=lambda c: "seed%d" % c[0])
+def test_energy_with_pairwise_potentials_per_edge(case):
+    """Problems that give one table per edge (and no V): the energy reads theta_{i-r,i}(x_{i-r}, x_i)
+    from the edge's table."""
+    import torch
+    import paper_1910_10892_amd as mrf
+    from oracle import mrf_heads_oracle as ho
+    seed, B, H, W, L, dirs = case
+    print("case energy, per-edge tables", case[:5], flush=True)
+    pr = random_problem(seed, "isgmr", B, H, W, L, dirs, 1, per_edge=False)
+    rng = np.random.default_rng(seed + 600)
+    pr.pairwise_edge = rng.random((len(dirs), B, H, W, L, L)).astype(np.float32)
+    lab = rng.integers(0, L, (B, H, W)).astype(np.uint8)
+    g = _gpu_problem(pr)
+    assert g.prob.pairwise is None
+    ws = torch.empty(mrf.mrf_energy_workspace_bytes(g.prob), dtype=torch.uint8, device="cuda:0")
+    out = torch.full((B,), float("nan"), dtype=torch.float64, device="cuda:0")
+    mrf.mrf_energy(g.prob, torch.from_numpy(lab).cuda(), out, ws)
+    ref = ho.energy(pr.unary, None, pr.dirs, lab, pairwise_edge=pr.pairwise_edge)
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-12, atol=1e-9)
+
+
 def test_energy_of_the_labelling_the_sweeps_return():
     """Forward pass, then the energy of its labels, on the stereo recipe (cropped)."""
     import torch

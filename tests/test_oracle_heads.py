@@ -44,6 +44,41 @@ def test_energy_matches_enumeration_over_explicit_edges(H, W, L, dirs):
         np.testing.assert_allclose(got[0], E[k], rtol=1e-13, atol=1e-13)
 
 
+@pytest.mark.parametrize("H,W,L,dirs", [(2, 3, 3, DIRS4), (2, 2, 2, DIRS8), (3, 1, 3, [(1, 0), (0, 1)])])
+def test_energy_with_one_table_per_edge_matches_enumeration(H, W, L, dirs):
+    """Pairwise potentials given per edge: every edge of the explicit list carries its own table."""
+    rng = np.random.default_rng(70 + H * 10 + W)
+    unary = rng.random((1, H, W, L))
+    Te = rng.random((len(dirs), 1, H, W, L, L))
+    ones = np.ones((len(dirs), 1, H, W))
+    edges = [(a, b) for a, b, _, _ in explicit_edges(H, W, dirs, ones, None)]
+    # the table of edge (a, b) lives at the destination node b, under the direction that produced the edge
+    d = [tuple(v) for v in dirs]
+    table = {}
+    seen = set()
+    for r, (dh, dw) in enumerate(d):
+        if (-dh, -dw) in seen:
+            continue
+        seen.add((dh, dw))
+        for y in range(H):
+            for x in range(W):
+                ys, xs = y - dh, x - dw
+                if 0 <= ys < H and 0 <= xs < W:
+                    table[(ys * W + xs, y * W + x)] = Te[r, 0, y, x]
+    assert sorted(table) == sorted(edges)
+    X = all_labelings(H * W, L)
+    E = energies(X, unary.reshape(H * W, L), [(a, b, 1.0, table[(a, b)]) for a, b in edges])
+    for k in range(0, X.shape[0], max(1, X.shape[0] // 40)):
+        got = ho.energy(unary, None, np.array(dirs), X[k].reshape(1, H, W), pairwise_edge=Te)
+        np.testing.assert_allclose(got[0], E[k], rtol=1e-13, atol=1e-13)
+    # tables that repeat weight times V give the energy of the weighted form
+    V = rng.random((L, L))
+    w = rng.uniform(0.5, 1.5, (len(dirs), 1, H, W))
+    lab = X[X.shape[0] // 3].reshape(1, H, W)
+    np.testing.assert_allclose(ho.energy(unary, None, np.array(dirs), lab, pairwise_edge=w[..., None, None] * V),
+                               ho.energy(unary, V, np.array(dirs), lab, edge_weight=w), rtol=1e-13)
+
+
 def test_energy_scalar_weight_and_batch_independence():
     rng = np.random.default_rng(3)
     unary = rng.random((2, 3, 3, 4))
