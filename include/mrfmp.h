@@ -212,6 +212,12 @@ const char *mrf_last_error_detail(void);
  * of the sweep layouts the launch-size rules picked.  For reports; process-global. */
 const char *mrf_last_sweep_kernel(int backward);
 
+/* The same launch in full: "name<template arguments> grid=G block=T", e.g.
+ * "mrf_fwd_sweep_window<3,8,1,false,2> grid=9788 block=64" -- the instantiation a profiler
+ * lists and the launch shape.  For reports and for tests that pin which instantiation a
+ * benchmark shape gets; process-global, the library owns the string. */
+const char *mrf_last_sweep_launch(int backward);
+
 /* Profiling hook: while set (both non-NULL hipEvent_t handles), every forward or backward
  * call records `start_event` on its stream just before its first scanline-sweep launch and
  * `stop_event` just after its last one, so a caller can time the sweeps apart from the

@@ -25,6 +25,7 @@
 #endif
 
 #include <math.h>
+#include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
 
@@ -126,10 +127,26 @@ MRF_G(hipEvent_t g_ev_stop, nullptr);
 #if MRF_HAS_API
 char g_error_detail[256] = "";
 const char *g_last_sweep[2] = {"", ""};      // kernel of the last forward / backward sweep launch
+char g_last_launch[2][160] = {"", ""};       // the same with template arguments and launch shape
 #else
 extern char g_error_detail[256];
 extern const char *g_last_sweep[2];
+extern char g_last_launch[2][160];
 #endif
+
+// records the kernel of a sweep launch: its name, and "name<template arguments> grid=.. block=.."
+inline void note_launch(int backward, const char *name, long long grid, int block, const char *fmt, ...)
+    __attribute__((format(printf, 5, 6)));
+inline void note_launch(int backward, const char *name, long long grid, int block, const char *fmt, ...)
+{
+    g_last_sweep[backward] = name;
+    char args[96];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(args, sizeof(args), fmt, ap);
+    va_end(ap);
+    snprintf(g_last_launch[backward], sizeof(g_last_launch[backward]), "%s<%s> grid=%lld block=%d", name, args, grid, block);
+}
 
 // records which call failed and how, for mrf_last_error_detail
 inline int hip_fail(hipError_t e, const char *what)
@@ -168,7 +185,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
 template <int LP, int MCH, int RMAX, int D>
 hipError_t launch_fwd(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep";
+    note_launch(0, "mrf_fwd_sweep", blocks, 64 * P.NW, "%d,%d,%d,%d,%s", LP, MCH, RMAX, D, algo == MRF_TRWP ? "true" : "false");
     constexpr int NWMAX = (64 * LP + MCH - 1) / MCH;
     const size_t lds = (size_t)NWMAX * NWMAX * MCH * sizeof(float) +
                        (NWMAX > 1 ? (size_t)2 * NWMAX * 64 * LP * sizeof(float2) : 0);
@@ -201,12 +218,12 @@ int pick_mch(int L, int LP, bool many_sources)
 // (rounded up to a multiple of four)
 hipError_t launch_edge(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_edge";
     int ms = 0;
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
         if (P.n_src[r] > ms) ms = P.n_src[r];
     const int rmax = (ms + 1 <= 4) ? 4 : ((ms + 1 <= 8) ? 8 : 16);
     const int L = P.g.L;
+    note_launch(0, "mrf_fwd_sweep_edge", blocks, 64, "%d,%d,%s", (L + 7) / 8 * 4, rmax, algo == MRF_TRWP ? "true" : "false");
     if (L > 64) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(64);
 #define MRF_E(half, rm) \
@@ -225,7 +242,7 @@ hipError_t launch_edge(const MrfFwdParams &P, int algo, long long blocks, hipStr
 template <int LP, int RMAX, int D>
 hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_window";
+    note_launch(0, "mrf_fwd_sweep_window", blocks, 64, "%d,%d,%d,%s,%d", LP, RMAX, D, algo == MRF_TRWP ? "true" : "false", tw);
 #define MRF_W(twv) \
     if (tw == twv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, true, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
@@ -240,7 +257,8 @@ hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long bloc
 template <int LP, int RMAX, int D, int NI>
 hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_window_duo";
+    note_launch(0, "mrf_fwd_sweep_window_duo", blocks, 64 * (1 + NI), "%d,%d,%d,%s,%d,%d,false", LP, RMAX, D,
+                algo == MRF_TRWP ? "true" : "false", tw, NI);
 #define MRF_W(twv) \
     if (tw == twv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, true, twv, NI, false>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
@@ -256,7 +274,7 @@ hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long 
 template <int LP>
 hipError_t launch_window_loader(const MrfFwdParams &P, int tw, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_window_duo";
+    note_launch(0, "mrf_fwd_sweep_window_duo", blocks, 256, "%d,4,%d,true,%d,2,true", LP, (LP <= 2 ? 4 : 2), tw);
 #define MRF_W(twv) \
     if (tw == twv) { \
         hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, 4, (LP <= 2 ? 4 : 2), true, twv, 2, true>), dim3((unsigned)blocks), dim3(256), 0, st, P); \
@@ -270,8 +288,8 @@ hipError_t launch_window_loader(const MrfFwdParams &P, int tw, long long blocks,
 template <int RMAX, int D>
 hipError_t launch_window_split(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_window_split";
     const unsigned threads = 64u * (unsigned)((P.g.L + 63) / 64);
+    note_launch(0, "mrf_fwd_sweep_window_split", blocks, (int)threads, "%d,%d,%s,%d", RMAX, D, algo == MRF_TRWP ? "true" : "false", tw);
 #define MRF_W(twv) \
     if (tw == twv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_split<RMAX, D, true, twv>), dim3((unsigned)blocks), dim3(threads), 0, st, P); \
@@ -286,8 +304,9 @@ hipError_t launch_window_split(const MrfFwdParams &P, int algo, int tw, long lon
 template <int RMAX, int D>
 hipError_t launch_window_squad(const MrfFwdParams &P, int algo, int tw, int ni, long long blocks, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_window_squad";
     const unsigned nwv = (unsigned)((P.g.L + 63) / 64);
+    note_launch(0, "mrf_fwd_sweep_window_squad", blocks, (int)(64u * (nwv + ni)), "%d,%d,%s,%d,%d", RMAX, D,
+                algo == MRF_TRWP ? "true" : "false", tw, ni);
 #define MRF_W(twv, niv) \
     if (tw == twv && ni == niv) { \
         if (algo == MRF_TRWP) hipLaunchKernelGGL((mrf_fwd_sweep_window_squad<RMAX, D, true, twv, niv>), dim3((unsigned)blocks), dim3(64u * (nwv + niv)), 0, st, P); \
@@ -309,6 +328,8 @@ hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long
     // few wavefronts in the launch: further ones per workgroup for the argmin tables and the stores
     // (two of them: an index wavefront has more to do per node than the value wavefront)
     const bool idx = g_tune_pack_idx != 1 && (g_tune_pack_idx == 2 || blocks <= 1024);
+    note_launch(0, "mrf_fwd_sweep_packed", blocks, idx ? 192 : 64, "%d,%d,%d,%d,%s,%d", SEG, MU, rmax, rmax == 4 ? 4 : (rmax == 8 ? 2 : 1),
+                algo == MRF_TRWP ? "true" : "false", idx ? 2 : 0);
 #define MRF_P(rm, d) \
     if (rmax == rm) { \
         if (idx) { \
@@ -328,7 +349,6 @@ hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long
 template <int SEG>
 hipError_t launch_packed(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
 {
-    g_last_sweep[0] = "mrf_fwd_sweep_packed";
     // source labels per node: L rounded up to a multiple of four
     const int mu = (P.g.L + 3) / 4 * 4;
     if (mu <= SEG - 12) return launch_packed_mu<SEG, SEG - 12>(P, algo, rmax, scanlines, st);
@@ -548,8 +568,11 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
 template <int LP, int NS, int D>
 hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
-    g_last_sweep[1] = "mrf_bwd_sweep";
     const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_WAVES);
+    note_launch(1, "mrf_bwd_sweep", blocks, 64 * MRF_BWD_WAVES, "%d,%d,%d,%s,%s,%s", LP, NS, D,
+                (P.gw && P.v_mode == 0) ? "true" : "false",
+                (!(P.rho_e && P.gw && P.v_mode == 0) && !(P.rho_e || P.gE) && !(P.gw && P.v_mode == 0) && P.hot_label) ? "true" : "false",
+                (P.rho_e || P.gE) ? "true" : "false");
     if (P.rho_e && P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false, true>), grid, block, lds, st, P);
     else if (P.rho_e || P.gE)
@@ -566,8 +589,8 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
 template <int NS, int D>
 hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
-    g_last_sweep[1] = "mrf_bwd_sweep_split";
     const dim3 grid((unsigned)blocks), block(64u * (unsigned)((P.g.L + 63) / 64));
+    note_launch(1, "mrf_bwd_sweep_split", blocks, (int)block.x, "%d,%d,%s", NS, D, (P.gw && P.v_mode == 0) ? "true" : "false");
     if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep_split<NS, D, true>), grid, block, lds, st, P);
     else
@@ -587,9 +610,11 @@ inline size_t chain_lds_cap(long long scanlines)
 template <int LP, int NS, int D>
 hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t st)
 {
-    g_last_sweep[1] = "mrf_bwd_sweep_chain";
     const dim3 grid((unsigned)P.total_scanlines);
     const bool gv = P.gV != nullptr;
+    note_launch(1, "mrf_bwd_sweep_chain", P.total_scanlines, 64 * (1 + ni), "%d,%d,%d,%d,%s,%s,%s", LP, NS, D, ni,
+                (!(LP == 1 && gv) && vg) ? "true" : "false", (LP == 1 && gv) ? "true" : "false",
+                (!(LP == 1 && gv) && !vg && P.hot_label) ? "true" : "false");
     if (gv && (LP != 1 || P.total_scanlines * ni > grad_slots(P.g.L))) return hipErrorInvalidValue;
     const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg, gv);
     if (lds > chain_lds_cap(P.total_scanlines)) return hipErrorInvalidValue;
@@ -625,11 +650,11 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
 template <int SEG>
 hipError_t launch_bwd_packed(const MrfBwdParams &P, int ns, hipStream_t st)
 {
-    g_last_sweep[1] = "mrf_bwd_sweep_packed";
     constexpr int NSEG = 64 / SEG;
     const int L = P.g.L;
     long long blocks = (P.total_scanlines + NSEG - 1) / NSEG;
     if (P.gV && blocks > grad_slots(L) / NSEG) blocks = grad_slots(L) / NSEG;
+    note_launch(1, "mrf_bwd_sweep_packed", blocks, 64, "%d,%d,%d", SEG, ns, ns <= 4 ? 4 : (ns == 8 ? 2 : 1));
     const size_t lds = sizeof(double) * (64 + (P.gV ? (size_t)NSEG * L * L : 0)) + sizeof(float) * (size_t)L * L;
     const dim3 grid((unsigned)blocks), block(64);
     if (ns == 1) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 1, 4>), grid, block, lds, st, P);
@@ -1069,6 +1094,8 @@ int mrf_softmin_l1(int64_t n_pixels, int32_t L, const float *cost, const float *
 const char *mrf_last_error_detail(void) { return g_error_detail; }
 
 const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ? 1 : 0]; }
+
+const char *mrf_last_sweep_launch(int backward) { return g_last_launch[backward ? 1 : 0]; }
 
 const char *mrf_version(void) { return "0.1.0"; }
 

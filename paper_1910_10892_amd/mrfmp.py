@@ -88,6 +88,8 @@ def load_library():
     lib.mrf_last_error_detail.argtypes = []
     lib.mrf_last_sweep_kernel.restype = ctypes.c_char_p
     lib.mrf_last_sweep_kernel.argtypes = [ci]
+    lib.mrf_last_sweep_launch.restype = ctypes.c_char_p
+    lib.mrf_last_sweep_launch.argtypes = [ci]
     lib.mrf_energy_workspace_bytes.restype = sz
     lib.mrf_energy_workspace_bytes.argtypes = [P]
     lib.mrf_energy.restype = ci
@@ -179,6 +181,10 @@ def mrf_last_error_detail() -> str:
 
 def mrf_last_sweep_kernel(backward: bool) -> str:
     return load_library().mrf_last_sweep_kernel(1 if backward else 0).decode()
+
+
+def mrf_last_sweep_launch(backward: bool) -> str:
+    return load_library().mrf_last_sweep_launch(1 if backward else 0).decode()
 
 
 def mrf_version() -> str:

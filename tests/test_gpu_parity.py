@@ -4,8 +4,10 @@ element, on the same seeded inputs.
 Bar: p, q, labels bit-exact (the argmins are decided in float32 on both sides, lowest
 index on ties); costs and messages within 1e-5 relative / 1e-4 absolute (they are in fact
 expected to be identical: same operations in the same order); gradients within the same
-tolerance of the float32 oracle -- or, where float32 summation order makes the float32
-oracle itself drift by about that much, of the exact (double) replay of the same indices.
+tolerance of the oracle's double instantiation replaying the same indices (the library
+carries its sums in double and rounds once on store; the float32 instantiation of the
+oracle rounds after every addition and is itself up to about one tolerance away from the
+double one on the larger problems -- its distance is printed, not asserted).
 """
 import numpy as np
 import pytest
@@ -39,19 +41,22 @@ def check_forward(g, f):
 
 
 def check_grad(name, got, ref32, ref64):
+    """Asserts against the double replay alone; ref32 (the float32 oracle, may be None) only
+    adds its own distance to the message."""
     assert np.isfinite(got).all(), name
-    e32 = np.abs(got.astype(np.float64) - ref32) / (ATOL + RTOL * np.abs(ref32))
     e64 = np.abs(got.astype(np.float64) - ref64) / (ATOL + RTOL * np.abs(ref64))
-    worst = np.minimum(e32, e64).max()
-    assert worst <= 1.0, "%s: worst error/tolerance %.3f (vs f32 oracle %.3f, vs exact %.3f)" % (
-        name, worst, e32.max(), e64.max())
+    worst = e64.max() if e64.size else 0.0
+    if worst > 1.0:
+        e32 = -1.0 if ref32 is None else (np.abs(got.astype(np.float64) - ref32) / (ATOL + RTOL * np.abs(ref32))).max()
+        raise AssertionError("%s: worst error/tolerance vs double replay %.3f (vs f32 oracle %.3f)" % (name, worst, e32))
 
 
 def check_backward(g, b32, b64, want_V=True):
-    check_grad("grad_unary", g.grad_unary, b32.grad_unary, b64.grad_unary)
-    check_grad("grad_edge_weight", g.grad_edge_weight, b32.grad_edge_weight, b64.grad_edge_weight)
+    f = lambda name: None if b32 is None else getattr(b32, name)
+    check_grad("grad_unary", g.grad_unary, f("grad_unary"), b64.grad_unary)
+    check_grad("grad_edge_weight", g.grad_edge_weight, f("grad_edge_weight"), b64.grad_edge_weight)
     if want_V:
-        check_grad("grad_pairwise", g.grad_pairwise, b32.grad_pairwise, b64.grad_pairwise)
+        check_grad("grad_pairwise", g.grad_pairwise, f("grad_pairwise"), b64.grad_pairwise)
 
 
 def full_check(oracle, pr, threads=False, want_V=True):
@@ -510,6 +515,100 @@ def test_full_size_stereo_config_trwp(oracle):
         g = run_gpu(pr, want_V=want_V)
         check_forward(g, f)
         check_backward(g, b32, b64, want_V)
+
+
+def _progress(msg):
+    """Long tests say where they are: on stdout and, where a GPU job's output folder exists, in
+    a file there (a run that is silent for minutes is taken for hung)."""
+    import os, time
+    print(msg, flush=True)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "test_progress.log"), "a") as fh:
+            fh.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
+
+
+def _full_size_check(oracle, pr, want_V, fwd_launch, bwd_launch):
+    """Whole-grid parity in the launch configuration bench.py times: forward element by element
+    (oracle forward on all host threads, bit-identical to one thread), gradients against the
+    double replay, and the kernel instantiations the launch rules picked."""
+    import gc
+    import torch
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import GpuProblem
+    g = GpuProblem(pr)
+    g.poison_outputs()
+    g.forward()
+    g.backward(want_V=want_V)
+    torch.cuda.synchronize()
+    assert mrf.mrf_last_sweep_launch(False) == fwd_launch, mrf.mrf_last_sweep_launch(False)
+    assert mrf.mrf_last_sweep_launch(True) == bwd_launch, mrf.mrf_last_sweep_launch(True)
+    _progress("  GPU done; oracle forward (all host threads)")
+    f = oracle_forward(oracle, pr, threads=True)
+    _progress("  oracle forward done; comparing")
+    for name in ("p", "q", "labels"):
+        got = getattr(g, name).cpu().numpy()
+        assert np.array_equal(got, getattr(f, name)), name
+        del got
+    for name in ("messages", "cost"):
+        got = getattr(g, name).cpu().numpy()
+        ref = getattr(f, name)
+        # (identical in fact: same operations in the same order)
+        bad = np.abs(got - ref) > ATOL + RTOL * np.abs(ref)
+        assert not bad.any(), "%s: %d entries off" % (name, int(bad.sum()))
+        del got, bad
+    p, q = f.p, f.q
+    del f
+    gc.collect()
+    _progress("  oracle backward (double)")
+    b64 = oracle_backward(oracle, pr, p, q, np.float64)
+    _progress("  oracle backward done; comparing")
+    check_grad("grad_unary", g.grad_unary.cpu().numpy(), None, b64.grad_unary)
+    check_grad("grad_edge_weight", g.grad_edge_weight.cpu().numpy(), None, b64.grad_edge_weight)
+    if want_V:
+        check_grad("grad_pairwise", g.grad_pairwise.cpu().numpy(), None, b64.grad_pairwise)
+
+
+def test_full_size_driving_stereo_config_isgmr(oracle):
+    """The largest benchmark shape whole, as bench.py times it: ISGMR, 384 x 1248, L = 192, 8
+    directions, K = 3 -- 9,788 scanlines per launch, message and index arrays beyond 2^31 bytes.
+    The first iteration runs the launch with zero messages, the later ones the launch that reads
+    seven message arrays.  (The oracle's share of the test is about 35 s per iteration on 16 host
+    threads.)"""
+    _progress("case full config 3")
+    pr = make_config(3)
+    _full_size_check(oracle, pr, False,
+                     "mrf_fwd_sweep_window<3,8,1,false,2> grid=9788 block=64",
+                     "mrf_bwd_sweep<3,1,2,false,true,false> grid=2447 block=256")
+
+
+def test_full_size_denoising_config_trwp(oracle):
+    """The denoising shape whole: TRWP, 256 x 256, L = 256, truncated quadratic, rho = 0.5, in the
+    launch configuration of the bench (no grad_pairwise buffer), all K = 10 iterations."""
+    _progress("case full config 4")
+    pr = make_config(4)
+    _full_size_check(oracle, pr, False,
+                     "mrf_fwd_sweep_window_squad<4,4,true,16,8> grid=256 block=768",
+                     "mrf_bwd_sweep_chain<4,4,1,8,false,false,true> grid=256 block=576")
+
+
+def test_full_size_denoising_config_dense_sweep(oracle):
+    """The same shape through the dense O(L^2) sweep (the launch bench.py times as the dense
+    variant of this configuration): K = 2, forward outputs only."""
+    import torch
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import GpuProblem
+    _progress("case full config 4, dense sweep (K = 2)")
+    pr = make_config(4, K=2)
+    pr.pairwise_kind = 0
+    g = GpuProblem(pr)
+    g.poison_outputs()
+    g.forward()
+    torch.cuda.synchronize()
+    assert mrf.mrf_last_sweep_kernel(False) == "mrf_fwd_sweep"
+    f = oracle_forward(oracle, pr, threads=True)
+    for name in ("p", "q", "labels", "messages", "cost"):
+        assert np.array_equal(getattr(g, name).cpu().numpy(), getattr(f, name)), name
 
 
 def _drawn_problem(seed):
