@@ -57,7 +57,8 @@ typedef enum {
     MRF_ERR_WORKSPACE_TOO_SMALL = -6,
     MRF_ERR_BAD_PAIRWISE_KIND = -7, /* unknown pairwise_kind, trunc <= 0 for kinds 1-3, or scale < 0 for kinds 1, 2 */
     MRF_ERR_BAD_ALGORITHM = -8,     /* algo argument is neither MRF_ISGMR nor MRF_TRWP */
-    MRF_ERR_HIP = -9                /* a HIP runtime call or kernel launch failed */
+    MRF_ERR_HIP = -9,               /* a HIP runtime call or kernel launch failed */
+    MRF_ERR_SCRATCH_LIMIT = -10     /* the problem exceeds the fixed scratch of a no-allocation entry point */
 } mrf_status;
 
 enum { MRF_ISGMR = 0, MRF_TRWP = 1 };
@@ -179,6 +180,17 @@ int mrf_scanline_head(int32_t H, int32_t W, int32_t dh, int32_t dw, int64_t t,
 size_t mrf_energy_workspace_bytes(const mrf_problem *prob);
 int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, void *workspace,
                size_t workspace_bytes, void *hip_stream);
+
+/* mrf_energy for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): same arguments and results without the
+ * workspace.  The partial sums go to a device array inside the library (2 MiB per GPU the
+ * library runs on, held until the process ends), which holds them for at most
+ * MRF_ENERGY_NOALLOC_MAX_BATCH batch images: a larger prob->B returns MRF_ERR_SCRATCH_LIMIT
+ * before any GPU work.  The call allocates nothing and frees nothing.  All calls on one GPU
+ * share that array: calls that may overlap on one GPU (different streams, different threads)
+ * race and must be ordered by the caller; calls on one stream are ordered by the stream. */
+#define MRF_ENERGY_NOALLOC_MAX_BATCH 64
+int mrf_energy_noalloc(const mrf_problem *prob, const uint8_t *labels, double *energy, void *hip_stream);
 
 /* Loss head of the learning set-up (Appendix, Eqs. supp-isgmr-confidence,
  * supp-isgmr-regression, and the L1 loss named there): per pixel

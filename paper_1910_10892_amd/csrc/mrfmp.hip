@@ -1006,6 +1006,7 @@ const char *mrf_strerror(int status)
     case MRF_ERR_BAD_PAIRWISE_KIND: return "unknown pairwise_kind, invalid trunc or negative scale";
     case MRF_ERR_BAD_ALGORITHM: return "algo must be MRF_ISGMR or MRF_TRWP";
     case MRF_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    case MRF_ERR_SCRATCH_LIMIT: return "problem exceeds the fixed scratch of a no-allocation entry point (batch > 64)";
     default: return "unknown status";
     }
 }
@@ -1049,6 +1050,33 @@ int mrf_energy(const mrf_problem *prob, const uint8_t *labels, double *energy, v
     if (!labels || !energy || !workspace) return MRF_ERR_NULL_POINTER;
     if (workspace_bytes < mrf_energy_workspace_bytes(prob)) return MRF_ERR_WORKSPACE_TOO_SMALL;
     return energy_launch(prob, labels, energy, (double *)workspace, (hipStream_t)hip_stream);
+}
+
+// ---- mrf_energy for callers that cannot allocate: the partial sums live in a device array of the
+// library's own.  Every GPU holds its own copy of the array at its own address; the name below is
+// only the host-side handle of the symbol, so host code asks the runtime once per device where the
+// copy lives and passes that pointer on.
+static __device__ __align__(256) double mrf_energy_scratch[(size_t)MRF_ENERGY_NOALLOC_MAX_BATCH * MRF_HEAD_BLOCKS];
+#define MRF_MAX_DEVICES 64
+static double *g_energy_scratch_ptr[MRF_MAX_DEVICES];     // per device, set on the first call there
+
+int mrf_energy_noalloc(const mrf_problem *prob, const uint8_t *labels, double *energy, void *hip_stream)
+{
+    const int rc = check_problem(prob, MRF_ISGMR, true);
+    if (rc != MRF_OK) return rc;
+    if (!labels || !energy) return MRF_ERR_NULL_POINTER;
+    if (prob->B > MRF_ENERGY_NOALLOC_MAX_BATCH) return MRF_ERR_SCRATCH_LIMIT;
+    int dev = -1;
+    { const hipError_t e_ = hipGetDevice(&dev); if (e_ != hipSuccess) return hip_fail(e_, "hipGetDevice"); }
+    if (dev < 0 || dev >= MRF_MAX_DEVICES) return MRF_ERR_SCRATCH_LIMIT;
+    if (!g_energy_scratch_ptr[dev]) {
+        double *ptr = nullptr;
+        const hipError_t e_ = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(mrf_energy_scratch));
+        if (e_ != hipSuccess || !ptr) return hip_fail(e_, "hipGetSymbolAddress(mrf_energy_scratch)");
+        g_energy_scratch_ptr[dev] = ptr;
+    }
+    // (every partial sum the second kernel reads is written by the first: nothing has to start at zero)
+    return energy_launch(prob, labels, energy, g_energy_scratch_ptr[dev], (hipStream_t)hip_stream);
 }
 
 size_t mrf_softmin_l1_workspace_bytes(void)

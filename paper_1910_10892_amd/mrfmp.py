@@ -94,6 +94,8 @@ def load_library():
     lib.mrf_energy_workspace_bytes.argtypes = [P]
     lib.mrf_energy.restype = ci
     lib.mrf_energy.argtypes = [P, vp, vp, vp, sz, vp]
+    lib.mrf_energy_noalloc.restype = ci
+    lib.mrf_energy_noalloc.argtypes = [P, vp, vp, vp]
     lib.mrf_softmin_l1_workspace_bytes.restype = sz
     lib.mrf_softmin_l1_workspace_bytes.argtypes = []
     lib.mrf_softmin_l1.restype = ci
@@ -286,6 +288,15 @@ def mrf_energy(prob, labels, energy, workspace, stream=None):
                                    _dev_ptr(workspace), _ws_size(workspace), _stream_handle(stream))
     if rc != 0:
         raise MrfError(rc, "mrf_energy")
+
+
+def mrf_energy_noalloc(prob, labels, energy, stream=None):
+    """mrf_energy without a workspace argument (the library's own fixed scratch; batch <= 64)."""
+    c = prob.c_struct()
+    rc = load_library().mrf_energy_noalloc(ctypes.byref(c), _dev_ptr(labels, "uint8"), _dev_ptr(energy, "float64"),
+                                           _stream_handle(stream))
+    if rc != 0:
+        raise MrfError(rc, "mrf_energy_noalloc")
 
 
 def mrf_softmin_l1_workspace_bytes() -> int:

@@ -74,7 +74,7 @@ def test_validation_codes_without_gpu():
     assert V(_cprob(pairwise_kind=1, trunc=2.0, scale=0.0)) == 0
     assert V(_cprob(pairwise_kind=3, trunc=2.0, scale=-1.0)) == 0     # kind 3 does not use scale
     assert lib.mrf_validate(None, 0) == -1
-    for code in range(0, -10, -1):
+    for code in range(0, -11, -1):
         assert mrf.mrf_strerror(code) != "unknown status"
 
 
@@ -124,6 +124,18 @@ def test_entry_points_reject_before_any_gpu_work():
         needb = lib.mrf_workspace_bytes(ctypes.byref(c), algo, 1)
         assert f(ctypes.byref(c), None, fake, fake, fake, None, None, fake, needb, None) == -1
         assert f(ctypes.byref(c), fake, fake, fake, fake, None, None, fake, needb - 1, None) == -6
+
+
+def test_noalloc_energy_rejects_what_its_scratch_cannot_hold():
+    """mrf_energy_noalloc: a batch beyond its fixed device array is an error before any GPU call."""
+    lib = mrf.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    f = lib.mrf_energy_noalloc
+    f.restype = ctypes.c_int
+    assert f(ctypes.byref(_cprob(B=65)), fake, fake, None) == -10
+    assert f(ctypes.byref(_cprob(B=64)), None, fake, None) == -1
+    assert f(ctypes.byref(_cprob(L=0)), fake, fake, None) == -3
+    assert "scratch" in mrf.mrf_strerror(-10)
 
 
 @pytest.mark.parametrize("H,W", [(1, 1), (1, 7), (6, 1), (5, 9), (9, 5), (4, 4)])
