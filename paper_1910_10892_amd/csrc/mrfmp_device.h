@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
+#ifdef __HIPCC__
+#include <utility>
+#endif
 
 #define MRF_WAVE 64
 #define MRF_MAXR 16
@@ -102,6 +105,162 @@ __device__ inline float mrf_min3(float a, float b, float c)
     float r;
     asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
+}
+
+// ---- running (minimum, lowest argmin) without wait states --------------------------------------
+// On this chip a vector instruction that reads a lane mask (v_cndmask) must sit at least two vector
+// instructions behind the compare that wrote the mask; left to itself the compiler routes every
+// compare through VCC and pays an s_nop per candidate.  The blocks below keep G independent
+// (best, index) chains in flight: all compares first, each into a scalar register pair of its own,
+// then the minima, then the index selects, so that every select is 2 G - 1 >= 3 instructions behind
+// its compare.  best' = min(best, d), index' = d < best ? K : index: strict '<' keeps the lowest
+// index when candidates arrive in ascending order.  Inputs are never NaN.
+template <int K>
+__device__ inline void mrf_argmin_step(float (&b)[4], int (&i)[4], const float (&d)[4])
+{
+    unsigned long long m0, m1, m2, m3;
+    asm("v_cmp_lt_f32_e64 %8, %12, %0\n\t"
+        "v_cmp_lt_f32_e64 %9, %13, %1\n\t"
+        "v_cmp_lt_f32_e64 %10, %14, %2\n\t"
+        "v_cmp_lt_f32_e64 %11, %15, %3\n\t"
+        "v_min_f32_e32 %0, %0, %12\n\t"
+        "v_min_f32_e32 %1, %1, %13\n\t"
+        "v_min_f32_e32 %2, %2, %14\n\t"
+        "v_min_f32_e32 %3, %3, %15\n\t"
+        "v_cndmask_b32_e64 %4, %4, %16, %8\n\t"
+        "v_cndmask_b32_e64 %5, %5, %16, %9\n\t"
+        "v_cndmask_b32_e64 %6, %6, %16, %10\n\t"
+        "v_cndmask_b32_e64 %7, %7, %16, %11"
+        : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(i[0]), "+v"(i[1]), "+v"(i[2]), "+v"(i[3]),
+          "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3)
+        : "v"(d[0]), "v"(d[1]), "v"(d[2]), "v"(d[3]), "n"(K));
+}
+
+template <int K>
+__device__ inline void mrf_argmin_step(float (&b)[3], int (&i)[3], const float (&d)[3])
+{
+    unsigned long long m0, m1, m2;
+    asm("v_cmp_lt_f32_e64 %6, %9, %0\n\t"
+        "v_cmp_lt_f32_e64 %7, %10, %1\n\t"
+        "v_cmp_lt_f32_e64 %8, %11, %2\n\t"
+        "v_min_f32_e32 %0, %0, %9\n\t"
+        "v_min_f32_e32 %1, %1, %10\n\t"
+        "v_min_f32_e32 %2, %2, %11\n\t"
+        "v_cndmask_b32_e64 %3, %3, %12, %6\n\t"
+        "v_cndmask_b32_e64 %4, %4, %12, %7\n\t"
+        "v_cndmask_b32_e64 %5, %5, %12, %8"
+        : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(i[0]), "+v"(i[1]), "+v"(i[2]), "=&s"(m0), "=&s"(m1), "=&s"(m2)
+        : "v"(d[0]), "v"(d[1]), "v"(d[2]), "n"(K));
+}
+
+template <int K>
+__device__ inline void mrf_argmin_step(float (&b)[2], int (&i)[2], const float (&d)[2])
+{
+    unsigned long long m0, m1;
+    asm("v_cmp_lt_f32_e64 %4, %6, %0\n\t"
+        "v_cmp_lt_f32_e64 %5, %7, %1\n\t"
+        "v_min_f32_e32 %0, %0, %6\n\t"
+        "v_min_f32_e32 %1, %1, %7\n\t"
+        "v_cndmask_b32_e64 %2, %2, %8, %4\n\t"
+        "v_cndmask_b32_e64 %3, %3, %8, %5"
+        : "+v"(b[0]), "+v"(b[1]), "+v"(i[0]), "+v"(i[1]), "=&s"(m0), "=&s"(m1)
+        : "v"(d[0]), "v"(d[1]), "n"(K));
+}
+
+// one chain: two candidates in a row (indices K and K + 1), the second compared with the minimum
+// that includes the first
+template <int K>
+__device__ inline void mrf_argmin_step2(float &b, int &i, float d0, float d1)
+{
+    unsigned long long m0, m1;
+    asm("v_cmp_lt_f32_e64 %2, %4, %0\n\t"
+        "v_min_f32_e32 %0, %0, %4\n\t"
+        "v_cmp_lt_f32_e64 %3, %5, %0\n\t"
+        "v_min_f32_e32 %0, %0, %5\n\t"
+        "v_cndmask_b32_e64 %1, %1, %6, %2\n\t"
+        "v_cndmask_b32_e64 %1, %1, %7, %3"
+        : "+v"(b), "+v"(i), "=&s"(m0), "=&s"(m1)
+        : "v"(d0), "v"(d1), "n"(K), "n"(K + 1));
+}
+
+// the same for candidates that bring their index in a register (merging partial results)
+template <int G>
+__device__ inline void mrf_argmin_merge(float (&b)[G], int (&i)[G], const float (&d)[G], const int (&k)[G])
+{
+    static_assert(G >= 1 && G <= 4, "chains per block");
+    if constexpr (G == 4) {
+        unsigned long long m0, m1, m2, m3;
+        asm("v_cmp_lt_f32_e64 %8, %12, %0\n\t"
+            "v_cmp_lt_f32_e64 %9, %13, %1\n\t"
+            "v_cmp_lt_f32_e64 %10, %14, %2\n\t"
+            "v_cmp_lt_f32_e64 %11, %15, %3\n\t"
+            "v_min_f32_e32 %0, %0, %12\n\t"
+            "v_min_f32_e32 %1, %1, %13\n\t"
+            "v_min_f32_e32 %2, %2, %14\n\t"
+            "v_min_f32_e32 %3, %3, %15\n\t"
+            "v_cndmask_b32_e64 %4, %4, %16, %8\n\t"
+            "v_cndmask_b32_e64 %5, %5, %17, %9\n\t"
+            "v_cndmask_b32_e64 %6, %6, %18, %10\n\t"
+            "v_cndmask_b32_e64 %7, %7, %19, %11"
+            : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(i[0]), "+v"(i[1]), "+v"(i[2]), "+v"(i[3]),
+              "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3)
+            : "v"(d[0]), "v"(d[1]), "v"(d[2]), "v"(d[3]), "v"(k[0]), "v"(k[1]), "v"(k[2]), "v"(k[3]));
+    } else if constexpr (G == 3) {
+        unsigned long long m0, m1, m2;
+        asm("v_cmp_lt_f32_e64 %6, %9, %0\n\t"
+            "v_cmp_lt_f32_e64 %7, %10, %1\n\t"
+            "v_cmp_lt_f32_e64 %8, %11, %2\n\t"
+            "v_min_f32_e32 %0, %0, %9\n\t"
+            "v_min_f32_e32 %1, %1, %10\n\t"
+            "v_min_f32_e32 %2, %2, %11\n\t"
+            "v_cndmask_b32_e64 %3, %3, %12, %6\n\t"
+            "v_cndmask_b32_e64 %4, %4, %13, %7\n\t"
+            "v_cndmask_b32_e64 %5, %5, %14, %8"
+            : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(i[0]), "+v"(i[1]), "+v"(i[2]), "=&s"(m0), "=&s"(m1), "=&s"(m2)
+            : "v"(d[0]), "v"(d[1]), "v"(d[2]), "v"(k[0]), "v"(k[1]), "v"(k[2]));
+    } else if constexpr (G == 2) {
+        unsigned long long m0, m1;
+        asm("v_cmp_lt_f32_e64 %4, %6, %0\n\t"
+            "v_cmp_lt_f32_e64 %5, %7, %1\n\t"
+            "v_min_f32_e32 %0, %0, %6\n\t"
+            "v_min_f32_e32 %1, %1, %7\n\t"
+            "v_cndmask_b32_e64 %2, %2, %8, %4\n\t"
+            "v_cndmask_b32_e64 %3, %3, %9, %5"
+            : "+v"(b[0]), "+v"(b[1]), "+v"(i[0]), "+v"(i[1]), "=&s"(m0), "=&s"(m1)
+            : "v"(d[0]), "v"(d[1]), "v"(k[0]), "v"(k[1]));
+    } else {
+        if (d[0] < b[0]) { b[0] = d[0]; i[0] = k[0]; }
+    }
+}
+
+// lowest index among four candidates K .. K + 3 that equal `best`, else `i` unchanged: the four
+// compares first, then the selects from the highest index down (the lowest one lands last)
+template <int K>
+__device__ inline void mrf_first_equal4(int &i, float best, float d0, float d1, float d2, float d3)
+{
+    unsigned long long m0, m1, m2, m3;
+    asm("v_cmp_eq_f32_e64 %4, %6, %5\n\t"
+        "v_cmp_eq_f32_e64 %3, %7, %5\n\t"
+        "v_cmp_eq_f32_e64 %2, %8, %5\n\t"
+        "v_cmp_eq_f32_e64 %1, %9, %5\n\t"
+        "v_cndmask_b32_e64 %0, %0, %10, %4\n\t"
+        "v_cndmask_b32_e64 %0, %0, %11, %3\n\t"
+        "v_cndmask_b32_e64 %0, %0, %12, %2\n\t"
+        "v_cndmask_b32_e64 %0, %0, %13, %1"
+        : "+v"(i), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3)
+        : "v"(best), "v"(d3), "v"(d2), "v"(d1), "v"(d0), "n"(K + 3), "n"(K + 2), "n"(K + 1), "n"(K));
+}
+
+// compile-time loop: f(std::integral_constant<int, 0>), ..., f(std::integral_constant<int, N - 1>)
+template <class F, int... I>
+__device__ inline void mrf_static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ inline void mrf_static_for(F &&f)
+{
+    mrf_static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 // minimum over the 64 lanes, returned to every lane (wave-uniform).

@@ -219,18 +219,27 @@ mrf_fwd_sweep(const MrfFwdParams P)
             int bidx[LP];
 #pragma unroll
             for (int s = 0; s < LP; ++s) { best[s] = INFINITY; bidx[s] = 0; }
-#pragma unroll
-            for (int i4 = 0; i4 < MCH; i4 += 4) {
+            // (compares, minima and index selects of the LP label slots go out in blocks that need
+            // no wait states: mrf_argmin_step)
+            mrf_static_for<MCH / 4>([&](auto q4) {
+                constexpr int i4 = 4 * decltype(q4)::value;
                 const float4 hv = *reinterpret_cast<const float4 *>(&hbuf[mu0 + i4]);
                 const float hq[4] = { hv.x, hv.y, hv.z, hv.w };
+                if constexpr (LP == 1) {
+                    mrf_argmin_step2<i4>(best[0], bidx[0], __builtin_fmaf(wgt, Vr[i4][0], hq[0]),
+                                         __builtin_fmaf(wgt, Vr[i4 + 1][0], hq[1]));
+                    mrf_argmin_step2<i4 + 2>(best[0], bidx[0], __builtin_fmaf(wgt, Vr[i4 + 2][0], hq[2]),
+                                             __builtin_fmaf(wgt, Vr[i4 + 3][0], hq[3]));
+                } else {
+                    mrf_static_for<4>([&](auto cc) {
+                        constexpr int c = decltype(cc)::value;
+                        float dlt[LP];
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-#pragma unroll
-                    for (int s = 0; s < LP; ++s) {
-                        const float dlt = __builtin_fmaf(wgt, Vr[i4 + c][s], hq[c]);
-                        if (dlt < best[s]) { best[s] = dlt; bidx[s] = i4 + c; }
-                    }
-            }
+                        for (int s = 0; s < LP; ++s) dlt[s] = __builtin_fmaf(wgt, Vr[i4 + c][s], hq[c]);
+                        mrf_argmin_step<i4 + c>(best, bidx, dlt);
+                    });
+                }
+            });
 
             float tv[LP];
             int tp[LP];
@@ -244,11 +253,15 @@ mrf_fwd_sweep(const MrfFwdParams P)
                 for (int s = 0; s < LP; ++s) { tv[s] = INFINITY; tp[s] = 0; }
 #pragma unroll
                 for (int w2 = 0; w2 < NWMAX; ++w2) {
+                    float ev[LP];
+                    int ei[LP];
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
                         const float2 e = pb[w2 * SLOTS + lane + 64 * s];
-                        if (e.x < tv[s]) { tv[s] = e.x; tp[s] = __float_as_int(e.y); }
+                        ev[s] = e.x;
+                        ei[s] = __float_as_int(e.y);
                     }
+                    mrf_argmin_merge<LP>(tv, tp, ev, ei);
                 }
                 buf ^= 1;
             } else {
@@ -2168,8 +2181,10 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 #pragma unroll
             for (int m = 2; m + 1 < MU; m += 2) best = mrf_min3(best, dl[m], dl[m + 1]);
             int bidx = MU - 1;
-#pragma unroll
-            for (int m = MU - 2; m >= 0; --m) bidx = (dl[m] == best) ? m : bidx;
+            mrf_static_for<MU / 4>([&](auto g4) {
+                constexpr int m0 = MU - 4 - 4 * decltype(g4)::value;      // groups from the top down
+                mrf_first_equal4<m0>(bidx, best, dl[m0], dl[m0 + 1], dl[m0 + 2], dl[m0 + 3]);
+            });
             const float tv = valid ? best : INFINITY;
             const float tq = mrf_segment_min<SEG>(tv);
             const unsigned long long bal = __ballot(tv == tq);
@@ -2279,8 +2294,10 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             if (IDX) continue;                    // the index wavefront does the rest
 
             int bidx = MU - 1;
-#pragma unroll
-            for (int m = MU - 2; m >= 0; --m) bidx = (dl[m] == best) ? m : bidx;
+            mrf_static_for<MU / 4>([&](auto g4) {
+                constexpr int m0 = MU - 4 - 4 * decltype(g4)::value;      // groups from the top down
+                mrf_first_equal4<m0>(bidx, best, dl[m0], dl[m0 + 1], dl[m0 + 2], dl[m0 + 3]);
+            });
             const unsigned long long bal = __ballot(tv == tq);
             const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
             const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
