@@ -136,7 +136,8 @@ def make_config(index: int, crop: Optional[tuple] = None, K: Optional[int] = Non
         unary = rng.random((B, H, W, L), dtype=np.float32)
         V = truncated_linear(L, 4.0)
         w = mirrored_edge_weights(rng, B, H, W, dirs, lambda g, s: g.uniform(0.5, 1.5, s))
-        prob = Problem("cfg1_isgmr_32x48_L16", algo or "isgmr", unary, V, np.array(dirs, np.int32), k,
+        a = algo or "isgmr"
+        prob = Problem("cfg1_%s_32x48_L16" % a, a, unary, V, np.array(dirs, np.int32), k,
                        edge_weight=w, pairwise_kind=KIND_TRUNC_LINEAR, trunc=4.0, scale=1.0)
     elif index == 2:
         H, W = crop or (256, 512)
@@ -149,7 +150,8 @@ def make_config(index: int, crop: Optional[tuple] = None, K: Optional[int] = Non
         unary[bb, yy, xx, disp[None].repeat(B, 0)] = planted
         V = truncated_linear(L, 8.0)
         w = _contrast_weights(rng, B, H, W, dirs)
-        prob = Problem("cfg2_trwp_stereo_256x512_L96", algo or "trwp", unary, V, np.array(dirs, np.int32), k,
+        a = algo or "trwp"
+        prob = Problem("cfg2_%s_stereo_256x512_L96" % a, a, unary, V, np.array(dirs, np.int32), k,
                        edge_weight=w, rho=np.full(4, 0.25, np.float32),
                        pairwise_kind=KIND_TRUNC_LINEAR, trunc=8.0, scale=1.0)
     elif index == 3:
@@ -157,7 +159,8 @@ def make_config(index: int, crop: Optional[tuple] = None, K: Optional[int] = Non
         B, L, dirs, k = 1, 192, DIRS8, 3
         unary = rng.random((B, H, W, L), dtype=np.float32)
         V = truncated_linear(L, 2.0)
-        prob = Problem("cfg3_isgmr_driving_384x1248_L192", algo or "isgmr", unary, V, np.array(dirs, np.int32), k,
+        a = algo or "isgmr"
+        prob = Problem("cfg3_%s_driving_384x1248_L192" % a, a, unary, V, np.array(dirs, np.int32), k,
                        edge_weight=None, edge_weight_scalar=0.5,
                        pairwise_kind=KIND_TRUNC_LINEAR, trunc=2.0, scale=1.0)
     elif index == 4:
@@ -171,7 +174,8 @@ def make_config(index: int, crop: Optional[tuple] = None, K: Optional[int] = Non
         unary = (((lab[None, None, :] - noisy[:, :, None]) ** 2) / 255.0 ** 2).astype(np.float32)[None]
         scale = np.float32(1.0 / 255.0 ** 2)
         V = truncated_quadratic(L, 200.0, scale)
-        prob = Problem("cfg4_trwp_denoise_256x256_L256", algo or "trwp", np.ascontiguousarray(unary), V,
+        a = algo or "trwp"
+        prob = Problem("cfg4_%s_denoise_256x256_L256" % a, a, np.ascontiguousarray(unary), V,
                        np.array(dirs, np.int32), k, edge_weight=None, edge_weight_scalar=1.0,
                        rho=np.full(4, 0.5, np.float32),
                        pairwise_kind=KIND_TRUNC_QUADRATIC, trunc=200.0, scale=float(scale))

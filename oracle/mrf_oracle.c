@@ -31,9 +31,14 @@
  *     are stored at node i.
  *  9. Gradients of theta_i, theta_{i-r,i} and V accumulate over all iterations,
  *     directions and nodes (Appendix D.3 item 1).
+ * 10. Standard SGM (Eq. sgm_old): first node's message = its unary; computed messages are
+ *     reparametrised by Eq. isgmr-norm like all others.
  * Pins (tests/test_oracle_*.py): brute-force min-marginals on chains and trees,
- * discounted brute force for TRWP with rho != 1, Viterbi for K = 1, invariants, central
- * finite differences of the double instantiation.  Printed-value parity: unpinned (the
+ * discounted brute force for TRWP with rho != 1, Viterbi for K = 1, the iteration-2 messages of
+ * ISGMR on a loopy grid enumerated from those of iteration 1, standard SGM by scanline
+ * enumeration with the node's own unary inside the minimum, invariants, central finite
+ * differences of the double instantiation; tests/test_oracle_mutations.py plants mistakes in a
+ * copy of this source and checks that the pins catch each.  Printed-value parity: unpinned (the
  * paper prints no worked numeric example).
  */
 #include <math.h>

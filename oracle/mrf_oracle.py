@@ -133,6 +133,30 @@ def forward(algo: str, unary, pairwise, dirs, K: int, edge_weight=None, edge_wei
     return ForwardResult(cost, labels, p, q, msg)
 
 
+def sgm_standard_forward(unary, pairwise, dirs, edge_weight=None, edge_weight_scalar=1.0,
+                         dtype=np.float32) -> ForwardResult:
+    """Standard single-pass SGM (Sec. 3.2, Eq. sgm_old and Eq. isgmr-aggregation-old): messages that
+    carry the node's own unary, one pass, cost = sum of the messages.  p, q as for K = 1."""
+    sfx, creal = _real(dtype)
+    unary = np.ascontiguousarray(unary, dtype=dtype)
+    B, H, W, L, dirs, R = _common(unary.shape, dirs, dtype)
+    V = np.ascontiguousarray(pairwise, dtype=dtype)
+    assert V.shape == (L, L)
+    w = None if edge_weight is None else np.ascontiguousarray(edge_weight, dtype=dtype)
+    cost = np.empty((B, H, W, L), dtype)
+    labels = np.empty((B, H, W), np.uint8)
+    p = np.empty((1, R, B, H, W, L), np.uint8)
+    q = np.empty((1, R, B, H, W), np.uint8)
+    msg = np.empty((R, B, H, W, L), dtype)
+    fn = getattr(_lib(False), "mrfo_sgm_standard_forward_" + sfx)
+    rc = fn(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(W), ctypes.c_int(L), ctypes.c_int(R), _ptr(dirs),
+            _ptr(unary), _ptr(V), _ptr(w), creal(edge_weight_scalar), _ptr(cost), _ptr(labels), _ptr(p), _ptr(q),
+            _ptr(msg))
+    if rc != 0:
+        raise ValueError("oracle rejected the problem (rc=%d)" % rc)
+    return ForwardResult(cost, labels, p, q, msg)
+
+
 def backward(algo: str, shape, pairwise, dirs, K: int, grad_cost, p, q, edge_weight=None,
              edge_weight_scalar=1.0, rho=None, dtype=np.float32, rho_edge=None,
              per_edge_pairwise: bool = False) -> BackwardResult:

@@ -8,6 +8,7 @@
  * order and notation, with no blocking, fusion or reordering:
  *   Alg. 1  forward ISGMR      Alg. 2  forward TRWP
  *   Alg. 3  backprop ISGMR     Alg. 4  backprop TRWP   (Appendix A)
+ *   Sec. 3.2  standard single-pass SGM (Eq. sgm_old, Eq. isgmr-aggregation-old), forward only
  * using the pairwise decomposition theta_{i-r,i}(mu,lambda) = theta_{i-r,i} V(mu,lambda)
  * (Sec. 5.1 "MRF model parameters", Appendix D.2) so that the gradients are those of
  * the edge weights (Eq. supp-gradient-edge) and of V (Eq. supp-gradient-smoothness).
@@ -137,6 +138,84 @@ int NAME(mrfo_isgmr_forward)(int B, int H, int W, int L, int R, const int *dirs,
     NAME(aggregate)(&g, unary, m, cost, labels);
     if (messages) memcpy(messages, m, sizeof(REAL) * (size_t)R * N * L);
     free(m); free(mhat);
+    return 0;
+}
+
+/* ==================== standard single-pass SGM (Sec. 3.2) ====================== *
+ * The update in the form the SGM paper gives it, Eq. sgm_old: the message to node i holds
+ * the node's own unary,
+ *     m^r_i(lambda) = theta_i(lambda) + min_mu ( m^r_{i-r}(mu) + theta_{i-r,i}(mu,lambda) ),
+ * one pass over every direction, and the final cost is the plain sum of the messages,
+ * Eq. isgmr-aggregation-old (which counts every unary |R| times -- the over-counting that
+ * the revised update removes).
+ * Readings: the first node of a scanline has nothing before it, so its message is its
+ * unary; every computed message is reparametrised by Eq. isgmr-norm (minimum over labels
+ * subtracted, q = its lowest argmin), as the paper states for messages in general; ties
+ * and the fused multiply-add as everywhere else.  p, q have the K = 1 layout.            */
+int NAME(mrfo_sgm_standard_forward)(int B, int H, int W, int L, int R, const int *dirs,
+                                    const REAL *unary, const REAL *V, const REAL *w, REAL w_scalar,
+                                    REAL *cost, uint8_t *labels, uint8_t *p, uint8_t *q,
+                                    REAL *messages)
+{
+    grid_t g;
+    if (grid_init(&g, B, H, W, L, R, dirs, 1)) return -1;
+    const size_t N = grid_nodes(&g);
+    REAL *m = (REAL *)calloc((size_t)R * N * L, sizeof(REAL));
+    REAL *t = (REAL *)malloc(sizeof(REAL) * L);
+    heads_t hd;
+    memset(p, 0, (size_t)R * N * L);
+    memset(q, 0, (size_t)R * N);
+    for (int r = 0; r < R; ++r) {
+        heads_collect(&g, r, &hd);
+        for (size_t s = 0; s < hd.n; ++s) {
+            int b = hd.b[s], y = hd.y[s], x = hd.x[s];
+            size_t j = node_index(&g, b, y, x);
+            for (int lam = 0; lam < L; ++lam) m[((size_t)r * N + j) * L + lam] = unary[j * L + lam];
+            for (;;) {
+                int yn = y + g.dh[r], xn = x + g.dw[r];
+                if (!in_grid(&g, yn, xn)) break;
+                size_t i = node_index(&g, b, yn, xn);
+                j = node_index(&g, b, y, x);
+                REAL wgt = w ? w[(size_t)r * N + i] : w_scalar;
+                const REAL *prev = &m[((size_t)r * N + j) * L];
+                REAL *out = &m[((size_t)r * N + i) * L];
+                for (int lam = 0; lam < L; ++lam) {
+                    REAL best = (REAL)INFINITY;
+                    int arg = 0;
+                    for (int mu = 0; mu < L; ++mu) {
+                        REAL delta = REAL_FMA(wgt, V[(size_t)mu * L + lam], prev[mu]);
+                        if (delta < best) { best = delta; arg = mu; }
+                    }
+                    t[lam] = best;
+                    p[((size_t)r * N + i) * L + lam] = (uint8_t)arg;
+                }
+                for (int lam = 0; lam < L; ++lam) t[lam] = unary[i * L + lam] + t[lam];
+                int qq = 0;
+                for (int lam = 1; lam < L; ++lam)
+                    if (t[lam] < t[qq]) qq = lam;
+                q[(size_t)r * N + i] = (uint8_t)qq;
+                REAL mn = t[qq];
+                for (int lam = 0; lam < L; ++lam) out[lam] = t[lam] - mn;
+                y = yn; x = xn;
+            }
+        }
+        heads_free(&hd);
+    }
+    for (size_t i = 0; i < N; ++i) {
+        for (int lam = 0; lam < L; ++lam) {
+            REAL c = (REAL)0;
+            for (int d = 0; d < R; ++d) c = c + m[((size_t)d * N + i) * L + lam];
+            cost[i * L + lam] = c;
+        }
+        if (labels) {
+            int a = 0;
+            for (int lam = 1; lam < L; ++lam)
+                if (cost[i * L + lam] < cost[i * L + a]) a = lam;
+            labels[i] = (uint8_t)a;
+        }
+    }
+    if (messages) memcpy(messages, m, sizeof(REAL) * (size_t)R * N * L);
+    free(m); free(t);
     return 0;
 }
 

@@ -157,6 +157,56 @@ def test_single_iteration_is_scanline_dp_all_directions(oracle, dirs):
         assert seen.all()  # every node lies on exactly one scanline of each direction
 
 
+def _scanlines(H, W, dh, dw):
+    """Maximal in-grid chains of direction (dh, dw), written from the grid alone."""
+    out = []
+    for y0 in range(H):
+        for x0 in range(W):
+            if 0 <= y0 - dh < H and 0 <= x0 - dw < W:
+                continue
+            line, y, x = [], y0, x0
+            while 0 <= y < H and 0 <= x < W:
+                line.append((y, x)); y += dh; x += dw
+            out.append(line)
+    return out
+
+
+@pytest.mark.parametrize("H,W,L", [(3, 3, 3), (3, 4, 2)])
+def test_isgmr_second_iteration_reads_last_iterations_messages(oracle, H, W, L):
+    """The schedule of Alg. 1 on a loopy grid: in iteration 2, direction r reads the messages that
+    iteration 1 left in the other directions d (not the ones iteration 2 is producing), and neither
+    its own old message nor that of r- (Eq. isgmr).  Then the iteration-2 messages of direction r are
+    the scanline minimisation of Eq. sgm over the unaries theta + sum_{d not in {r, r-}} m^{d,1}.
+    Both the iteration-1 messages and the iteration-2 reference are enumerated here."""
+    rng = np.random.default_rng(100 + H * W)
+    unary = rng.random((1, H, W, L))
+    V = rng.random((L, L))                 # asymmetric
+    w = rng.uniform(0.5, 1.5, (4, 1, H, W))
+    opp = {0: 1, 1: 0, 2: 3, 3: 2}
+    m1 = np.zeros((4, H, W, L))
+    for r, (dh, dw) in enumerate(DIRS4):
+        for line in _scanlines(H, W, dh, dw):
+            ul = np.array([unary[0, y, x] for y, x in line])
+            wl = np.array([w[r, 0, y, x] for y, x in line])
+            ref = scanline_prefix_min(ul, wl, V)
+            for n, (y, x) in enumerate(line):
+                m1[r, y, x] = ref[n]
+    f1 = oracle.forward("isgmr", unary, V, DIRS4, 1, edge_weight=w, dtype=F64)
+    np.testing.assert_allclose(f1.messages[:, 0], m1, atol=1e-12)
+    f2 = oracle.forward("isgmr", unary, V, DIRS4, 2, edge_weight=w, dtype=F64)
+    for r, (dh, dw) in enumerate(DIRS4):
+        others = [d for d in range(4) if d != r and d != opp[r]]
+        theta = unary[0] + sum(m1[d] for d in others)
+        for line in _scanlines(H, W, dh, dw):
+            ul = np.array([theta[y, x] for y, x in line])
+            wl = np.array([w[r, 0, y, x] for y, x in line])
+            ref = scanline_prefix_min(ul, wl, V)
+            got = np.array([f2.messages[r, 0, y, x] for y, x in line])
+            np.testing.assert_allclose(got, ref, atol=1e-12)
+    # and the final costs are the aggregation of exactly those messages
+    np.testing.assert_allclose(f2.cost[0], unary[0] + f2.messages[:, 0].sum(0), atol=1e-12)
+
+
 def test_trwp_single_direction_equals_isgmr(oracle):
     """First direction of the first iteration: all messages are 0, so Eq. trwp with rho = 1
     and Eq. isgmr coincide."""
