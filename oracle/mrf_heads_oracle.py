@@ -61,13 +61,15 @@ def energy(unary, pairwise, dirs, labels, edge_weight=None, edge_weight_scalar=1
     return out
 
 
-def softmin_l1(cost, target, mask=None):
+def softmin_l1(cost, target, mask=None, beta=0.0):
     """cost [..., L], target [...] (real-valued disparities), mask [...] (non-zero = pixel
     counts) or None.  Returns (disparity [...], loss scalar, grad_cost [..., L]), all float64.
 
     f = exp(-c) / sum exp(-c) over labels; d = sum_lambda lambda f(lambda);
-    loss = mean over counted pixels of |d - g|;
-    d loss / d c(lambda) = sign(d - g) / n * (-f(lambda)) * (lambda - d)."""
+    loss = mean over counted pixels of l(d - g), with l(x) = |x| (standard L1, beta = 0) or the
+    smooth L1 the paper names beside it (beta > 0): l(x) = x^2 / (2 beta) for |x| < beta, else
+    |x| - beta / 2 (the usual definition; the paper gives none, beta = 1 is the common choice);
+    d loss / d c(lambda) = l'(d - g) / n * (-f(lambda)) * (lambda - d)."""
     c = np.asarray(cost, np.float64)
     g = np.asarray(target, np.float64)
     L = c.shape[-1]
@@ -79,7 +81,14 @@ def softmin_l1(cost, target, mask=None):
     m = np.ones(g.shape, bool) if mask is None else (np.asarray(mask) != 0)
     n = int(m.sum())
     diff = d - g
-    loss = float(np.abs(diff[m]).sum() / n) if n > 0 else 0.0
-    s = np.where(m, np.sign(diff), 0.0) / max(n, 1)
+    if beta > 0.0:
+        small = np.abs(diff) < beta
+        per_pixel = np.where(small, diff * diff / (2.0 * beta), np.abs(diff) - beta / 2.0)
+        slope = np.where(small, diff / beta, np.sign(diff))
+    else:
+        per_pixel = np.abs(diff)
+        slope = np.sign(diff)
+    loss = float(per_pixel[m].sum() / n) if n > 0 else 0.0
+    s = np.where(m, slope, 0.0) / max(n, 1)
     grad = s[..., None] * (-f) * (lam - d[..., None])
     return d, loss, grad

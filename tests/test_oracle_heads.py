@@ -147,3 +147,35 @@ def test_softmin_l1_gradient_by_finite_differences(masked):
     np.testing.assert_allclose(grad, fd, rtol=1e-6, atol=1e-9)
     if masked:
         assert np.all(grad[mask == 0] == 0.0)
+
+
+@pytest.mark.parametrize("beta", [1.0, 0.25])
+def test_smooth_l1_closed_forms_and_gradient(beta):
+    """Smooth L1 against its two closed-form branches, its limits, and finite differences."""
+    rng = np.random.default_rng(41)
+    n, L = 9, 5
+    c = rng.normal(0, 1.5, (n, L))
+    d, _, _ = ho.softmin_l1(c, np.zeros(n))
+    # targets placed so that some pixels fall on either side of |d - g| = beta
+    g = d + np.array([0.0, 0.1, -0.2, 0.9, -0.99, 1.01, -3.0, 0.5, 2.0]) * beta
+    _, l1, _ = ho.softmin_l1(c, g)
+    _, ls, grad = ho.softmin_l1(c, g, beta=beta)
+    x = np.abs(d - g)
+    want = np.where(x < beta, x * x / (2 * beta), x - beta / 2).mean()
+    assert ls == pytest.approx(want, rel=1e-13)
+    assert ls <= l1 + 1e-15                                  # smooth L1 never exceeds L1
+    far = ho.softmin_l1(c, d + 5.0 * beta, beta=beta)[1]
+    assert far == pytest.approx(5.0 * beta - beta / 2, rel=1e-12)
+    h = 1e-6
+    fd = np.zeros_like(c)
+    for i in range(n):
+        for l in range(L):
+            cp, cm = c.copy(), c.copy()
+            cp[i, l] += h; cm[i, l] -= h
+            fd[i, l] = (ho.softmin_l1(cp, g, beta=beta)[1] - ho.softmin_l1(cm, g, beta=beta)[1]) / (2 * h)
+    np.testing.assert_allclose(grad, fd, rtol=2e-5, atol=1e-9)
+    # beta -> 0 recovers the plain L1 loss and its gradient away from d = g
+    _, l0, g0 = ho.softmin_l1(c, g, beta=1e-12)
+    _, _, g1 = ho.softmin_l1(c, g)
+    assert l0 == pytest.approx(l1, abs=1e-11)
+    np.testing.assert_allclose(g0[1:], g1[1:], atol=1e-12)
