@@ -241,6 +241,37 @@ def heads(index, algo):
     return {"workload": pr.name, "energy": rf(e_bytes, t_e), "softmin_l1": rf(l_bytes, t_l)}
 
 
+def energy_protocol():
+    """The protocol of the paper's energy tables (Sec. 5.1) on the synthetic stereo and denoising
+    shapes: K = 1 and K = 50 iterations of both algorithms, the energy of the labelling each returns
+    (Eq. energy-function, mrf_energy) and the time of the forward pass.  The tables' own numbers need
+    the paper's datasets; these are the stand-ins' energies."""
+    import torch
+    from mrf_inputs import make_config
+    from gpu_harness import GpuProblem
+    import paper_1910_10892_amd as mrf
+    rows = []
+    for index in (2, 4):
+        for algo in ("isgmr", "trwp"):
+            for K in (1, 50):
+                pr = make_config(index, algo=algo, K=K)
+                g = GpuProblem(pr, want_messages=False)
+                ws = torch.empty(mrf.mrf_energy_workspace_bytes(g.prob), dtype=torch.uint8, device="cuda:0")
+                e = torch.empty((pr.shape[0],), dtype=torch.float64, device="cuda:0")
+                g.forward()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                g.forward()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                mrf.mrf_energy(g.prob, g.labels, e, ws)
+                rows.append({"workload": pr.name, "algorithm": algo, "iterations": K,
+                             "energy": float(e.sum().item()), "forward_ms": (t1 - t0) * 1e3})
+                del g
+                torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -257,6 +288,9 @@ def main():
                     help="also run a 1 GiB device-to-device copy (calibration of HBM byte counters)")
     ap.add_argument("--heads", action="store_true",
                     help="also time the energy and SoftMin + L1 heads (extra \"heads\" object)")
+    ap.add_argument("--energy-protocol", action="store_true",
+                    help="also run K = 1 and K = 50 iterations of both algorithms on configurations 2 and 4 and "
+                         "report the energy of each labelling (extra \"energy_protocol\" array)")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
                     help="experiment: set a kernel-choice knob of mrf_tune (results never depend on them)")
     args = ap.parse_args()
@@ -316,6 +350,8 @@ def main():
     }
     if args.heads:
         out["heads"] = heads(head_run[0], head_run[1])
+    if args.energy_protocol:
+        out["energy_protocol"] = energy_protocol()
     if not args.no_cpu_baseline:
         crops = {1: (32, 48), 2: (128, 256), 3: (40, 104), 4: (24, 32), 5: (512, 512)}
         out["cpu_baseline"] = cpu_baseline(head_run[0], head_run[1], crops[head_run[0]])

@@ -103,6 +103,13 @@ typedef struct {
                                    points take grad_edge_weight = NULL and write to grad_pairwise, if given,
                                    the gradient of these tables, [R][B][H][W][L][L]
                                    (Eq. supp-gradient-pairwise; tables of first nodes get 0). */
+    int32_t sgm_standard;       /* non-zero: standard single-pass SGM (Sec. 3.2, Eq. sgm_old and
+                                   Eq. isgmr-aggregation-old) instead of the revised update: the message carries
+                                   the node's own unary, m^r_i(lambda) = theta_i(lambda) + min_mu (m^r_{i-r}(mu) +
+                                   theta_{i-r,i}(mu,lambda)), reparametrised by Eq. isgmr-norm (q is the argmin of
+                                   this sum), the first node of a scanline holds its unary, and c_i = sum_r m^r_i.
+                                   Forward only, through mrf_isgmr_forward with K = 1 (anything else, the backward
+                                   entry points included, returns MRF_ERR_BAD_ALGORITHM); runs the dense sweep. */
 } mrf_problem;
 
 /* Bytes of DEVICE workspace (256-byte aligned base required) that the forward
@@ -210,6 +217,14 @@ size_t mrf_softmin_l1_workspace_bytes(void);
 int mrf_softmin_l1(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
                    float *disparity, double *loss, float *grad_cost, void *workspace, size_t workspace_bytes,
                    void *hip_stream);
+
+/* The same head with the smooth L1 loss that Appendix D.1 names beside the standard one:
+ *   per pixel l(x) = x^2 / (2 beta) for |x| < beta, |x| - beta / 2 otherwise, x = d - target
+ * (the usual definition; the paper gives none), slope x / beta or sign(x) in grad_cost.
+ * beta > 0 and finite, else MRF_ERR_BAD_PAIRWISE_KIND.  Same buffers and workspace as mrf_softmin_l1. */
+int mrf_softmin_smooth_l1(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
+                          float beta, float *disparity, double *loss, float *grad_cost, void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
 
 /* Static text for a status code. */
 const char *mrf_strerror(int status);

@@ -45,6 +45,8 @@ inline int check_problem(const mrf_problem *pr, int algo, bool forward)
     if (pr->B < 1 || pr->H < 1 || pr->W < 1) return MRF_ERR_BAD_SHAPE;
     if (pr->L < 1 || pr->L > MRF_MAX_LABELS) return MRF_ERR_BAD_LABELS;
     if (pr->K < 1) return MRF_ERR_BAD_ITERATIONS;
+    // standard SGM is a single pass of the ISGMR sweeps without a backward pass of its own
+    if (pr->sgm_standard && (algo != MRF_ISGMR || pr->K != 1 || pr->pairwise_edge)) return MRF_ERR_BAD_ALGORITHM;
     if (pr->R < 1 || pr->R > MRF_MAX_DIRECTIONS) return MRF_ERR_BAD_DIRECTIONS;
     if (!pr->dirs) return MRF_ERR_NULL_POINTER;
     for (int r = 0; r < pr->R; ++r) {
@@ -364,7 +366,8 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
     if (P.Te) return launch_edge(P, algo, blocks, st);
     // (TRW coefficients per edge: the two one-wavefront-per-scanline sweeps read them)
     const bool generic = P.rho_e != nullptr;
-    if (!generic && P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
+    if (P.sgm_std) tw = 0;         // standard SGM: the dense sweep is the one that knows it
+    if (!P.sgm_std && !generic && P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
         int ms = 0;
         for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
             if (P.n_src[r] > ms) ms = P.n_src[r];
@@ -497,6 +500,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     for (int r = 0; r < R; ++r) P.rho[r] = (algo == MRF_TRWP && pr->rho) ? pr->rho[r] : 1.0f;
     P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
     P.Te = pr->pairwise_edge;
+    P.sgm_std = pr->sgm_standard ? 1 : 0;
 
     // workspace: [scalars 256 B][messages A][messages B (ISGMR only)]
     float *scal = (float *)workspace;
@@ -549,7 +553,7 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     mark(g_ev_stop, st);
 
     MrfAggParams A;
-    A.N = N; A.L = L; A.R = R;
+    A.N = N; A.L = L; A.R = R; A.no_unary = pr->sgm_standard ? 1 : 0;
     A.unary = pr->unary; A.m = final_m; A.cost = cost; A.labels = labels;
     long long ablocks = (N + 3) / 4;
     if (ablocks > 65536) ablocks = 65536;
@@ -772,6 +776,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
                  float *grad_unary, float *grad_w, float *grad_V, void *workspace, size_t workspace_bytes,
                  void *hip_stream)
 {
+    if (pr && pr->sgm_standard) return MRF_ERR_BAD_ALGORITHM;    // (Alg. 3 differentiates the revised update only)
     int rc = check_problem(pr, algo, false);
     if (rc != MRF_OK) return rc;
     if (!grad_cost || !p || !q || !grad_unary) return MRF_ERR_NULL_POINTER;
@@ -1084,9 +1089,30 @@ size_t mrf_softmin_l1_workspace_bytes(void)
     return kAlign + (sizeof(double) + sizeof(long long)) * MRF_HEAD_BLOCKS;
 }
 
+static int softmin_loss(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
+                        float *disparity, double *loss, float *grad_cost, double beta, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
+
 int mrf_softmin_l1(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
                    float *disparity, double *loss, float *grad_cost, void *workspace, size_t workspace_bytes,
                    void *hip_stream)
+{
+    return softmin_loss(n_pixels, L, cost, target, mask, disparity, loss, grad_cost, 0.0, workspace, workspace_bytes,
+                        hip_stream);
+}
+
+int mrf_softmin_smooth_l1(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
+                          float beta, float *disparity, double *loss, float *grad_cost, void *workspace,
+                          size_t workspace_bytes, void *hip_stream)
+{
+    if (!(beta > 0.0f) || !(beta < INFINITY)) return MRF_ERR_BAD_PAIRWISE_KIND;
+    return softmin_loss(n_pixels, L, cost, target, mask, disparity, loss, grad_cost, (double)beta, workspace,
+                        workspace_bytes, hip_stream);
+}
+
+static int softmin_loss(int64_t n_pixels, int32_t L, const float *cost, const float *target, const uint8_t *mask,
+                        float *disparity, double *loss, float *grad_cost, double beta, void *workspace,
+                        size_t workspace_bytes, void *hip_stream)
 {
     if (n_pixels < 1 || n_pixels > 0x7fffffffLL) return MRF_ERR_BAD_SHAPE;
     if (L < 1 || L > MRF_MAX_LABELS) return MRF_ERR_BAD_LABELS;
@@ -1096,7 +1122,7 @@ int mrf_softmin_l1(int64_t n_pixels, int32_t L, const float *cost, const float *
     MrfLossParams Q;
     memset(&Q, 0, sizeof(Q));
     Q.N = n_pixels; Q.L = L; Q.cost = cost; Q.target = target; Q.mask = mask;
-    Q.disparity = disparity; Q.grad_cost = grad_cost;
+    Q.disparity = disparity; Q.grad_cost = grad_cost; Q.beta = beta;
     Q.count = (long long *)workspace;
     Q.partial = (double *)((char *)workspace + kAlign);
     Q.cpartial = (long long *)((char *)workspace + kAlign + sizeof(double) * MRF_HEAD_BLOCKS);

@@ -50,6 +50,8 @@ struct MrfFwdParams {
     signed char n_pre[MRF_MAXR], n_src[MRF_MAXR];
     signed char rm_slot[MRF_MAXR];         // position of r^- in src_dir[r], or -1 (term absent / still 0)
     int NW;                                // wavefronts per workgroup = ceil(L / MCH)
+    int sgm_std;                           // standard single-pass SGM (Eq. sgm_old): the message carries the node's own
+                                           // unary, m^r_i = theta_i + min_mu (m^r_{i-r} + theta_{i-r,i}); mrf_fwd_sweep only
 };
 
 // LP: labels per lane; MCH: source labels per wavefront; RMAX: bound on 1 + n_src;
@@ -93,7 +95,10 @@ mrf_fwd_sweep(const MrfFwdParams P)
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
     const float vz = mrf_opaque_zero_f();     // keeps the flags below in vector registers
-    src[0] = P.unary;
+    // standard SGM adds the unary of node i itself after the minimum (Eq. sgm_old): slot 0 then
+    // holds theta_i, one node further along the scanline, instead of theta_{i-r}
+    const bool sgm_std = !TRWP && P.sgm_std;
+    src[0] = P.unary + (sgm_std ? nstep * L : 0);
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
@@ -128,7 +133,8 @@ mrf_fwd_sweep(const MrfFwdParams P)
         for (int s = 0; s < LP; ++s) {
             const int lam = lane + 64 * s;
             if (lam < L) {
-                P.m_out[((size_t)r * N + head) * L + lam] = 0.0f;
+                // (standard SGM: with nothing before it, the first node's message is its unary)
+                P.m_out[((size_t)r * N + head) * L + lam] = sgm_std ? P.unary[(size_t)head * L + lam] : 0.0f;
                 P.p[((size_t)r * N + head) * L + lam] = 0;
             }
         }
@@ -165,7 +171,8 @@ mrf_fwd_sweep(const MrfFwdParams P)
 
     float carry[LP];   // normalised message of this direction at the previous node
 #pragma unroll
-    for (int s = 0; s < LP; ++s) carry[s] = 0.0f;
+    for (int s = 0; s < LP; ++s)
+        carry[s] = (sgm_std && lane + 64 * s < L) ? P.unary[(size_t)head * L + lane + 64 * s] : 0.0f;
     int buf = 0, turn = 0;
 
     for (int n0 = 1; n0 < len; n0 += D) {
@@ -202,6 +209,8 @@ mrf_fwd_sweep(const MrfFwdParams P)
                     v = v + carry[s];
 #pragma unroll
                     for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                    // Eq. sgm_old: the previous message alone (it holds theta_{i-r} already)
+                    v = sgm_std ? carry[s] : v;
                 }
                 a[s] = v;
             }
@@ -269,6 +278,10 @@ mrf_fwd_sweep(const MrfFwdParams P)
                 for (int s = 0; s < LP; ++s) { tv[s] = best[s]; tp[s] = bidx[s]; }
             }
 
+            if (sgm_std) {
+#pragma unroll
+                for (int s = 0; s < LP; ++s) tv[s] = cur[u][0][s] + tv[s];     // theta_i + min_mu (...)
+            }
             // ---- q = lowest argmin over lambda, reparametrisation (Eq. isgmr-norm) ----
             float mn = INFINITY;
 #pragma unroll
@@ -466,6 +479,7 @@ mrf_fwd_sweep_edge(const MrfFwdParams P)
 struct MrfAggParams {
     long long N;
     int L, R;
+    int no_unary;        // Eq. isgmr-aggregation-old (standard SGM): c_i = sum_r m^r_i
     const float *unary, *m;
     float *cost;
     uint8_t *labels;     // may be NULL
@@ -485,7 +499,7 @@ __global__ void __launch_bounds__(256) mrf_aggregate(const MrfAggParams P)
             const int lam = lane + 64 * s;
             c[s] = INFINITY;
             if (lam < L) {
-                float v = P.unary[(size_t)i * L + lam];
+                float v = P.no_unary ? 0.0f : P.unary[(size_t)i * L + lam];
                 for (int d = 0; d < P.R; ++d) v = v + P.m[((size_t)d * P.N + i) * L + lam];
                 c[s] = v;
                 P.cost[(size_t)i * L + lam] = v;

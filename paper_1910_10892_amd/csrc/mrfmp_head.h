@@ -103,6 +103,7 @@ struct MrfLossParams {
     double *partial;         // [MRF_HEAD_BLOCKS] sums of |d - g|
     long long *count;        // number of counted pixels (written by mrf_count_mask, or N)
     long long *cpartial;     // [MRF_HEAD_BLOCKS]
+    double beta;             // 0: standard L1; > 0: smooth L1 with this threshold
 };
 
 __global__ void mrf_set_i64(long long *dst, long long v)
@@ -166,10 +167,13 @@ __global__ void __launch_bounds__(256) mrf_softmin_l1_kernel(const MrfLossParams
         const double g = (double)P.target[i];
         const bool counts = P.mask ? P.mask[i] != 0 : true;
         const double diff = d - g;
-        if (counts) acc += fabs(diff);
+        // per-pixel loss l(d - g) and its slope: |x| and sign(x), or for smooth L1 x^2 / (2 beta) and
+        // x / beta inside |x| < beta, |x| - beta / 2 and sign(x) outside
+        const bool small = P.beta > 0.0 && fabs(diff) < P.beta;
+        if (counts) acc += small ? diff * diff / (2.0 * P.beta) : fabs(diff) - 0.5 * P.beta;
         if (lane == 0 && P.disparity) P.disparity[i] = (float)d;
         if (P.grad_cost) {
-            const double sgn = counts ? (diff > 0.0 ? 1.0 : (diff < 0.0 ? -1.0 : 0.0)) : 0.0;
+            const double sgn = counts ? (small ? diff / P.beta : (diff > 0.0 ? 1.0 : (diff < 0.0 ? -1.0 : 0.0))) : 0.0;
             const double k = sgn * inv_n / se;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {

@@ -42,6 +42,7 @@ class _CProblem(ctypes.Structure):
         ("trunc", ctypes.c_float), ("scale", ctypes.c_float),
         ("rho_edge", ctypes.c_void_p),
         ("pairwise_edge", ctypes.c_void_p),
+        ("sgm_standard", ctypes.c_int32),
     ]
 
 
@@ -100,6 +101,8 @@ def load_library():
     lib.mrf_softmin_l1_workspace_bytes.argtypes = []
     lib.mrf_softmin_l1.restype = ci
     lib.mrf_softmin_l1.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.mrf_softmin_smooth_l1.restype = ci
+    lib.mrf_softmin_smooth_l1.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, sz, vp]
     lib.mrf_strerror.argtypes = [ci]
     lib.mrf_version.restype = ctypes.c_char_p
     lib.mrf_set_sweep_events.restype = ci
@@ -138,6 +141,7 @@ class MrfProblem:
     shape: Optional[tuple] = None  # (B,H,W,L); taken from unary when given
     rho_edge: object = None       # [R,B,H,W] float32 GPU tensor or None (TRWP: rho per directed edge)
     pairwise_edge: object = None  # [R,B,H,W,L,L] float32 GPU tensor or None (pairwise potentials per edge)
+    sgm_standard: bool = False    # standard single-pass SGM (Eq. sgm_old) instead of the revised update; forward, K = 1
 
     def __post_init__(self):
         if self.shape is None:
@@ -164,6 +168,7 @@ class MrfProblem:
         c.trunc, c.scale = float(self.trunc), float(self.scale)
         c.rho_edge = _dev_ptr(self.rho_edge, "float32")
         c.pairwise_edge = _dev_ptr(self.pairwise_edge, "float32")
+        c.sgm_standard = 1 if self.sgm_standard else 0
         return c
 
 
@@ -314,3 +319,15 @@ def mrf_softmin_l1(cost, target, mask, disparity, loss, grad_cost, workspace, st
                                        _dev_ptr(workspace), _ws_size(workspace), _stream_handle(stream))
     if rc != 0:
         raise MrfError(rc, "mrf_softmin_l1")
+
+
+def mrf_softmin_smooth_l1(cost, target, mask, beta, disparity, loss, grad_cost, workspace, stream=None):
+    """mrf_softmin_l1 with the smooth L1 loss (threshold beta > 0)."""
+    L = int(cost.shape[-1])
+    n = int(cost.numel() // L)
+    rc = load_library().mrf_softmin_smooth_l1(n, L, _dev_ptr(cost, "float32"), _dev_ptr(target, "float32"),
+                                              _dev_ptr(mask, "uint8"), ctypes.c_float(beta), _dev_ptr(disparity, "float32"),
+                                              _dev_ptr(loss, "float64"), _dev_ptr(grad_cost, "float32"),
+                                              _dev_ptr(workspace), _ws_size(workspace), _stream_handle(stream))
+    if rc != 0:
+        raise MrfError(rc, "mrf_softmin_smooth_l1")

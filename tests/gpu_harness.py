@@ -38,7 +38,8 @@ class GpuProblem:
         self.rho_edge = t(getattr(pr, "rho_edge", None))
         self.prob = mrf.MrfProblem(self.unary, self.pairwise, pr.dirs, K, self.edge_weight,
                                    pr.edge_weight_scalar, pr.rho, pr.pairwise_kind, pr.trunc, pr.scale,
-                                   rho_edge=self.rho_edge, pairwise_edge=self.pairwise_edge)
+                                   rho_edge=self.rho_edge, pairwise_edge=self.pairwise_edge,
+                                   sgm_standard=bool(getattr(pr, "sgm_standard", False)))
         self.cost = torch.empty((B, H, W, L), dtype=torch.float32, device=dev)
         self.labels = torch.empty((B, H, W), dtype=torch.uint8, device=dev)
         self.p = torch.empty((K, R, B, H, W, L), dtype=torch.uint8, device=dev)

@@ -73,6 +73,10 @@ def test_validation_codes_without_gpu():
     assert V(_cprob(pairwise_kind=2, trunc=2.0, scale=float("nan"))) == -7
     assert V(_cprob(pairwise_kind=1, trunc=2.0, scale=0.0)) == 0
     assert V(_cprob(pairwise_kind=3, trunc=2.0, scale=-1.0)) == 0     # kind 3 does not use scale
+    # standard SGM: one pass of the ISGMR sweeps, no TRWP form, no per-edge tables
+    assert V(_cprob(sgm_standard=1, K=1)) == 0
+    assert V(_cprob(sgm_standard=1, K=2)) == -8
+    assert V(_cprob(sgm_standard=1, K=1), 1) == -8
     assert lib.mrf_validate(None, 0) == -1
     for code in range(0, -11, -1):
         assert mrf.mrf_strerror(code) != "unknown status"

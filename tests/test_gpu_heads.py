@@ -75,6 +75,37 @@ def test_energy_of_the_labelling_the_sweeps_return():
     np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-12, atol=1e-9)
 
 
+@pytest.mark.parametrize("index,crop", [(2, (24, 40)), (4, (10, 12))])
+@pytest.mark.parametrize("algo", ["isgmr", "trwp"])
+def test_energy_minimisation_protocol_on_crops(oracle, index, crop, algo):
+    """The protocol of the energy tables of Sec. 5.1 on synthetic stand-ins: run K = 1 and K = 50
+    iterations, take the labelling, evaluate its energy.  Labels against the oracle's forward pass,
+    the energy of those labels against the fp64 definition (the tables' own numbers need the
+    paper's datasets: parity with them is unpinned)."""
+    import torch
+    import paper_1910_10892_amd as mrf
+    from oracle import mrf_heads_oracle as ho
+    energies = {}
+    for K in (1, 50):
+        print("case energy protocol", index, crop, algo, K, flush=True)
+        pr = make_config(index, crop=crop, algo=algo, K=K)
+        g = _gpu_problem(pr)
+        g.forward()
+        f = oracle.forward(pr.algo, pr.unary, pr.pairwise, pr.dirs, pr.K, edge_weight=pr.edge_weight,
+                           edge_weight_scalar=pr.edge_weight_scalar, rho=pr.rho, threads=True)
+        labels = g.labels.cpu().numpy()
+        np.testing.assert_array_equal(labels, f.labels)
+        ws = torch.empty(mrf.mrf_energy_workspace_bytes(g.prob), dtype=torch.uint8, device="cuda:0")
+        out = torch.empty((pr.shape[0],), dtype=torch.float64, device="cuda:0")
+        mrf.mrf_energy(g.prob, g.labels, out, ws)
+        ref = ho.energy(pr.unary, pr.pairwise, pr.dirs, f.labels, edge_weight=pr.edge_weight,
+                        edge_weight_scalar=pr.edge_weight_scalar)
+        np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-12, atol=1e-9)
+        energies[K] = float(ref.sum())
+    print("  energies", energies, flush=True)
+    assert np.isfinite(list(energies.values())).all()
+
+
 @pytest.mark.parametrize("n,L,masked", [(1, 1, False), (37, 2, False), (1000, 96, True), (513, 200, True),
                                         (4099, 21, False), (64, 256, True)])
 def test_softmin_l1_matches_oracle(n, L, masked):
@@ -97,6 +128,35 @@ def test_softmin_l1_matches_oracle(n, L, masked):
     np.testing.assert_allclose(disp.cpu().numpy(), d, rtol=1e-5, atol=1e-4)
     np.testing.assert_allclose(loss.cpu().numpy()[0], l, rtol=1e-9, atol=1e-12)
     np.testing.assert_allclose(grad.cpu().numpy(), gr, rtol=1e-5, atol=1e-7 / max(n, 1) + 1e-12)
+
+
+@pytest.mark.parametrize("n,L,masked,beta", [(1000, 96, True, 1.0), (513, 21, False, 0.25), (64, 256, True, 3.0)])
+def test_softmin_smooth_l1_matches_oracle(n, L, masked, beta):
+    import torch
+    import paper_1910_10892_amd as mrf
+    from oracle import mrf_heads_oracle as ho
+    print("case softmin smooth l1", n, L, masked, beta, flush=True)
+    rng = np.random.default_rng(950 + n + L)
+    cost = rng.normal(0.0, 3.0, (n, L)).astype(np.float32)
+    d0, _, _ = ho.softmin_l1(cost, np.zeros(n))
+    # targets on both sides of the threshold |d - g| = beta
+    target = (d0 + rng.uniform(-3.0 * beta, 3.0 * beta, n)).astype(np.float32)
+    mask = (rng.random(n) > 0.25).astype(np.uint8) if masked else None
+    ws = torch.empty(mrf.mrf_softmin_l1_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
+    disp = torch.full((n,), float("nan"), device="cuda:0")
+    grad = torch.full((n, L), float("nan"), device="cuda:0")
+    loss = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    mrf.mrf_softmin_smooth_l1(torch.from_numpy(cost).cuda(), torch.from_numpy(target).cuda(),
+                              None if mask is None else torch.from_numpy(mask).cuda(), beta, disp, loss, grad, ws)
+    d, l, gr = ho.softmin_l1(cost, target, mask, beta=beta)
+    np.testing.assert_allclose(disp.cpu().numpy(), d, rtol=1e-5, atol=1e-4)
+    # (the regressed disparity carries the single-precision exponential: about 1e-6 relative)
+    np.testing.assert_allclose(loss.cpu().numpy()[0], l, rtol=1e-5, atol=1e-7)
+    # (inside the threshold the slope (d - g) / beta inherits the absolute error of d, about 1e-7 L)
+    np.testing.assert_allclose(grad.cpu().numpy(), gr, rtol=1e-4, atol=2e-4 / max(n, 1))
+    with pytest.raises(mrf.MrfError):
+        mrf.mrf_softmin_smooth_l1(torch.from_numpy(cost).cuda(), torch.from_numpy(target).cuda(), None, 0.0, disp, loss,
+                                  grad, ws)
 
 
 def test_heads_reject_bad_arguments():

@@ -517,6 +517,51 @@ def test_full_size_stereo_config_trwp(oracle):
         check_backward(g, b32, b64, want_V)
 
 
+SGM_STD_CASES = [
+    # seed, B, H, W, L, dirs, integer_valued, per_edge, kind (0 dense table, 3 SGM penalties)
+    (501, 1, 6, 9, 16, DIRS8, False, True, 3),
+    (502, 2, 5, 7, 70, DIRS4, True, True, 3),        # integer data: ties in both argmins
+    (503, 1, 4, 6, 130, DIRS16, False, False, 3),
+    (504, 1, 7, 5, 21, DIRS8, False, True, 0),       # general dense table
+    (505, 1, 1, 9, 200, DIRS4, True, True, 3),       # one row
+    (506, 1, 3, 3, 256, DIRS8, False, True, 0),
+    (507, 1, 5, 5, 1, DIRS4, False, True, 0),
+]
+
+
+@pytest.mark.parametrize("case", SGM_STD_CASES, ids=lambda c: "seed%d" % c[0])
+def test_standard_single_pass_sgm(oracle, case):
+    """The standard SGM update (Eq. sgm_old: the message carries the node's own unary) and its
+    aggregation (Eq. isgmr-aggregation-old) as a problem flag: forward outputs against the oracle;
+    the backward entry points refuse the flag."""
+    import torch
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import GpuProblem
+    from mrf_inputs import sgm_penalties
+    print("case standard sgm", case, flush=True)
+    seed, B, H, W, L, dirs, iv, pe, kind = case
+    pr = random_problem(seed, "isgmr", B, H, W, L, dirs, 1, integer_valued=iv, per_edge=pe, symmetric=False)
+    if kind == 3:
+        pr.pairwise = sgm_penalties(L, 1.0 if iv else 0.3, 2.0 if iv else 1.7)
+        pr.pairwise_kind, pr.trunc, pr.scale = 3, 2.0, 1.0
+    pr.sgm_standard = True
+    g = GpuProblem(pr)
+    g.poison_outputs()
+    g.forward()
+    got = g.results(backward=False)
+    f = oracle.sgm_standard_forward(pr.unary, pr.pairwise, pr.dirs, edge_weight=pr.edge_weight,
+                                    edge_weight_scalar=pr.edge_weight_scalar)
+    check_forward(got, f)
+    np.testing.assert_array_equal(got.messages, f.messages)
+    np.testing.assert_array_equal(got.cost, f.cost)
+    with pytest.raises(mrf.MrfError) as ei:
+        g.backward()
+    assert ei.value.status == -8
+    # more than one iteration has no meaning for a single-pass method
+    g.prob.K = 2
+    assert mrf.mrf_validate(g.prob, mrf.MRF_ISGMR) == -8
+
+
 def _progress(msg):
     """Long tests say where they are: on stdout and, where a GPU job's output folder exists, in
     a file there (a run that is silent for minutes is taken for hung)."""
