@@ -58,7 +58,8 @@ typedef enum {
     MRF_ERR_BAD_PAIRWISE_KIND = -7, /* unknown pairwise_kind, trunc <= 0 for kinds 1-3, or scale < 0 for kinds 1, 2 */
     MRF_ERR_BAD_ALGORITHM = -8,     /* algo argument is neither MRF_ISGMR nor MRF_TRWP */
     MRF_ERR_HIP = -9,               /* a HIP runtime call or kernel launch failed */
-    MRF_ERR_SCRATCH_LIMIT = -10     /* the problem exceeds the fixed scratch of a no-allocation entry point */
+    MRF_ERR_SCRATCH_LIMIT = -10,    /* the problem exceeds the fixed scratch of a no-allocation entry point */
+    MRF_ERR_WAIT_EXPIRED = -11      /* reported by mrf_workspace_fault: a wait between wavefronts ran out */
 } mrf_status;
 
 enum { MRF_ISGMR = 0, MRF_TRWP = 1 };
@@ -226,6 +227,16 @@ int mrf_softmin_smooth_l1(int64_t n_pixels, int32_t L, const float *cost, const 
                           float beta, float *disparity, double *loss, float *grad_cost, void *workspace,
                           size_t workspace_bytes, void *hip_stream);
 
+/* Some sweep layouts spread a scanline over several wavefronts that hand nodes to each other
+ * through rings in on-chip memory.  A wavefront that still finds itself waiting for another four
+ * seconds after its workgroup started (sweeps take milliseconds) ends at once, those that wait for it
+ * follow, and it raises a word in the first 256 bytes of the workspace, which every forward / backward call
+ * clears when it starts.  This call waits for `hip_stream` to drain, reads that word and returns
+ * MRF_OK, or MRF_ERR_WAIT_EXPIRED if the last call on this workspace was cut short (its outputs
+ * are then incomplete; with correct kernels this never happens), or MRF_ERR_NULL_POINTER /
+ * MRF_ERR_HIP.  Synchronous; workspace is the DEVICE pointer the call was given. */
+int mrf_workspace_fault(const void *workspace, void *hip_stream);
+
 /* Static text for a status code. */
 const char *mrf_strerror(int status);
 
@@ -274,6 +285,12 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           1 = never, 2 = always
  *   knob 12: in the sweep of knob 6, sum the lanes of the most popular scatter target in registers
  *           (truncated models): 0 = by launch shape, 1 = never, 2 = whenever V is not a dense table
+ *   knob 13: three scanlines per wavefront (segments of 21 lanes) in the sweeps of knob 3 for 17..21 labels:
+ *           0 = by launch size, 1 = never (two per wavefront), 2 = always
+ *   knob 14: microseconds after the start of a workgroup beyond which a wavefront that still finds itself
+ *           waiting for another gives up (see mrf_workspace_fault): 0 = default (4 s); 1 makes the
+ *           multi-wavefront layouts give up almost at once (for tests of that path: every kernel still ends
+ *           normally)
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

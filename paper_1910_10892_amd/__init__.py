@@ -9,5 +9,5 @@ from .mrfmp import (  # noqa: F401
     mrf_strerror,
     mrf_last_error_detail, mrf_last_sweep_kernel, mrf_last_sweep_launch,
     mrf_energy, mrf_energy_noalloc, mrf_energy_workspace_bytes, mrf_softmin_l1, mrf_softmin_smooth_l1, mrf_softmin_l1_workspace_bytes,
-    mrf_trwp_backward, mrf_trwp_forward, mrf_tune, mrf_validate, mrf_version, mrf_workspace_bytes,
+    mrf_trwp_backward, mrf_trwp_forward, mrf_tune, mrf_workspace_fault, mrf_validate, mrf_version, mrf_workspace_bytes,
 )

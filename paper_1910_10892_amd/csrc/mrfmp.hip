@@ -119,6 +119,8 @@ MRF_G(int g_tune_duo_ni, 0);     // index wavefronts per scanline: 0 auto, 1, 2
 MRF_G(int g_tune_loader, 0);     // loader wavefront in the window sweep: 0 auto, 1 never, 2 whenever possible
 MRF_G(int g_tune_squad, 0);      // index wavefronts next to the split layout: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
+MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
+MRF_G(int g_tune_spin_limit, 0); // turns a wait between wavefronts may take: 0 = default
 MRF_G(int g_tune_pack_idx, 0);   // index wavefronts in the packed dense sweep: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_chain, 0);      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
 MRF_G(int g_tune_chain_hot, 0);  // its pre-reduction of the most popular scatter target: 0 auto, 1 never, 2 whenever V is no dense table
@@ -149,6 +151,15 @@ inline void note_launch(int backward, const char *name, long long grid, int bloc
     va_end(ap);
     snprintf(g_last_launch[backward], sizeof(g_last_launch[backward]), "%s<%s> grid=%lld block=%d", name, args, grid, block);
 }
+
+// Workspace header (the first 256 bytes): float [0] = the scalar edge weight, int at byte 128 = the
+// fault word that a wait between wavefronts raises when it runs out (mrf_wait_again).
+constexpr size_t kFaultOffset = 128;
+// how long after its start a workgroup may still find one of its wavefronts waiting for another, in microseconds
+// (sweeps take milliseconds)
+constexpr int kSpinLimit = 4000000;
+inline int spin_limit() { return g_tune_spin_limit > 0 ? g_tune_spin_limit : kSpinLimit; }
+hipError_t init_header(void *workspace, float w_scalar, hipStream_t st);
 
 // records which call failed and how, for mrf_last_error_detail
 inline int hip_fail(hipError_t e, const char *what)
@@ -351,12 +362,17 @@ hipError_t launch_packed_mu(const MrfFwdParams &P, int algo, int rmax, long long
 template <int SEG>
 hipError_t launch_packed(const MrfFwdParams &P, int algo, int rmax, long long scanlines, hipStream_t st)
 {
-    // source labels per node: L rounded up to a multiple of four
-    const int mu = (P.g.L + 3) / 4 * 4;
-    if (mu <= SEG - 12) return launch_packed_mu<SEG, SEG - 12>(P, algo, rmax, scanlines, st);
-    if (mu <= SEG - 8) return launch_packed_mu<SEG, SEG - 8>(P, algo, rmax, scanlines, st);
-    if (mu <= SEG - 4) return launch_packed_mu<SEG, SEG - 4>(P, algo, rmax, scanlines, st);
-    return launch_packed_mu<SEG, SEG>(P, algo, rmax, scanlines, st);
+    // three scanlines of up to 21 labels per wavefront: always 24 source labels
+    if constexpr (SEG == 21) {
+        return launch_packed_mu<21, 24>(P, algo, rmax, scanlines, st);
+    } else {
+        // source labels per node: L rounded up to a multiple of four
+        const int mu = (P.g.L + 3) / 4 * 4;
+        if (mu <= SEG - 12) return launch_packed_mu<SEG, SEG - 12>(P, algo, rmax, scanlines, st);
+        if (mu <= SEG - 8) return launch_packed_mu<SEG, SEG - 8>(P, algo, rmax, scanlines, st);
+        if (mu <= SEG - 4) return launch_packed_mu<SEG, SEG - 4>(P, algo, rmax, scanlines, st);
+        return launch_packed_mu<SEG, SEG>(P, algo, rmax, scanlines, st);
+    }
 }
 
 hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
@@ -373,6 +389,10 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
             if (P.n_src[r] > ms) ms = P.n_src[r];
         const int rmax = (ms + 1 <= 4) ? 4 : ((ms + 1 <= 8) ? 8 : 16);
         P.NW = 1;
+        // 17..21 labels (the 21 classes of the segmentation shape): three scanlines per wavefront once the
+        // launch has wavefronts to spare, else two (a latency-bound launch gains nothing from fewer wavefronts)
+        if (P.g.L > 16 && P.g.L <= 21 && g_tune_pack3 != 1 && (g_tune_pack3 == 2 || blocks >= 3072))
+            return launch_packed<21>(P, algo, rmax, blocks, st);
         return P.g.L <= 16 ? launch_packed<16>(P, algo, rmax, blocks, st) : launch_packed<32>(P, algo, rmax, blocks, st);
     }
     if (tw > 0) {
@@ -506,12 +526,12 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     float *scal = (float *)workspace;
     float *bufA = (float *)((char *)workspace + kAlign);
     float *bufB = (float *)((char *)workspace + kAlign + msg_bytes(pr));
+    // header: the scalar weight (read through the same vector loads as per-edge weights) and the fault word
+    { const hipError_t e_ = init_header(workspace, pr->edge_weight_scalar, st); if (e_ != hipSuccess) return hip_fail(e_, "init_header"); }
+    P.fault = (int *)((char *)workspace + kFaultOffset);
+    P.spin_limit = spin_limit();
     if (pr->edge_weight) { P.w = pr->edge_weight; P.w_mul = 1; }
-    else {
-        // a scalar weight is read through the same vector loads as per-edge weights
-        { const hipError_t e_ = fill(scal, 1, pr->edge_weight_scalar, st); if (e_ != hipSuccess) return hip_fail(e_, "fill"); }
-        P.w = scal; P.w_mul = 0;
-    }
+    else { P.w = scal; P.w_mul = 0; }
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
     float *final_m = nullptr;
     const int tw = window_width(pr);
@@ -719,7 +739,13 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     // few labels: several scanlines per wavefront, once there are enough of them
     if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
         !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= 1024)))
+    {
+        // three scanlines per wavefront: measured slower than two on the segmentation shape (the LDS
+        // scatter, not instruction issue, bounds this sweep), so only on request
+        if (L > 16 && L <= 21 && g_tune_pack3 == 2)
+            return launch_bwd_packed<21>(P, ns, st);
         return L <= 16 ? launch_bwd_packed<16>(P, ns, st) : launch_bwd_packed<32>(P, ns, st);
+    }
     if (chain) {
         // truncated models: the chain wavefront sums the lanes of the most popular scatter target
         // in registers
@@ -809,11 +835,11 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     float *buf0 = (float *)(ws + kAlign);                   // ISGMR: grad m-hat   TRWP: s per direction
     float *buf1 = (float *)(ws + kAlign + msg_bytes(pr));   // ISGMR: s per direction
     double *gvslots = (double *)(ws + kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(pr));
+    { const hipError_t e_ = init_header(workspace, pr->edge_weight_scalar, st); if (e_ != hipSuccess) return hip_fail(e_, "init_header"); }
+    P.fault = (int *)(ws + kFaultOffset);
+    P.spin_limit = spin_limit();
     if (pr->edge_weight) { P.w = pr->edge_weight; P.w_mul = 1; }
-    else {
-        { const hipError_t e_ = fill(scal, 1, pr->edge_weight_scalar, st); if (e_ != hipSuccess) return hip_fail(e_, "fill"); }
-        P.w = scal; P.w_mul = 0;
-    }
+    else { P.w = scal; P.w_mul = 0; }
 
     if (grad_w) {
         const hipError_t e_ = fill(grad_w, (long long)R * N, 0.0f, st);
@@ -919,6 +945,15 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
 }  // namespace mrf_host
 
 #if MRF_HAS_API
+namespace mrf_host {
+hipError_t init_header(void *workspace, float w_scalar, hipStream_t st)
+{
+    hipLaunchKernelGGL(mrf_init_header, dim3(1), dim3(64), 0, st, (float *)workspace,
+                       (int *)((char *)workspace + kFaultOffset), w_scalar);
+    return hipGetLastError();
+}
+}  // namespace mrf_host
+
 using namespace mrf_host;
 
 extern "C" {
@@ -1011,6 +1046,7 @@ const char *mrf_strerror(int status)
     case MRF_ERR_BAD_PAIRWISE_KIND: return "unknown pairwise_kind, invalid trunc or negative scale";
     case MRF_ERR_BAD_ALGORITHM: return "algo must be MRF_ISGMR or MRF_TRWP";
     case MRF_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    case MRF_ERR_WAIT_EXPIRED: return "a wait between wavefronts of a sweep ran out of its budget: the results of that call are incomplete";
     case MRF_ERR_SCRATCH_LIMIT: return "problem exceeds the fixed scratch of a no-allocation entry point (batch > 64)";
     default: return "unknown status";
     }
@@ -1145,6 +1181,19 @@ static int softmin_loss(int64_t n_pixels, int32_t L, const float *cost, const fl
     return MRF_OK;
 }
 
+// Which forward or backward call used this workspace last, did one of its waits between
+// wavefronts run out?  Waits for the stream, then reads the fault word of the header.
+int mrf_workspace_fault(const void *workspace, void *hip_stream)
+{
+    if (!workspace) return MRF_ERR_NULL_POINTER;
+    hipStream_t st = (hipStream_t)hip_stream;
+    { const hipError_t e_ = hipStreamSynchronize(st); if (e_ != hipSuccess) return hip_fail(e_, "hipStreamSynchronize"); }
+    int word = 0;
+    { const hipError_t e_ = hipMemcpy(&word, (const char *)workspace + kFaultOffset, sizeof(int), hipMemcpyDeviceToHost);
+      if (e_ != hipSuccess) return hip_fail(e_, "hipMemcpy"); }
+    return word != 0 ? MRF_ERR_WAIT_EXPIRED : MRF_OK;
+}
+
 const char *mrf_last_error_detail(void) { return g_error_detail; }
 
 const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ? 1 : 0]; }
@@ -1174,6 +1223,8 @@ int mrf_tune(int knob, int value)
     if (knob == 9) { g_tune_squad = value; return MRF_OK; }
     if (knob == 11) { g_tune_pack_idx = value; return MRF_OK; }
     if (knob == 10) { g_tune_squad_ni = value; return MRF_OK; }
+    if (knob == 13) { g_tune_pack3 = value; return MRF_OK; }
+    if (knob == 14) { g_tune_spin_limit = value > 0 ? value : 0; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

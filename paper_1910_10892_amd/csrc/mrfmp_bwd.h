@@ -74,6 +74,8 @@ struct MrfBwdParams {
     float *gE;                             // [R][N][L][L] gradient of per-edge pairwise tables (zeroed by the host,
                                            // accumulated over iterations), or NULL; mrf_bwd_sweep<..., RHOE> only
     int force_plain;                       // the problem has no V: only mrf_bwd_sweep may run
+    int *fault;                            // launch-wide word raised when a wait between wavefronts is given up (mrf_wait_turn)
+    int spin_limit;                        // microseconds after which a wait is given up
 };
 
 #define MRF_BWD_WAVES 4   // wavefronts (= scanlines in flight) per workgroup
@@ -83,9 +85,10 @@ struct MrfBwdParams {
 __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L, bool with_theta, bool vg, bool gv)
 {
     const size_t NR = 2 * (size_t)NI, LL = 64 * (size_t)LP;
-    return sizeof(double) * (3 * NR * LL + LL + (gv ? (size_t)NI * L * L : 0)) +
-           sizeof(float) * (with_theta ? NR * LL : 0) + sizeof(int) * (3 * MRF_CHAIN_MAX_HELPERS + 1) +
-           sizeof(float) * (gv ? (size_t)L * L : (vg ? 0 : (size_t)L)) + NR * LL;
+    const size_t arrays = sizeof(double) * (3 * NR * LL + LL + (gv ? (size_t)NI * L * L : 0)) +
+                          sizeof(float) * (with_theta ? NR * LL : 0) + sizeof(int) * (3 * MRF_CHAIN_MAX_HELPERS + 1) +
+                          sizeof(float) * (gv ? (size_t)L * L : (vg ? 0 : (size_t)L)) + NR * LL;
+    return (arrays + 7) / 8 * 8 + sizeof(MrfWaitBlock);      // the deadline of the waits sits behind the arrays
 }
 
 // LP labels per lane, NS source slots, D prefetch distance, VG: V for the edge-weight
@@ -453,6 +456,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     int *a_hot = chain_done + 1;                                 // [NR] pre -> chain: most popular scatter target, or -1
     float *vl = reinterpret_cast<float *>(a_hot + 2 * MRF_CHAIN_MAX_HELPERS);   // [L] first row of V (unless VG), all of V (GV)
     uint8_t *a_p = reinterpret_cast<uint8_t *>(vl + (GV ? P.g.L * P.g.L : (VG ? 0 : P.g.L)));   // [NR][LL]
+    MrfWaitBlock &wait_lds = *reinterpret_cast<MrfWaitBlock *>(
+        mrf_bsmem + ((a_p + NR * LL - mrf_bsmem) + 7) / 8 * 8);  // for the waits below (mrf_wait_turn)
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
@@ -465,7 +470,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
         for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
     }
     if (threadIdx.x < MRF_CHAIN_MAX_HELPERS) pre_done[threadIdx.x] = (int)threadIdx.x - NI;
-    if (threadIdx.x == 0) *chain_done = -1;
+    if (threadIdx.x == 0) { *chain_done = -1; mrf_wait_init(&wait_lds, P.fault, P.spin_limit); }
     for (int e = threadIdx.x; e < LL; e += blockDim.x) sbuf[e] = 0.0;
     __syncthreads();
 
@@ -493,10 +498,11 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
         int pv[LP];
         auto await = [&](int u, int tt) {
             int sn;
+            int wait_turns = 0;
             do {
                 sn = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&pre_done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                if (sn < tt) __builtin_amdgcn_s_sleep(1);
+                if (sn < tt) mrf_wait_turn(&wait_lds, wait_turns);
             } while (sn < tt);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
         };
@@ -728,10 +734,11 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
             const int tp = tt - NI;
             if (tp >= 0 && tp < len) {
                 // ---- post(tp): what is left of node len-1-tp once the chain has passed --------
+                int wait_turns = 0;
                 while (chain_seen < tp) {
                     chain_seen = __builtin_amdgcn_readfirstlane(
                         __hip_atomic_load(chain_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                    if (chain_seen < tp) __builtin_amdgcn_s_sleep(1);
+                    if (chain_seen < tp) mrf_wait_turn(&wait_lds, wait_turns);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
                 const int slot = tp % NR;
@@ -995,9 +1002,37 @@ __global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
 // lanes, each replaying its own scanline (any direction, any length).  Label sums are DPP
 // row sums (plus one swizzle for 32-lane segments), the scatter vector and the V-gradient
 // accumulator are per segment in LDS.
+// sum over a segment of 21 lanes (three per wavefront, see mrf_seg21_upper): the upper and the lower
+// lanes of every row are summed apart, the previous row's upper sum joins this row's lower sum,
+// and the upper lanes fetch the result from the row after theirs; a fixed order
+__device__ inline double mrf_segment_sum21_f64(double v, int lane)
+{
+    const bool up = mrf_seg21_upper(lane);
+    double u = up ? v : 0.0, lo = up ? 0.0 : v;
+    u += mrf_dpp_f64<0xB1>(u);
+    lo += mrf_dpp_f64<0xB1>(lo);
+    u += mrf_dpp_f64<0x4E>(u);
+    lo += mrf_dpp_f64<0x4E>(lo);
+    u += mrf_dpp_f64<0x141>(u);
+    lo += mrf_dpp_f64<0x141>(lo);
+    u += mrf_dpp_f64<0x140>(u);
+    lo += mrf_dpp_f64<0x140>(lo);
+    const long long ub = __builtin_bit_cast(long long, u);
+    // row_bcast:15 into rows 1..3, zero for row 0
+    const int plo = __builtin_amdgcn_update_dpp(0, (int)(ub & 0xffffffffLL), 0x142, 0xE, 0xF, false);
+    const int phi = __builtin_amdgcn_update_dpp(0, (int)(ub >> 32), 0x142, 0xE, 0xF, false);
+    const double full = lo + __builtin_bit_cast(double, ((long long)phi << 32) | (long long)(unsigned)plo);
+    const int from = (up ? ((lane & 48) + 16) & 63 : lane) << 2;
+    const long long fb = __builtin_bit_cast(long long, full);
+    const int rlo = __builtin_amdgcn_ds_bpermute(from, (int)(fb & 0xffffffffLL));
+    const int rhi = __builtin_amdgcn_ds_bpermute(from, (int)(fb >> 32));
+    return __builtin_bit_cast(double, ((long long)rhi << 32) | (long long)(unsigned)rlo);
+}
+
 template <int SEG>
 __device__ inline double mrf_segment_sum_f64(double v)
 {
+    if (SEG == 21) return mrf_segment_sum21_f64(v, (int)(threadIdx.x & 63));
     v += mrf_dpp_f64<0xB1>(v);
     v += mrf_dpp_f64<0x4E>(v);
     v += mrf_dpp_f64<0x141>(v);
@@ -1018,8 +1053,10 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
     const int L = P.g.L;
     const int lane = threadIdx.x;
-    const int seg = lane / SEG, lam = lane % SEG;
-    const bool valid = lam < L;
+    // (three segments of 21 lanes leave lane 63 over: it shadows the last segment and stores nothing)
+    const bool lane_on = lane / SEG < NSEG;
+    const int seg = lane_on ? lane / SEG : NSEG - 1, lam = lane % SEG;
+    const bool valid = lane_on && lam < L;
     const int lc = valid ? lam : 0;
     const long long N = P.g.N;
     double *sbuf = reinterpret_cast<double *>(mrf_bsmem) + seg * SEG;                       // [NSEG][SEG]
@@ -1028,7 +1065,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     double *gVs = P.gV ? P.gV + ((size_t)blockIdx.x * NSEG + seg) * L * L : nullptr;
 
     for (int e = lane; e < L * L; e += 64) vl[e] = P.V[e];
-    if (gVs)
+    if (gVs && lane_on)
         for (int e = lam; e < L * L; e += SEG) gvl[e] = 0.0;
     sbuf[lam] = 0.0;
     __syncthreads();
@@ -1037,7 +1074,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     const long long npacks = (P.total_scanlines + NSEG - 1) / NSEG;
     for (long long pk = blockIdx.x; pk < npacks; pk += gridDim.x) {
         const long long sl = pk * NSEG + seg;
-        const bool act_seg = sl < P.total_scanlines;
+        const bool act_seg = lane_on && sl < P.total_scanlines;
 
         int r = P.r_first, nsc = 1, dh = 0, dw = 1, nsrc = 0;
         long long local = 0;
@@ -1181,7 +1218,8 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     }
     if (gVs) {
         mrf_wave_lds_fence();
-        for (int e = lam; e < L * L; e += SEG) gVs[e] += gvl[e];
+        if (lane_on)
+            for (int e = lam; e < L * L; e += SEG) gVs[e] += gvl[e];
     }
 }
 

@@ -303,6 +303,18 @@ __device__ inline double mrf_wave_sum_f64(double v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Three segments of 21 lanes (lanes 0-20, 21-41, 42-62; lane 63 idle) do not line up with the DPP
+// rows of 16.  Call the lanes of a row that belong to the segment that began in an earlier row its
+// lower part, the others its upper part (row 0 is all upper): segment s is the upper part of row s
+// plus the lower part of row s + 1.  Two row reductions (upper lanes only, lower lanes only), one
+// row_bcast:15 that brings the previous row's upper minimum to the lower lanes and completes the
+// segment minimum there, and one lane permutation that hands it back to the upper lanes of the
+// row before.
+__device__ inline bool mrf_seg21_upper(int lane)
+{
+    return lane < 16 || (lane >= 21 && lane < 32) || (lane >= 42 && lane < 48) || lane == 63;
+}
+
 // Orders this wavefront's LDS writes before its later LDS reads by other lanes (lanes of
 // one wavefront run in lock step; only the compiler and the LDS queue need telling).
 __device__ inline void mrf_wave_lds_fence()
@@ -310,6 +322,53 @@ __device__ inline void mrf_wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- bounded waits --------------------------------------------------------------------------------
+// Wavefronts of one workgroup that hand nodes to each other through LDS rings wait on counters
+// that only grow.  The workgroup notes a deadline (constant-rate clock, 100 MHz) in LDS when it
+// starts.  Only a wait that finds its condition unmet looks at the clock, so the wavefronts carry
+// nothing for this in registers and the path of a wait that need not wait is untouched.  Past the
+// deadline the waiting wavefront raises the launch's fault word in global memory (read by the host
+// once the stream has drained) and ends on the spot; whoever waits for it follows.  A slip in the
+// ring logic thus ends as an error code, not as a launch that never returns.
+struct MrfWaitBlock {
+    unsigned long long deadline;     // s_memrealtime ticks
+    int *fault;
+};
+
+__device__ inline void mrf_wait_init(MrfWaitBlock *w, int *fault, int budget_us)   // one thread, before the first barrier
+{
+    w->deadline = __builtin_amdgcn_s_memrealtime() + (unsigned long long)budget_us * 100ull;
+    w->fault = fault;
+}
+
+// Raises the fault word and ends the wavefront here.  Written as one opaque block of instructions,
+// not as a store and the compiler's "end of program": the compiler then sees neither a second way
+// out of the loops that wait nor anything that touches memory there, and the code it lays out for
+// the case that nobody has to wait stays as it is without the deadline (with a visible exit the
+// straight path of every wait picked up taken branches: 15 % on the launches that are bound by the
+// latency of one wavefront).
+__device__ inline void mrf_fault_and_end(int *fault)
+{
+    const int one = 1;
+    asm volatile("global_store_dword %0, %1, off\n\ts_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_endpgm" : : "v"(fault), "v"(one));
+}
+
+// The condition of a wait was found unmet: end this wavefront if the deadline has passed.
+__device__ inline void mrf_wait_check(const MrfWaitBlock *w)
+{
+    if (__builtin_expect(__builtin_amdgcn_s_memrealtime() > w->deadline, 0)) mrf_fault_and_end(w->fault);
+}
+
+// One turn of such a wait: sleep a little, the caller looks again.  The clock is looked at on the
+// 8th turn of a wait and every 64 turns from there (`turn` is a counter local to the wait): the
+// short waits of a pipeline that is running never touch it, and the time between two looks at the
+// awaited counter stays what it is without the deadline.
+__device__ inline void mrf_wait_turn(const MrfWaitBlock *w, int &turn)
+{
+    if ((++turn & 63) == 8) mrf_wait_check(w);
+    __builtin_amdgcn_s_sleep(1);
 }
 
 // A zero the compiler cannot see through: keeps wave-uniform addresses in vector loads, so

@@ -50,6 +50,8 @@ struct MrfFwdParams {
     signed char n_pre[MRF_MAXR], n_src[MRF_MAXR];
     signed char rm_slot[MRF_MAXR];         // position of r^- in src_dir[r], or -1 (term absent / still 0)
     int NW;                                // wavefronts per workgroup = ceil(L / MCH)
+    int *fault;                            // launch-wide word raised when a wait between wavefronts is given up (mrf_wait_turn)
+    int spin_limit;                        // microseconds after which a wait is given up
     int sgm_std;                           // standard single-pass SGM (Eq. sgm_old): the message carries the node's own
                                            // unary, m^r_i = theta_i + min_mu (m^r_{i-r} + theta_{i-r,i}); mrf_fwd_sweep only
 };
@@ -812,6 +814,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
         float ftab[TW + 1];
         int produced;                             // last step published
         int loaded;                               // last step the loader has published
+        MrfWaitBlock wait;                        // for the waits below (mrf_wait_turn)
         alignas(16) int consumed[4];              // per index wavefront: last step finished
         float lw[NRL];
         alignas(16) float lring[LOADER ? NRL : 1][5][LOADER ? LL : 1];   // partial sum, 3 messages, r- vector
@@ -856,7 +859,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     if ((int)threadIdx.x <= TW) ftab[threadIdx.x] = (int)threadIdx.x < TW ? P.V[(int)threadIdx.x < L ? threadIdx.x : L - 1] : fT;
     // padding and the entries of labels >= L are never written again: they never win a strict '<'
     for (int i = threadIdx.x; i < NR * HB; i += NT) (&ring[0][0])[i] = INFINITY;
-    if (threadIdx.x == 0) { produced = 0; loaded = 0; }
+    if (threadIdx.x == 0) { produced = 0; loaded = 0; mrf_wait_init(&sm.wait, P.fault, P.spin_limit); }
+    const MrfWaitBlock *const wait_block = &sm.wait;
     // index wavefront j takes steps 1 + j, 1 + j + NI, ...; "finished" starts one turn before
     if (threadIdx.x < 4) consumed[threadIdx.x] = (int)threadIdx.x + 1 - NI;
     __syncthreads();
@@ -884,10 +888,11 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
         const int istep_l = (int)nstep * L;
         int seen = 0;
         for (int n = 1 + jw; n < len; n += NI) {
+            int wait_turns = 0;
             while (seen < n) {
                 seen = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                if (seen < n) __builtin_amdgcn_s_sleep(1);
+                if (seen < n) mrf_wait_turn(wait_block, wait_turns);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
             const int slot = n & (NR - 1);
@@ -1053,10 +1058,11 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                 const int nn = n0 + u;
                 if (nn < len) {
                     // the slot was last read for step nn - NRL, before that step was published
+                    int wait_turns = 0;
                     while (pseen < nn - NRL) {
                         pseen = __builtin_amdgcn_readfirstlane(
                             __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                        if (pseen < nn - NRL) __builtin_amdgcn_s_sleep(1);
+                        if (pseen < nn - NRL) mrf_wait_turn(wait_block, wait_turns);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
                     const int ls = nn & (NRL - 1);
@@ -1124,10 +1130,11 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
         for (int c = 1; c < RMAX; ++c) after[c] = ((c > n_pre && c <= n_src) ? 1.0f : 0.0f) + vz;
         auto await_loader = [&](int nn) {
             int sn;
+            int wait_turns = 0;
             do {
                 sn = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&loaded, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                if (sn < nn) __builtin_amdgcn_s_sleep(1);
+                if (sn < nn) mrf_wait_turn(wait_block, wait_turns);
             } while (sn < nn);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
             return sn;
@@ -1142,6 +1149,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
         for (int nn = 1; nn < len; ++nn) {
             const int slot = nn & (NR - 1);
             float *hbuf = &ring[slot][TW];
+            int wait_turns = 0;
             while (__builtin_expect(freed < nn - NR, 0)) {
                 int lo = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
@@ -1152,7 +1160,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     lo = cj < lo ? cj : lo;
                 }
                 freed = lo + NI - 1;
-                if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+                if (freed < nn - NR) mrf_wait_turn(wait_block, wait_turns);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
@@ -1308,6 +1316,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
 
             // the slot was last used by step nn - NR (steps past the end publish nothing
             // and write nothing)
+            int wait_turns = 0;
             while (__builtin_expect(!past && freed < nn - NR, 0)) {
                 int lo = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
@@ -1318,7 +1327,7 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     lo = cj < lo ? cj : lo;
                 }
                 freed = lo + NI - 1;
-                if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+                if (freed < nn - NR) mrf_wait_turn(wait_block, wait_turns);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
@@ -1688,6 +1697,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
     __shared__ __align__(16) unsigned long long hmx[2][4];     // local minima of h
     __shared__ __align__(16) unsigned long long tmx[2][4];     // local minima of the new message (general path)
     __shared__ int produced;
+    __shared__ MrfWaitBlock wait_lds;             // for the waits below (mrf_wait_turn)
     __shared__ __align__(16) int consumed[8];
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
@@ -1723,7 +1733,8 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
         (&tmx[0][0])[threadIdx.x] = 0ull;
         consumed[threadIdx.x] = (int)threadIdx.x + 1 - NI;     // "finished" starts one turn before
     }
-    if (threadIdx.x == 0) produced = 0;
+    if (threadIdx.x == 0) { produced = 0; mrf_wait_init(&wait_lds, P.fault, P.spin_limit); }
+    const MrfWaitBlock *const wait_block = &wait_lds;
     __syncthreads();
 
     if (wv >= NWV) {
@@ -1742,10 +1753,11 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
         }
         int seen = 0;
         for (int n = 1 + jw; n < len; n += NI) {
+            int wait_turns = 0;
             while (seen < n) {
                 seen = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                if (seen < n) __builtin_amdgcn_s_sleep(1);
+                if (seen < n) mrf_wait_turn(wait_block, wait_turns);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
             const int slot = n & (NR - 1);
@@ -1897,6 +1909,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         float m;
         bool all;
+        int looks = 0;
         do {
             // all four posts in one batch of LDS reads (those of absent wavefronts are ignored)
             unsigned long long e[4];
@@ -1912,6 +1925,8 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                 m = mrf_min(m, here ? __int_as_float((int)(unsigned)e[w2]) : INFINITY);
             }
             all = __builtin_amdgcn_readfirstlane((int)all) != 0;
+            // (the partners are a few instructions apart: look again at once, and at the clock now and then)
+            if (!all && (++looks & 4095) == 0) mrf_wait_check(wait_block);
         } while (!all);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
         return m;
@@ -1932,6 +1947,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
             float *hb = &ring[slot][TW];
 
             // the slot was last used by step nn - NR
+            int wait_turns = 0;
             while (__builtin_expect(!past && freed < nn - NR, 0)) {
                 int lo = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&consumed[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
@@ -1942,7 +1958,7 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                     lo = cj < lo ? cj : lo;
                 }
                 freed = lo + NI - 1;
-                if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+                if (freed < nn - NR) mrf_wait_turn(wait_block, wait_turns);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 
@@ -2031,9 +2047,31 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
 // per-lane here.  V(.,lambda) sits in SEG registers per lane, h is exchanged through a
 // per-segment LDS row, the minimum over labels is a DPP row reduction (plus one swizzle
 // for 32-lane segments) and q comes from the segment's slice of a ballot.
+__device__ inline float mrf_segment_min21(float v, int lane)
+{
+    const bool up = mrf_seg21_upper(lane);
+    float u = up ? v : INFINITY, lo = up ? INFINITY : v;
+    u = mrf_min(u, mrf_dpp_f32<0xB1>(u));
+    lo = mrf_min(lo, mrf_dpp_f32<0xB1>(lo));
+    u = mrf_min(u, mrf_dpp_f32<0x4E>(u));
+    lo = mrf_min(lo, mrf_dpp_f32<0x4E>(lo));
+    u = mrf_min(u, mrf_dpp_f32<0x141>(u));
+    lo = mrf_min(lo, mrf_dpp_f32<0x141>(lo));
+    u = mrf_min(u, mrf_dpp_f32<0x140>(u));
+    lo = mrf_min(lo, mrf_dpp_f32<0x140>(lo));
+    // rows 1..3: lane 15 of the row before (its upper minimum) joins this row's lower minimum
+    const float pu = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        __builtin_bit_cast(int, INFINITY), __builtin_bit_cast(int, u), 0x142 /* row_bcast:15 */, 0xE, 0xF, false));
+    const float full = mrf_min(lo, pu);            // the whole segment's minimum, in rows 1..3 (segment = row - 1)
+    // upper lanes fetch it from the first lane of the next row; lower lanes hold it already
+    const int from = up ? ((lane & 48) + 16) & 63 : lane;
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from << 2, __builtin_bit_cast(int, full)));
+}
+
 template <int SEG>
 __device__ inline float mrf_segment_min(float v)
 {
+    if (SEG == 21) return mrf_segment_min21(v, (int)(threadIdx.x & 63));
     v = mrf_min(v, mrf_dpp_f32<0xB1>(v));
     v = mrf_min(v, mrf_dpp_f32<0x4E>(v));
     v = mrf_min(v, mrf_dpp_f32<0x141>(v));
@@ -2067,7 +2105,21 @@ __device__ inline float mrf_segment_min32_regs(float v, int lane)
     return lane < 32 ? a : b;
 }
 
-// MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG).
+// lowest lane of the caller's segment whose bit is set in a wavefront ballot, as a label
+template <int SEG>
+__device__ inline int mrf_segment_first(unsigned long long bal, int lane)
+{
+    if (SEG == 21) {
+        const int sh = (lane / 21) * 21;
+        return __ffs((int)((unsigned)(bal >> sh) & 0x1FFFFFu)) - 1;
+    }
+    const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
+    const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
+    return __ffs((int)mine) - 1;
+}
+
+// MU: source labels evaluated per node, L rounded up to a multiple of four (<= SEG, or 24 for the
+// 21-lane segments, whose LDS rows are padded to 28 entries).
 // IDX = 1, 2: that many further wavefronts per workgroup take the argmin tables and the stores (as in
 // mrf_fwd_sweep_window_duo): the first computes values only and hands each node's h and
 // weights over through a ring in LDS.  For launches that leave most issue slots idle; the host
@@ -2076,14 +2128,16 @@ template <int SEG, int MU, int RMAX, int D, bool TRWP, int IDX>
 __global__ void __launch_bounds__(64 * (1 + IDX))
 mrf_fwd_sweep_packed(const MrfFwdParams P)
 {
-    static_assert(MU % 4 == 0 && MU <= SEG, "source label count");
-    constexpr int NSEG = 64 / SEG;
-    constexpr int SEGP = SEG + 4;                 // row stride: keeps the segments on different banks
+    static_assert(MU % 4 == 0 && (MU <= SEG || (SEG == 21 && MU == 24)), "source label count");
+    constexpr int NSEG = 64 / SEG;                // (three segments of 21 lanes leave lane 63 idle)
+    constexpr int NROW = SEG == 21 ? 4 : NSEG;    // LDS rows: the idle lane gets one of its own to scribble in
+    constexpr int SEGP = SEG == 21 ? 28 : SEG + 4;   // row stride: 16-byte rows on different banks
     constexpr int NR = IDX ? 8 : 1;               // ring slots (IDX), else the one working row set
     static_assert(NR >= D || !IDX, "ring depth");
-    __shared__ __align__(16) float hring[NR][NSEG][SEGP];
+    __shared__ __align__(16) float hring[NR][NROW][SEGP];
     __shared__ float wring[NR][64];
     __shared__ int produced;
+    __shared__ MrfWaitBlock wait_lds;             // for the waits below (mrf_wait_turn)
     __shared__ int consumed[2];                   // per index wavefront: last step finished
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
@@ -2095,7 +2149,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     const long long N = P.g.N;
     const long long total = P.blk_begin[P.r_count];
     const long long sl = (long long)blockIdx.x * NSEG + seg;
-    const bool act_seg = sl < total;
+    const bool act_seg = sl < total && seg < NSEG;
 
     // per-lane description of the segment's scanline
     int r = P.r_first, nsc = 1, dh = 0, dw = 1, n_pre = 0, n_src = 0, rm_slot = -1;
@@ -2145,10 +2199,11 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 #pragma unroll
         for (int sl2 = 0; sl2 < NR; ++sl2) {
             hring[sl2][seg][lam] = INFINITY;      // entries mu >= L stay +inf: they never win
-            if (lam < 4) hring[sl2][seg][SEG + lam] = INFINITY;
+            if (lam < SEGP - SEG) hring[sl2][seg][SEG + lam] = INFINITY;
         }
-        if (lane == 0) { produced = 0; consumed[0] = 1 - IDX; consumed[1] = 0; }   // "finished" starts one turn before
+        if (lane == 0) { produced = 0; consumed[0] = 1 - IDX; consumed[1] = 0; mrf_wait_init(&wait_lds, P.fault, P.spin_limit); }   // "finished" starts one turn before
     }
+    const MrfWaitBlock *const wait_block = &wait_lds;
     __syncthreads();
 
     if ((!IDX || wave == 1) && act_seg && valid) {
@@ -2171,10 +2226,11 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
         const int jw = wave - 1;
         int seen = 0;
         for (int nn = 1 + jw; nn < maxlen; nn += (IDX > 0 ? IDX : 1)) {
+            int wait_turns = 0;
             while (seen < nn) {
                 seen = __builtin_amdgcn_readfirstlane(
                     __hip_atomic_load(&produced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                if (seen < nn) __builtin_amdgcn_s_sleep(1);
+                if (seen < nn) mrf_wait_turn(wait_block, wait_turns);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
             const int slot = nn & (NR - 1);
@@ -2201,10 +2257,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             });
             const float tv = valid ? best : INFINITY;
             const float tq = mrf_segment_min<SEG>(tv);
-            const unsigned long long bal = __ballot(tv == tq);
-            const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
-            const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
-            const int qidx = __ffs((int)mine) - 1;
+            const int qidx = mrf_segment_first<SEG>(__ballot(tv == tq), lane);
             if (act && valid) {
                 P.m_out[((size_t)r * N + i) * L + lam] = tv - tq;
                 P.p[((size_t)r * N + i) * L + lam] = (uint8_t)bidx;
@@ -2261,6 +2314,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             const int slot = IDX ? (nn & (NR - 1)) : 0;
             if (IDX) {
                 // the slot was last used by step nn - NR
+                int wait_turns = 0;
                 while (__builtin_expect(freed < nn - NR, 0)) {
                     // the index wavefronts take the steps in turn: behind the slowest one's last
                     // step, the others have finished theirs
@@ -2272,7 +2326,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
                         lo = c1 < lo ? c1 : lo;
                     }
                     freed = lo + IDX - 1;
-                    if (freed < nn - NR) __builtin_amdgcn_s_sleep(1);
+                    if (freed < nn - NR) mrf_wait_turn(wait_block, wait_turns);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
                 }
                 wring[slot][lane] = wgt;
@@ -2312,10 +2366,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
                 constexpr int m0 = MU - 4 - 4 * decltype(g4)::value;      // groups from the top down
                 mrf_first_equal4<m0>(bidx, best, dl[m0], dl[m0 + 1], dl[m0 + 2], dl[m0 + 3]);
             });
-            const unsigned long long bal = __ballot(tv == tq);
-            const unsigned word = lane < 32 ? (unsigned)bal : (unsigned)(bal >> 32);
-            const unsigned mine = SEG == 32 ? word : ((word >> (lane & 16)) & 0xFFFFu);
-            const int qidx = __ffs((int)mine) - 1;
+            const int qidx = mrf_segment_first<SEG>(__ballot(tv == tq), lane);
 
             if (act && valid) {
                 P.m_out[((size_t)r * N + i) * L + lam] = carry;

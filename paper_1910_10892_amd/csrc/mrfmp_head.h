@@ -92,6 +92,12 @@ __global__ void __launch_bounds__(64) mrf_sum_partials(const double *partial, in
     }
 }
 
+// first 256 bytes of a sweep workspace: the scalar edge weight and the cleared fault word
+__global__ void mrf_init_header(float *scalar, int *fault, float w)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) { *scalar = w; *fault = 0; }
+}
+
 struct MrfLossParams {
     long long N;             // pixels
     int L;

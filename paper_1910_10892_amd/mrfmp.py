@@ -103,6 +103,8 @@ def load_library():
     lib.mrf_softmin_l1.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mrf_softmin_smooth_l1.restype = ci
     lib.mrf_softmin_smooth_l1.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, sz, vp]
+    lib.mrf_workspace_fault.restype = ci
+    lib.mrf_workspace_fault.argtypes = [vp, vp]
     lib.mrf_strerror.argtypes = [ci]
     lib.mrf_version.restype = ctypes.c_char_p
     lib.mrf_set_sweep_events.restype = ci
@@ -331,3 +333,9 @@ def mrf_softmin_smooth_l1(cost, target, mask, beta, disparity, loss, grad_cost, 
                                               _dev_ptr(workspace), _ws_size(workspace), _stream_handle(stream))
     if rc != 0:
         raise MrfError(rc, "mrf_softmin_smooth_l1")
+
+
+def mrf_workspace_fault(workspace, stream=None) -> int:
+    """0, or -11 if a wait between wavefronts ran out in the last call that used this workspace
+    (synchronises the stream)."""
+    return int(load_library().mrf_workspace_fault(_dev_ptr(workspace), _stream_handle(stream)))

@@ -78,7 +78,7 @@ def test_validation_codes_without_gpu():
     assert V(_cprob(sgm_standard=1, K=2)) == -8
     assert V(_cprob(sgm_standard=1, K=1), 1) == -8
     assert lib.mrf_validate(None, 0) == -1
-    for code in range(0, -11, -1):
+    for code in range(0, -12, -1):
         assert mrf.mrf_strerror(code) != "unknown status"
 
 
@@ -128,6 +128,13 @@ def test_entry_points_reject_before_any_gpu_work():
         needb = lib.mrf_workspace_bytes(ctypes.byref(c), algo, 1)
         assert f(ctypes.byref(c), None, fake, fake, fake, None, None, fake, needb, None) == -1
         assert f(ctypes.byref(c), fake, fake, fake, fake, None, None, fake, needb - 1, None) == -6
+
+
+def test_workspace_fault_query_rejects_null():
+    lib = mrf.load_library()
+    assert lib.mrf_workspace_fault(None, None) == -1
+    assert "wait" in mrf.mrf_strerror(-11)
+    assert mrf.mrf_tune(14, 5) == 0 and mrf.mrf_tune(14, 0) == 0
 
 
 def test_noalloc_energy_rejects_what_its_scratch_cannot_hold():

@@ -410,6 +410,9 @@ PACK_CASES = [
     (74, "trwp", 3, 5, 6, 32, DIRS4, 2, False, False),
     (75, "isgmr", 1, 8, 3, 17, DIRS8, 2, True, True),
     (76, "trwp", 1, 3, 9, 1, DIRS4, 2, False, True),
+    (77, "isgmr", 2, 13, 17, 21, DIRS8, 2, False, True),    # 21 labels, scanlines of many lengths: packs of three
+    (78, "trwp", 1, 10, 7, 20, DIRS4, 3, True, True),
+    (79, "isgmr", 1, 5, 64, 18, DIRS4, 2, True, False),
 ]
 
 
@@ -428,12 +431,25 @@ def test_packed_scanlines_layout(oracle, case):
         b = full_check(oracle, pr)
         assert mrf.mrf_tune(11, 2) == 0                                  # packed, value + index wavefront
         c = full_check(oracle, pr)
+        more = []
+        if 16 < L <= 21:
+            # three scanlines per wavefront (segments of 21 lanes), with and without index wavefronts
+            assert mrf.mrf_tune(13, 2) == 0
+            more.append(full_check(oracle, pr))
+            assert "mrf_fwd_sweep_packed<21," in mrf.mrf_last_sweep_launch(False)
+            assert "mrf_bwd_sweep_packed<21," in mrf.mrf_last_sweep_launch(True)
+            assert mrf.mrf_tune(11, 1) == 0
+            more.append(full_check(oracle, pr))
+            more.append(full_check(oracle, pr, want_V=False))
     finally:
         mrf.mrf_tune(3, 0)
         mrf.mrf_tune(11, 0)
+        mrf.mrf_tune(13, 0)
     for name in ("p", "q", "labels", "cost", "messages"):
         np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
         np.testing.assert_array_equal(getattr(a, name), getattr(c, name), err_msg=name)
+        for m in more:
+            np.testing.assert_array_equal(getattr(a, name), getattr(m, name), err_msg=name)
 
 
 def test_optional_outputs_may_be_null(oracle):
@@ -470,6 +486,44 @@ def test_backward_is_reproducible_run_to_run():
         b = g.results()
         for name in ("cost", "p", "q", "grad_unary", "grad_edge_weight", "grad_pairwise"):
             np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
+
+
+def test_waits_between_wavefronts_are_bounded(oracle):
+    """The layouts that spread a scanline over several wavefronts give every wait a budget.  With a
+    budget of one turn (set from the host) their first unmet wait gives up: every kernel still ends
+    normally, and mrf_workspace_fault reports it.  With the default budget the same calls complete
+    and report nothing."""
+    import torch
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import GpuProblem
+    print("case bounded waits", flush=True)
+    cases = [make_config(2, crop=(24, 40), algo="trwp"),       # value / loader / index wavefronts, chain backward
+             make_config(4, crop=(10, 12), algo="trwp", K=2),  # value wavefronts that meet through LDS, index wavefronts
+             make_config(5, crop=(24, 32), algo="trwp")]       # packed scanlines with index wavefronts
+    for pr in cases:
+        g = GpuProblem(pr)
+        try:
+            assert mrf.mrf_tune(14, 1) == 0
+            g.forward()
+            fwd = mrf.mrf_workspace_fault(g.workspace)
+            g.backward(want_V=False)
+            bwd = mrf.mrf_workspace_fault(g.workspace)
+        finally:
+            mrf.mrf_tune(14, 0)
+        print("  ", pr.name, mrf.mrf_last_sweep_launch(False), fwd, mrf.mrf_last_sweep_launch(True), bwd, flush=True)
+        assert fwd in (0, -11) and bwd in (0, -11)
+        assert fwd == -11 or bwd == -11          # these shapes take multi-wavefront layouts: some wait is unmet at first
+        # default budget: complete, correct, nothing reported
+        g.poison_outputs()
+        g.forward()
+        assert mrf.mrf_workspace_fault(g.workspace) == 0
+        g.backward(want_V=False)
+        assert mrf.mrf_workspace_fault(g.workspace) == 0
+        got = g.results()
+        f = oracle_forward(oracle, pr)
+        check_forward(got, f)
+        b64 = oracle_backward(oracle, pr, f.p, f.q, np.float64)
+        check_grad("grad_unary", got.grad_unary, None, b64.grad_unary)
 
 
 def test_workspace_too_small_is_an_error_not_a_fault():
@@ -585,7 +639,7 @@ def _full_size_check(oracle, pr, want_V, fwd_launch, bwd_launch):
     g.poison_outputs()
     g.forward()
     g.backward(want_V=want_V)
-    torch.cuda.synchronize()
+    assert mrf.mrf_workspace_fault(g.workspace) == 0
     assert mrf.mrf_last_sweep_launch(False) == fwd_launch, mrf.mrf_last_sweep_launch(False)
     assert mrf.mrf_last_sweep_launch(True) == bwd_launch, mrf.mrf_last_sweep_launch(True)
     _progress("  GPU done; oracle forward (all host threads)")
@@ -719,7 +773,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
@@ -882,7 +936,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
     f = oracle_forward(oracle, pr, threads=True)
     b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
