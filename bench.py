@@ -152,9 +152,17 @@ def measure(index, algo, dense, steps, warmup, traffic, tune=()):
     window = mrf.mrf_forward_window(g.prob, g.algo)
     dirs = pr.dirs.tolist()
     opp = sum(1 for d in dirs if [-d[0], -d[1]] in dirs)
-    n_in = R if pr.algo == "trwp" else (R - 1 if opp == R else R)   # label vectors read per update
+    n_in = R if pr.algo == "trwp" else (R - 1 if opp == R else R)   # label vectors read per update (iterations >= 2)
     node_dirs = sum(E) * K                                          # node-direction-iterations per pass
-    fwd_bytes = node_dirs * (L * (4 * n_in + 5) + 5)
+    # Message arrays that are still zero are part of the algorithm's initialisation, not of its
+    # traffic: in the first iteration ISGMR reads the unary only, and TRWP's sweep of direction r the
+    # unary and the r directions swept before it.
+    def vectors_read(k, r):
+        has_opp = [-dirs[r][0], -dirs[r][1]] in dirs
+        if pr.algo == "trwp":
+            return 1 + (r if k == 0 else R - 1)
+        return 1 + (0 if k == 0 else R - 1 - (1 if has_opp else 0))
+    fwd_bytes = sum(E[r] * (L * (4 * vectors_read(k, r) + 5) + 5) for k in range(K) for r in range(R))
     bwd_bytes = node_dirs * (9 * L + 8 * L / R + 9)
     fwd_launch, bwd_launch = mrf.mrf_last_sweep_launch(False), mrf.mrf_last_sweep_launch(True)
     fwd_kernel, bwd_kernel = mrf.mrf_last_sweep_kernel(False), mrf.mrf_last_sweep_kernel(True)
@@ -164,7 +172,7 @@ def measure(index, algo, dense, steps, warmup, traffic, tune=()):
         gbs = fwd_bytes / (fwd_sweeps_ms * 1e-3) / 1e9
         roof_fwd = {"kernel": fwd_kernel, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gbs / HBM_PEAK_GBS, "traffic": traffic.get((pr.name, fwd_kernel)),
-                    "algorithmic_bytes_per_launch": fwd_bytes / n_launch, "bytes_per_node_direction": L * (4 * n_in + 5) + 5,
+                    "algorithmic_bytes_per_launch": fwd_bytes / n_launch, "bytes_per_node_direction_later_iterations": L * (4 * n_in + 5) + 5,
                     "launches_per_pass": n_launch, "avg_launch_ms": fwd_sweeps_ms / n_launch, "window": window}
     else:
         pairs = node_dirs * L * L                       # (lambda, mu) candidates of one forward pass
@@ -353,7 +361,7 @@ def main():
     if args.energy_protocol:
         out["energy_protocol"] = energy_protocol()
     if not args.no_cpu_baseline:
-        crops = {1: (32, 48), 2: (128, 256), 3: (40, 104), 4: (24, 32), 5: (512, 512)}
+        crops = {1: (32, 48), 2: (128, 256), 3: (56, 144), 4: (24, 32), 5: (256, 256)}
         out["cpu_baseline"] = cpu_baseline(head_run[0], head_run[1], crops[head_run[0]])
     print(json.dumps(out))
 

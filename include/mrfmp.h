@@ -291,6 +291,9 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           waiting for another gives up (see mrf_workspace_fault): 0 = default (4 s); 1 makes the
  *           multi-wavefront layouts give up almost at once (for tests of that path: every kernel still ends
  *           normally)
+ *   knob 15: ISGMR backward with up to four directions, where the sweeps may read the other directions' scatter
+ *           arrays themselves (one combine pass at the end) instead of a combine pass after every iteration:
+ *           0 = for small problems (launch bound), 1 = never, 2 = always
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

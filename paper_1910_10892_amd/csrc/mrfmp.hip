@@ -120,6 +120,7 @@ MRF_G(int g_tune_loader, 0);     // loader wavefront in the window sweep: 0 auto
 MRF_G(int g_tune_squad, 0);      // index wavefronts next to the split layout: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
 MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
+MRF_G(int g_tune_isgmr_lazy, 0); // ISGMR backward without a combine pass per iteration (up to 4 directions): 0 auto, 1 never
 MRF_G(int g_tune_spin_limit, 0); // turns a wait between wavefronts may take: 0 = default
 MRF_G(int g_tune_pack_idx, 0);   // index wavefronts in the packed dense sweep: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_chain, 0);      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
@@ -869,7 +870,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         }
         MrfCombineParams C;
         memset(&C, 0, sizeof(C));
-        C.NL = NL; C.R = R;
+        C.NL = NL; C.R = R; C.skip_dir = -1;
         for (int r = 0; r < R; ++r) C.opp[r] = P.g.opp[r];
         C.S = buf1; C.gc = grad_cost; C.gunary = grad_unary;
         long long cblocks = (NL + 255) / 256;
@@ -879,7 +880,53 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         long long cblocks4 = (NL / 4 + 255) / 256;
         if (cblocks4 > 32768) cblocks4 = 32768;
         if (cblocks4 < 1) cblocks4 = 1;
-        for (int k = K - 1; k >= 0; --k) {
+        // Up to four directions: no combine pass between iterations.  The sweep of direction d in
+        // iteration k reads what the other directions scattered in iteration k + 1 itself (grad m-hat^d =
+        // sum over r not in {d, d-} of s^r: at most two arrays, against one array plus the combine's 2 R + 2
+        // per node) and the sweep of direction 0 adds all of them, and its own s, to grad theta; one
+        // combine pass at the end adds what the other directions scattered in the last sweep.  The s
+        // arrays of two iterations alternate between the two buffers.
+        // Pays only where the pass is bound by its launches (the combine passes are a third of them): on the
+        // stereo and segmentation shapes the sweeps, which are bound by instruction issue and latency, lose
+        // more on the extra arrays (2.29 against 1.80 ms, 4.05 against 3.76 ms) than the combine passes cost.
+        const bool lazy = R <= 4 && g_tune_isgmr_lazy != 1 && (g_tune_isgmr_lazy == 2 || NL <= (1LL << 20));
+        for (int k = K - 1; lazy && k >= 0; --k) {
+            float *s_cur = ((K - 1 - k) & 1) ? buf0 : buf1, *s_prev = ((K - 1 - k) & 1) ? buf1 : buf0;
+            P.S = s_cur;
+            P.unary_dir = 0;
+            P.unary_init = (k == K - 1);
+            if (k == K - 1) {
+                // back Eq. isgmr-aggregation: every direction's message, and theta, receive grad c
+                P.src_base = grad_cost; P.src_stride = 0;
+                for (int r = 0; r < R; ++r) { P.n_src[r] = 1; P.src_dir[r][0] = (signed char)r; P.coefG[r][0] = 1.0f; P.coefT[r][0] = 1.0f; }
+            } else {
+                P.src_base = s_prev; P.src_stride = NL;
+                for (int d = 0; d < R; ++d) {
+                    int n = 0;
+                    for (int r = 0; r < R; ++r) {
+                        if (r == d) continue;
+                        const bool excluded = (r == P.g.opp[d]);          // Eq. isgmr leaves out r and r-
+                        if (excluded && d != 0) continue;
+                        P.src_dir[d][n] = (signed char)r;
+                        P.coefG[d][n] = excluded ? 0.0f : 1.0f;
+                        P.coefT[d][n] = 1.0f;                             // (grad theta: read by direction 0 only)
+                        ++n;
+                    }
+                    P.n_src[d] = (signed char)n;
+                }
+            }
+            P.p = p + (size_t)k * pk;
+            P.q = q + (size_t)k * qk;
+            { const hipError_t e_ = dispatch_bwd(P, pr->pairwise_kind, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_bwd"); }
+            if (k == 0) {
+                C.S = s_cur; C.first = 0; C.ghat = nullptr; C.skip_dir = 0;
+                const dim3 cg((unsigned)(cvec ? cblocks4 : cblocks)), cb(256);
+                if (cvec) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<4, 4>), cg, cb, 0, st, C);
+                else hipLaunchKernelGGL((mrf_isgmr_bwd_combine<4, 1>), cg, cb, 0, st, C);
+                { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
+            }
+        }
+        for (int k = K - 1; !lazy && k >= 0; --k) {
             if (k == K - 1) { P.src_base = grad_cost; P.src_stride = 0; }   // back Eq. isgmr-aggregation
             else { P.src_base = buf0; P.src_stride = NL; }
             P.p = p + (size_t)k * pk;
@@ -1200,7 +1247,7 @@ const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ?
 
 const char *mrf_last_sweep_launch(int backward) { return g_last_launch[backward ? 1 : 0]; }
 
-const char *mrf_version(void) { return "0.1.0"; }
+const char *mrf_version(void) { return "0.2.0"; }
 
 int mrf_set_sweep_events(void *start_event, void *stop_event)
 {
@@ -1225,6 +1272,7 @@ int mrf_tune(int knob, int value)
     if (knob == 10) { g_tune_squad_ni = value; return MRF_OK; }
     if (knob == 13) { g_tune_pack3 = value; return MRF_OK; }
     if (knob == 14) { g_tune_spin_limit = value > 0 ? value : 0; return MRF_OK; }
+    if (knob == 15) { g_tune_isgmr_lazy = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

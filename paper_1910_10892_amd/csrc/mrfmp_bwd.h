@@ -1234,6 +1234,7 @@ struct MrfCombineParams {
     float *gunary;           // [N][L]
     float *ghat;             // [R][N][L] out (next iteration's grad m-hat), NULL on the last
     int first;               // first processed iteration: grad theta starts from grad c
+    int skip_dir;            // direction whose s does not enter the sums (already added elsewhere), or -1
 };
 
 // RT: number of directions rounded up to 4, 8 or 16 (the loops below are unrolled to it);
@@ -1259,7 +1260,7 @@ __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombinePar
             double tot = 0.0;
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
-                sv[r] = (double)sraw[r][v];
+                sv[r] = (r == P.skip_dir) ? 0.0 : (double)sraw[r][v];
                 tot += sv[r];
             }
             uout[v] = (float)((double)braw[v] + tot);
