@@ -294,6 +294,9 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 15: ISGMR backward with up to four directions, where the sweeps may read the other directions' scatter
  *           arrays themselves (one combine pass at the end) instead of a combine pass after every iteration:
  *           0 = for small problems (launch bound), 1 = never, 2 = always
+ *   knob 16: dense forward sweep in which every wavefront owns 32 labels (loads, merge, normalisation and
+ *           stores divided among the wavefronts) instead of doing that work for all labels (the layout knob 0
+ *           tunes): 0 = for more than 128 labels, 1 = never, 2 = for more than 64 labels
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

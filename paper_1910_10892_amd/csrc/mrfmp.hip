@@ -121,6 +121,7 @@ MRF_G(int g_tune_squad, 0);      // index wavefronts next to the split layout: 0
 MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
 MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_isgmr_lazy, 0); // ISGMR backward without a combine pass per iteration (up to 4 directions): 0 auto, 1 never
+MRF_G(int g_tune_dense_sliced, 0); // dense sweep for more than 64 labels with a slice of the labels per wavefront: 0 yes, 1 no
 MRF_G(int g_tune_spin_limit, 0); // turns a wait between wavefronts may take: 0 = default
 MRF_G(int g_tune_pack_idx, 0);   // index wavefronts in the packed dense sweep: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_chain, 0);      // backward sweep with a chain wavefront: 0 auto, 1 never, 2 whenever possible
@@ -207,6 +208,17 @@ hipError_t launch_fwd(const MrfFwdParams &P, int algo, long long blocks, hipStre
         hipLaunchKernelGGL((mrf_fwd_sweep<LP, MCH, RMAX, D, true>), dim3((unsigned)blocks), dim3(64 * P.NW), lds, st, P);
     else
         hipLaunchKernelGGL((mrf_fwd_sweep<LP, MCH, RMAX, D, false>), dim3((unsigned)blocks), dim3(64 * P.NW), lds, st, P);
+    return hipGetLastError();
+}
+
+template <int LP, int RMAX, int D>
+hipError_t launch_fwd_sliced(const MrfFwdParams &P, int algo, long long blocks, hipStream_t st)
+{
+    note_launch(0, "mrf_fwd_sweep_sliced", blocks, 64 * P.NW, "%d,%d,%d,%s", LP, RMAX, D, algo == MRF_TRWP ? "true" : "false");
+    if (algo == MRF_TRWP)
+        hipLaunchKernelGGL((mrf_fwd_sweep_sliced<LP, RMAX, D, true>), dim3((unsigned)blocks), dim3(64 * P.NW), 0, st, P);
+    else
+        hipLaunchKernelGGL((mrf_fwd_sweep_sliced<LP, RMAX, D, false>), dim3((unsigned)blocks), dim3(64 * P.NW), 0, st, P);
     return hipGetLastError();
 }
 
@@ -462,6 +474,18 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
     for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
         if (P.n_src[r] > max_src) max_src = P.n_src[r];
     const int rmax = (max_src + 1 <= 4) ? 4 : ((max_src + 1 <= 8) ? 8 : 16);
+    // more than 64 labels: every wavefront owns 32 of them (unless a tuning knob or a per-edge variant asks
+    // for the sweep in which every wavefront does the O(L) work of the whole node)
+    // (for 65..128 labels only on request: three wavefronts of 32 source labels are no faster than four of 24)
+    if ((LP >= 3 || (LP == 2 && g_tune_dense_sliced == 2)) && !generic && !P.sgm_std && g_tune_mch == 0 && g_tune_dense_sliced != 1) {
+        P.NW = (L + 31) / 32;
+#define MRF_SCASE(lp) \
+        if (LP == lp && rmax == 4) return launch_fwd_sliced<lp, 4, 4>(P, algo, blocks, st); \
+        if (LP == lp && rmax == 8) return launch_fwd_sliced<lp, 8, 2>(P, algo, blocks, st); \
+        if (LP == lp && rmax == 16) return launch_fwd_sliced<lp, 16, 1>(P, algo, blocks, st);
+        MRF_SCASE(2) MRF_SCASE(3) MRF_SCASE(4)
+#undef MRF_SCASE
+    }
     const int mch = pick_mch(L, LP, rmax > 4);
     P.NW = (L + mch - 1) / mch;
     // prefetch depth: as deep as the register file allows next to the slice of V
@@ -1273,6 +1297,7 @@ int mrf_tune(int knob, int value)
     if (knob == 13) { g_tune_pack3 = value; return MRF_OK; }
     if (knob == 14) { g_tune_spin_limit = value > 0 ? value : 0; return MRF_OK; }
     if (knob == 15) { g_tune_isgmr_lazy = value; return MRF_OK; }
+    if (knob == 16) { g_tune_dense_sliced = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

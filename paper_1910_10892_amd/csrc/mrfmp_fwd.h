@@ -17,6 +17,7 @@
 //
 // Kernels in this file, all computing the same update in the same rounding order:
 //   mrf_fwd_sweep               dense O(L^2), NW wavefronts per scanline split the source labels
+//   mrf_fwd_sweep_sliced        dense, L > 64: the same with the O(L) work of a node divided among the wavefronts
 //   mrf_fwd_sweep_packed        dense, L <= 32: several scanlines per wavefront
 //   mrf_fwd_sweep_edge          pairwise potentials given per edge (L <= 64)
 //   mrf_aggregate               final costs and labels
@@ -328,6 +329,217 @@ mrf_fwd_sweep(const MrfFwdParams P)
             for (int c = 0; c < RMAX; ++c)
 #pragma unroll
                 for (int s = 0; s < LP; ++s) cur[u][c][s] = nxt[u][c][s];
+        }
+    }
+}
+
+// ---- dense sweep, every wavefront owns a slice of the labels ------------------------------------
+//
+// The same O(L^2) update as mrf_fwd_sweep for more than 64 labels, with the O(L) work of a node
+// divided instead of repeated.  Wavefront w holds rows [32 w, 32 w + 32) of V in registers as
+// before and evaluates their candidates for all L destination labels; but only these 32 labels
+// are also its "home": it alone loads the inputs of h for them, merges the partial results of all
+// wavefronts for them, normalises, keeps the running message for them, and stores them.  (In
+// mrf_fwd_sweep every wavefront does all of that for all L labels, so that one barrier per node
+// suffices; at L = 256 that is a third of its instructions.)  The price is a second barrier per
+// node: the minimum over all labels (Eq. isgmr-norm) is the minimum of the wavefronts' home minima,
+// exchanged through LDS.  Home labels sit in 32 consecutive lanes of one label slot (lane + 64 s),
+// so loads and stores of a wavefront are 128-byte runs.
+//   per node:  h(home) -> private LDS copy -> candidates of the 32 source labels for all lambda
+//              -> partial (min, argmin) per lambda to LDS -> barrier -> merge at home, home minimum
+//              -> LDS -> barrier -> global minimum, q, running message, stores
+// Same arithmetic in the same order as mrf_fwd_sweep: results are bit-identical.
+template <int LP, int RMAX, int D, bool TRWP>
+__global__ void __launch_bounds__(64 * 2 * LP)
+mrf_fwd_sweep_sliced(const MrfFwdParams P)
+{
+    constexpr int MCH = 32;
+    constexpr int NWMAX = 2 * LP;
+    constexpr int SLOTS = 64 * LP;
+    __shared__ __align__(16) float hbuf_all[NWMAX][MCH];         // h of every wavefront's slice (read by its owner only)
+    __shared__ float2 part[NWMAX][SLOTS];                        // partial (min, argmin) of wavefront w for label lambda
+    __shared__ float2 hmin[NWMAX];                               // home minimum and its label, per wavefront
+    const int L = P.g.L, NW = P.NW;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    float *hbuf = hbuf_all[wv];
+
+    const long long blk = blockIdx.x;
+    int ri = 0;
+    while (ri + 1 < P.r_count && blk >= P.blk_begin[ri + 1]) ++ri;
+    const int r = P.r_first + ri;
+    const long long local = blk - P.blk_begin[ri];
+    const int nsc = P.g.nscan[r];
+    const int b = (int)(local / nsc);
+    const long long t = local - (long long)b * nsc;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0, x0, len;
+    mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+    const long long N = P.g.N;
+    const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const float rho = P.rho[r];
+    const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
+
+    // home label of this lane: lanes [32 (w & 1), +32) of the wavefront hold labels 32 w .. 32 w + 31
+    const int mu0 = wv * MCH;
+    const bool home_lane = (lane >> 5) == (wv & 1);
+    const int hl = mu0 + (lane & 31);                 // home label (meaningful in home lanes)
+    const bool home = home_lane && hl < L;
+    const int hlc = home ? hl : 0;
+
+    const float *src[RMAX];
+    float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
+    const float vz = mrf_opaque_zero_f();
+    src[0] = P.unary;
+    use[0] = 1.0f;
+    is_rm[0] = 0.0f;
+#pragma unroll
+    for (int c = 1; c < RMAX; ++c) {
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
+        is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
+    }
+#pragma unroll
+    for (int c = 1; c <= RMAX; ++c) carry_at[c] = ((c == n_pre + 1) ? 1.0f : 0.0f) + vz;
+
+    // rows mu0 .. mu0 + 31 of V, columns = the lane's destination labels
+    float Vr[MCH][LP];
+#pragma unroll
+    for (int i = 0; i < MCH; ++i)
+#pragma unroll
+        for (int s = 0; s < LP; ++s) {
+            const int mu = mu0 + i, lam = lane + 64 * s;
+            Vr[i][s] = (mu < L && lam < L) ? P.V[(size_t)mu * L + lam] : 0.0f;
+        }
+    // entries of h past L never win a strict '<'; wavefronts that are absent (NW < NWMAX) neither
+    if (lane < MCH) hbuf[lane] = INFINITY;
+    for (int i = threadIdx.x; i < NWMAX * SLOTS; i += blockDim.x) (&part[0][0])[i] = make_float2(INFINITY, 0.0f);
+    if (threadIdx.x < NWMAX) hmin[threadIdx.x] = make_float2(INFINITY, 0.0f);
+    __syncthreads();
+
+    // first node of the scanline: message 0, p = q = 0
+    if (home) {
+        P.m_out[((size_t)r * N + head) * L + hl] = 0.0f;
+        P.p[((size_t)r * N + head) * L + hl] = 0;
+    }
+    if (threadIdx.x == 0) P.q[(size_t)r * N + head] = 0;
+
+    const int vzero = mrf_opaque_zero();
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+    const int lastsrc = len - 2;
+    float cur[D][RMAX], nxt[D][RMAX];
+    float wcur[D], wnxt[D];
+    auto prefetch = [&](float (&dst)[RMAX], float &wdst, int nj) {      // inputs of the update nj -> nj + 1
+        nj = nj < lastsrc ? nj : lastsrc;
+        const long long j = head + (long long)nj * nstep;
+#pragma unroll
+        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][(size_t)j * L + hlc];
+        wdst = wbase[(size_t)((j + nstep) * P.w_mul) + vzero];
+    };
+    if (len >= 2) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    }
+
+    float carry = 0.0f;        // normalised message of this direction at the previous node, home label
+
+    for (int n0 = 1; n0 < len; n0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int nn = n0 + u;
+            const bool past = nn >= len;
+            const int n = past ? len - 1 : nn;
+            const long long i = head + (long long)n * nstep;
+
+            // ---- h at node i-r for the home labels (same order of additions as mrf_fwd_sweep) ----
+            float v = cur[u][0];
+            if (TRWP) {
+                float mrm = 0.0f;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) {
+                    v = __builtin_fmaf(carry_at[c], carry, v);
+                    v = __builtin_fmaf(use[c], cur[u][c], v);
+                    mrm = __builtin_fmaf(is_rm[c], cur[u][c], mrm);
+                }
+                v = __builtin_fmaf(carry_at[RMAX], carry, v);
+                v = rho * v;
+                v = v - mrm;
+            } else {
+                v = v + carry;
+#pragma unroll
+                for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+            }
+            const float wgt = wcur[u];
+            if (home) hbuf[lane & 31] = v;
+            mrf_wave_lds_fence();
+
+            // ---- candidates of the 32 source labels of this wavefront, for every lambda ----
+            float best[LP];
+            int bidx[LP];
+#pragma unroll
+            for (int s = 0; s < LP; ++s) { best[s] = INFINITY; bidx[s] = 0; }
+            // (all of the slice's h in one batch of LDS reads: the registers that the divided loads
+            // freed pay for it, and the candidates then run without waiting for LDS)
+            float hq[MCH];
+#pragma unroll
+            for (int i4 = 0; i4 < MCH; i4 += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(&hbuf[i4]);
+                hq[i4] = hv.x; hq[i4 + 1] = hv.y; hq[i4 + 2] = hv.z; hq[i4 + 3] = hv.w;
+            }
+            mrf_static_for<MCH>([&](auto mm) {
+                constexpr int m = decltype(mm)::value;
+                float dlt[LP];
+#pragma unroll
+                for (int s = 0; s < LP; ++s) dlt[s] = __builtin_fmaf(wgt, Vr[m][s], hq[m]);
+                mrf_argmin_step<m>(best, bidx, dlt);
+            });
+#pragma unroll
+            for (int s = 0; s < LP; ++s)
+                part[wv][lane + 64 * s] = make_float2(best[s], __int_as_float(mu0 + bidx[s]));
+            mrf_block_sync_lds();
+
+            // ---- merge at home, in ascending source label: the lowest index survives ----
+            float tv = INFINITY;
+            int tp = 0;
+#pragma unroll
+            for (int w2 = 0; w2 < NWMAX; ++w2) {
+                const float2 e = part[w2][hlc];
+                if (e.x < tv) { tv = e.x; tp = __float_as_int(e.y); }
+            }
+            if (!home) tv = INFINITY;
+            // home minimum and the lowest home label that attains it
+            const float lmin = mrf_wave_min(tv);
+            const unsigned long long lbal = __ballot(tv == lmin);
+            const int llab = mu0 + ((__ffsll((long long)lbal) - 1) & 31);
+            if (lane == 0) hmin[wv] = make_float2(lmin, __int_as_float(llab));
+            mrf_block_sync_lds();
+
+            // ---- global minimum over the labels, q = lowest label attaining it (Eq. isgmr-norm) ----
+            float tq = INFINITY;
+            int qidx = 0;
+#pragma unroll
+            for (int w2 = 0; w2 < NWMAX; ++w2) {
+                const float2 e = hmin[w2];
+                if (e.x < tq) { tq = e.x; qidx = __float_as_int(e.y); }     // ascending wavefront = ascending label
+            }
+            carry = home ? tv - tq : 0.0f;
+
+            if (!past) {
+                if (home) {
+                    P.m_out[((size_t)r * N + i) * L + hl] = carry;
+                    P.p[((size_t)r * N + i) * L + hl] = (uint8_t)tp;
+                }
+                if (threadIdx.x == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            wcur[u] = wnxt[u];
+#pragma unroll
+            for (int c = 0; c < RMAX; ++c) cur[u][c] = nxt[u][c];
         }
     }
 }

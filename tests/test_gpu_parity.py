@@ -140,6 +140,34 @@ def test_wavefront_split_does_not_change_results(oracle, mch):
         mrf.mrf_tune(0, 0)
 
 
+@pytest.mark.parametrize("case", [
+    (601, "trwp", 1, 5, 9, 65, DIRS4, 2, False), (602, "isgmr", 2, 4, 7, 96, DIRS8, 2, True),
+    (603, "trwp", 1, 6, 5, 130, DIRS8, 2, False), (604, "isgmr", 1, 3, 11, 192, DIRS16, 2, False),
+    (605, "trwp", 1, 7, 6, 255, DIRS4, 3, True), (606, "isgmr", 1, 4, 8, 256, DIRS4, 2, False),
+    (607, "trwp", 1, 3, 40, 100, [(0, 1), (1, 0), (-1, 0)], 2, False),
+], ids=lambda c: "seed%d" % c[0])
+def test_dense_sweep_with_a_slice_of_labels_per_wavefront(oracle, case):
+    """More than 64 labels, general dense table: the sweep in which every wavefront owns 32 labels
+    against the oracle, and bit for bit against the sweep in which every wavefront does the O(L) work
+    of the whole node."""
+    import paper_1910_10892_amd as mrf
+    print("case dense sliced", case[:8], flush=True)
+    seed, algo, B, H, W, L, dirs, K, iv = case
+    pr = random_problem(seed, algo, B, H, W, L, dirs, K, integer_valued=iv, symmetric=False,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    try:
+        assert mrf.mrf_tune(16, 2) == 0
+        a = full_check(oracle, pr, want_V=False)
+        assert mrf.mrf_last_sweep_kernel(False) == "mrf_fwd_sweep_sliced"
+        assert mrf.mrf_tune(16, 1) == 0
+        b = full_check(oracle, pr, want_V=False)
+        assert mrf.mrf_last_sweep_kernel(False) == "mrf_fwd_sweep"
+    finally:
+        mrf.mrf_tune(16, 0)
+    for name in ("p", "q", "labels", "cost", "messages"):
+        np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
+
+
 def truncated_problem(seed, algo, H, W, L, dirs, K, kind, trunc, integer_valued, weights):
     """Truncated linear (kind 1) / quadratic (kind 2) pairwise with the kind announced, so the
     library may take its window path.  weights: 'pos' | 'zero_mix' | 'neg_mix'."""
@@ -704,7 +732,7 @@ def test_full_size_denoising_config_dense_sweep(oracle):
     g.poison_outputs()
     g.forward()
     torch.cuda.synchronize()
-    assert mrf.mrf_last_sweep_kernel(False) == "mrf_fwd_sweep"
+    assert mrf.mrf_last_sweep_launch(False) == "mrf_fwd_sweep_sliced<4,4,4,true> grid=256 block=512"
     f = oracle_forward(oracle, pr, threads=True)
     for name in ("p", "q", "labels", "messages", "cost"):
         assert np.array_equal(getattr(g, name).cpu().numpy(), getattr(f, name)), name
@@ -773,7 +801,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
@@ -936,7 +964,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
     f = oracle_forward(oracle, pr, threads=True)
     b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
