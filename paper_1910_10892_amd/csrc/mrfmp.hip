@@ -895,7 +895,10 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         MrfCombineParams C;
         memset(&C, 0, sizeof(C));
         C.NL = NL; C.R = R; C.skip_dir = -1;
-        for (int r = 0; r < R; ++r) C.opp[r] = P.g.opp[r];
+        for (int r = 0; r < R; ++r) {
+            C.opp[r] = P.g.opp[r];
+            C.canon[r] = (P.g.opp[r] >= 0 && P.g.opp[r] < r) ? P.g.opp[r] : r;
+        }
         C.S = buf1; C.gc = grad_cost; C.gunary = grad_unary;
         long long cblocks = (NL + 255) / 256;
         if (cblocks > 32768) cblocks = 32768;
@@ -953,6 +956,8 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         for (int k = K - 1; !lazy && k >= 0; --k) {
             if (k == K - 1) { P.src_base = grad_cost; P.src_stride = 0; }   // back Eq. isgmr-aggregation
             else { P.src_base = buf0; P.src_stride = NL; }
+            // (grad m-hat of a direction and of its opposite are the same sum: one array serves both)
+            for (int r = 0; r < R; ++r) P.src_dir[r][0] = (signed char)((k == K - 1) ? r : C.canon[r]);
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
             { const hipError_t e_ = dispatch_bwd(P, pr->pairwise_kind, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_bwd"); }

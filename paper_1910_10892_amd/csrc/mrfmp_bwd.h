@@ -1232,7 +1232,10 @@ struct MrfCombineParams {
     const float *S;          // [R][N][L]
     const float *gc;         // grad c, read when first != 0
     float *gunary;           // [N][L]
-    float *ghat;             // [R][N][L] out (next iteration's grad m-hat), NULL on the last
+    float *ghat;             // [R][N][L] out (next iteration's grad m-hat), NULL on the last; only the slabs of
+                             // directions d with canon[d] == d are written
+    int canon[MRF_MAXR];     // a direction and its opposite exclude the same pair {d, d-}, so their grad m-hat
+                             // is one and the same array: canon[d] = the lower index of the two
     int first;               // first processed iteration: grad theta starts from grad c
     int skip_dir;            // direction whose s does not enter the sums (already added elsewhere), or -1
 };
@@ -1277,7 +1280,7 @@ __global__ void __launch_bounds__(256) mrf_isgmr_bwd_combine(const MrfCombinePar
         if (P.ghat) {
 #pragma unroll
             for (int d = 0; d < RT; ++d)
-                if (d < P.R) *reinterpret_cast<vecf *>(P.ghat + (size_t)d * P.NL + e) = gout[d];
+                if (d < P.R && P.canon[d] == d) *reinterpret_cast<vecf *>(P.ghat + (size_t)d * P.NL + e) = gout[d];
         }
     }
 }
