@@ -116,10 +116,13 @@ int NAME(mrfo_isgmr_forward)(int B, int H, int W, int L, int R, const int *dirs,
                     if (!in_grid(&g, yn, xn)) break;
                     size_t j = node_index(&g, b, y, x), i = node_index(&g, b, yn, xn);
                     for (int mu = 0; mu < L; ++mu) {
+                        /* Eq. isgmr's bracket without the pairwise term: the terms known from
+                         * iteration k first (unary, then the other directions in index order),
+                         * the running message of this iteration last */
                         REAL a = unary[j * L + mu];
-                        a = a + mhat[((size_t)r * N + j) * L + mu];
                         for (int d = 0; d < R; ++d)
                             if (d != r && d != rm) a = a + m[((size_t)d * N + j) * L + mu];
+                        a = a + mhat[((size_t)r * N + j) * L + mu];
                         h[mu] = a;
                     }
                     REAL wgt = w ? w[(size_t)r * N + i] : w_scalar;
