@@ -162,9 +162,18 @@ def measure(index, algo, dense, steps, warmup, traffic, tune=()):
         if pr.algo == "trwp":
             return 1 + (r if k == 0 else R - 1)
         return 1 + (0 if k == 0 else R - 1 - (1 if has_opp else 0))
-    fwd_bytes = sum(E[r] * (L * (4 * vectors_read(k, r) + 5) + 5) for k in range(K) for r in range(R))
-    bwd_bytes = node_dirs * (9 * L + 8 * L / R + 9)
+    fwd_bytes_direct = sum(E[r] * (L * (4 * vectors_read(k, r) + 5) + 5) for k in range(K) for r in range(R))
     fwd_launch, bwd_launch = mrf.mrf_last_sweep_launch(False), mrf.mrf_last_sweep_launch(True)
+    presum = "mrf_isgmr_presum" in fwd_launch
+    if presum:
+        # ISGMR with many directions: a streaming pass per later iteration reads the unary and the R message
+        # arrays once and writes one sum per pair of opposite directions; every sweep then reads one vector
+        pairs_of_dirs = sum(1 for r in range(R) if [-dirs[r][0], -dirs[r][1]] not in dirs[:r])
+        fwd_bytes = (sum(E[r] * (L * (4 * 1 + 5) + 5) for k in range(K) for r in range(R)) +
+                     (K - 1) * 4 * B * H * W * L * (1 + R + pairs_of_dirs))
+    else:
+        fwd_bytes = fwd_bytes_direct
+    bwd_bytes = node_dirs * (9 * L + 8 * L / R + 9)
     fwd_kernel, bwd_kernel = mrf.mrf_last_sweep_kernel(False), mrf.mrf_last_sweep_kernel(True)
     if window > 0:
         # the window sweeps evaluate 2*window-1 candidates per label instead of L: bytes, not pairs, are
@@ -173,6 +182,7 @@ def measure(index, algo, dense, steps, warmup, traffic, tune=()):
         roof_fwd = {"kernel": fwd_kernel, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gbs / HBM_PEAK_GBS, "traffic": traffic.get((pr.name, fwd_kernel)),
                     "algorithmic_bytes_per_launch": fwd_bytes / n_launch, "bytes_per_node_direction_later_iterations": L * (4 * n_in + 5) + 5,
+                    "bytes_per_launch_if_every_sweep_read_all_its_sources": fwd_bytes_direct / n_launch,
                     "launches_per_pass": n_launch, "avg_launch_ms": fwd_sweeps_ms / n_launch, "window": window}
     else:
         pairs = node_dirs * L * L                       # (lambda, mu) candidates of one forward pass

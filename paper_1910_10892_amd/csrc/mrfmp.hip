@@ -121,6 +121,7 @@ MRF_G(int g_tune_squad, 0);      // index wavefronts next to the split layout: 0
 MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
 MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_isgmr_lazy, 0); // ISGMR backward without a combine pass per iteration (up to 4 directions): 0 auto, 1 never
+MRF_G(int g_tune_isgmr_presum, 0); // ISGMR forward with the per-pair sums of the previous iteration formed once: 0 from six directions, 1 never, 2 always
 MRF_G(int g_tune_dense_sliced, 0); // dense sweep for more than 64 labels with a slice of the labels per wavefront: 0 yes, 1 no
 MRF_G(int g_tune_spin_limit, 0); // turns a wait between wavefronts may take: 0 = default
 MRF_G(int g_tune_pack_idx, 0);   // index wavefronts in the packed dense sweep: 0 by launch size, 1 never, 2 always
@@ -568,13 +569,48 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
         long long blocks = 0;
         for (int r = 0; r < R; ++r) { P.blk_begin[r] = blocks; blocks += (long long)pr->B * P.g.nscan[r]; }
         P.blk_begin[R] = blocks;
+        // Six directions or more: one streaming pass per iteration sums what the previous iteration left at
+        // every node, once per pair of opposite directions (mrf_isgmr_presum), and the sweeps read that one
+        // array like a unary.  The messages of iteration k - 1 are dead once it has run, so the sweeps write
+        // over them and the second buffer holds the sums.
+        const long long NL = N * L;
+        const bool presum = K > 1 && !pr->sgm_standard && g_tune_isgmr_presum != 1 && (g_tune_isgmr_presum == 2 || R >= 6);
+        MrfPresumParams S;
+        memset(&S, 0, sizeof(S));
+        S.NL = NL; S.R = R; S.unary = pr->unary; S.m = bufA; S.out = bufB;
+        for (int r = 0; r < R; ++r) S.opp[r] = P.g.opp[r];
+        const bool svec = (NL % 4 == 0) && (((uintptr_t)pr->unary | (uintptr_t)bufA | (uintptr_t)bufB) % 16 == 0);
+        long long sblocks = ((svec ? NL / 4 : NL) + 255) / 256;
+        if (sblocks > 32768) sblocks = 32768;
+        if (sblocks < 1) sblocks = 1;
         for (int k = 0; k < K; ++k) {
-            P.m_in = (k & 1) ? bufB : bufA;      // written by iteration k-1 (unused when k = 0)
-            P.m_out = (k & 1) ? bufA : bufB;
-            for (int r = 0; r < R; ++r) fill_sources(P, algo, r, k == 0 ? 0u : 0xffffffffu);
+            if (presum) {
+                P.m_in = bufA; P.m_out = bufA;
+                P.unary = (k == 0) ? pr->unary : bufB;
+                for (int r = 0; r < R; ++r) {
+                    fill_sources(P, algo, r, 0u);
+                    P.unary_slab[r] = (signed char)((k == 0) ? 0 : ((P.g.opp[r] >= 0 && P.g.opp[r] < r) ? P.g.opp[r] : r));
+                }
+                if (k > 0) {
+                    const dim3 sg((unsigned)sblocks), sb(256);
+                    if (R <= 8 && svec) hipLaunchKernelGGL((mrf_isgmr_presum<8, 4>), sg, sb, 0, st, S);
+                    else if (R <= 8) hipLaunchKernelGGL((mrf_isgmr_presum<8, 1>), sg, sb, 0, st, S);
+                    else if (svec) hipLaunchKernelGGL((mrf_isgmr_presum<16, 4>), sg, sb, 0, st, S);
+                    else hipLaunchKernelGGL((mrf_isgmr_presum<16, 1>), sg, sb, 0, st, S);
+                    { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
+                }
+            } else {
+                P.m_in = (k & 1) ? bufB : bufA;      // written by iteration k-1 (unused when k = 0)
+                P.m_out = (k & 1) ? bufA : bufB;
+                for (int r = 0; r < R; ++r) fill_sources(P, algo, r, k == 0 ? 0u : 0xffffffffu);
+            }
             P.p = p + (size_t)k * pk;
             P.q = q + (size_t)k * qk;
             { const hipError_t e_ = dispatch_fwd(P, algo, tw, blocks, st); if (e_ != hipSuccess) return hip_fail(e_, "dispatch_fwd"); }
+            if (presum && k > 0) {
+                const size_t used = strlen(g_last_launch[0]);
+                snprintf(g_last_launch[0] + used, sizeof(g_last_launch[0]) - used, " after mrf_isgmr_presum<%d,%d>", R <= 8 ? 8 : 16, svec ? 4 : 1);
+            }
             final_m = P.m_out;
         }
     } else {
@@ -1303,6 +1339,7 @@ int mrf_tune(int knob, int value)
     if (knob == 14) { g_tune_spin_limit = value > 0 ? value : 0; return MRF_OK; }
     if (knob == 15) { g_tune_isgmr_lazy = value; return MRF_OK; }
     if (knob == 16) { g_tune_dense_sliced = value; return MRF_OK; }
+    if (knob == 17) { g_tune_isgmr_presum = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

@@ -53,6 +53,8 @@ struct MrfFwdParams {
     int NW;                                // wavefronts per workgroup = ceil(L / MCH)
     int *fault;                            // launch-wide word raised when a wait between wavefronts is given up (mrf_wait_turn)
     int spin_limit;                        // microseconds after which a wait is given up
+    signed char unary_slab[MRF_MAXR];      // direction r reads its lambda-independent start term at
+                                           // unary + unary_slab[r] * N * L (0 unless mrf_isgmr_presum prepared them)
     int sgm_std;                           // standard single-pass SGM (Eq. sgm_old): the message carries the node's own
                                            // unary, m^r_i = theta_i + min_mu (m^r_{i-r} + theta_{i-r,i}); mrf_fwd_sweep only
 };
@@ -101,12 +103,12 @@ mrf_fwd_sweep(const MrfFwdParams P)
     // standard SGM adds the unary of node i itself after the minimum (Eq. sgm_old): slot 0 then
     // holds theta_i, one node further along the scanline, instead of theta_{i-r}
     const bool sgm_std = !TRWP && P.sgm_std;
-    src[0] = P.unary + (sgm_std ? nstep * L : 0);
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L + (sgm_std ? nstep * L : 0);
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
         is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
@@ -208,10 +210,10 @@ mrf_fwd_sweep(const MrfFwdParams P)
                     v = rcur[u] * v;
                     v = v - mrm;
                 } else {
-                    // Eq. isgmr: theta_{i-r} + m-hat^r_{i-r} + sum_{d not in {r, r-}} m^d_{i-r}
-                    v = v + carry[s];
+                    // Eq. isgmr: theta_{i-r} + sum_{d not in {r, r-}} m^d_{i-r} (what iteration k left), then m-hat^r_{i-r}
 #pragma unroll
                     for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                    v = v + carry[s];
                     // Eq. sgm_old: the previous message alone (it holds theta_{i-r} already)
                     v = sgm_std ? carry[s] : v;
                 }
@@ -391,12 +393,12 @@ mrf_fwd_sweep_sliced(const MrfFwdParams P)
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
     const float vz = mrf_opaque_zero_f();
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
         is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
@@ -468,9 +470,9 @@ mrf_fwd_sweep_sliced(const MrfFwdParams P)
                 v = rho * v;
                 v = v - mrm;
             } else {
-                v = v + carry;
 #pragma unroll
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+                v = v + carry;
             }
             const float wgt = wcur[u];
             if (home) hbuf[lane & 31] = v;
@@ -583,12 +585,12 @@ mrf_fwd_sweep_edge(const MrfFwdParams P)
     // sources of h as in mrf_fwd_sweep: unused slots read the unary with factor 0
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = (c <= n_src) ? 1.0f : 0.0f;
         is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
     }
@@ -649,9 +651,9 @@ mrf_fwd_sweep_edge(const MrfFwdParams P)
             v = rcur * v;
             v = v - mrm;
         } else {
-            v = v + carry;
 #pragma unroll
             for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[c], v);
+            v = v + carry;
         }
 
         // ascending mu with a strict '<': the lowest minimiser survives
@@ -733,6 +735,47 @@ __global__ void __launch_bounds__(256) mrf_aggregate(const MrfAggParams P)
     }
 }
 
+// ---- ISGMR with many directions: what iteration k left at a node, summed once per pair of directions ----
+// Eq. isgmr's bracket holds, besides the running message, theta_i + sum over d not in {r, r-} of m^{d,k}_i:
+// the same sum for r and for r-, and the same terms in the same order for every node that reads node i.
+// One streaming pass per iteration forms it for every pair (2 R + 2 + R vectors moved per node instead of
+// R (R - 1) read by the sweeps); the sweeps then read that one vector where they read the unary in the
+// first iteration.  The additions are those of the sweeps, left to right in direction order.
+struct MrfPresumParams {
+    long long NL;            // entries per array
+    int R;
+    int opp[MRF_MAXR];       // opposite direction, or -1
+    const float *unary;      // [N][L]
+    const float *m;          // [R][N][L] messages of iteration k
+    float *out;              // [R][N][L]: slab d is written for every d with no lower-indexed opposite
+};
+
+template <int RT, int VEC>
+__global__ void __launch_bounds__(256) mrf_isgmr_presum(const MrfPresumParams P)
+{
+    typedef float vecf __attribute__((ext_vector_type(VEC)));
+    const long long n = P.NL / VEC;
+    for (long long e4 = (long long)blockIdx.x * blockDim.x + threadIdx.x; e4 < n; e4 += (long long)gridDim.x * blockDim.x) {
+        const long long e = e4 * VEC;
+        const vecf th = *reinterpret_cast<const vecf *>(P.unary + e);
+        vecf mv[RT];
+#pragma unroll
+        for (int d = 0; d < RT; ++d)
+            if (d < P.R) mv[d] = *reinterpret_cast<const vecf *>(P.m + (size_t)d * P.NL + e);
+#pragma unroll
+        for (int d = 0; d < RT; ++d) {
+            if (d >= P.R) continue;
+            const int od = P.opp[d];
+            if (od >= 0 && od < d) continue;          // the pair was done at its lower index
+            vecf a = th;
+#pragma unroll
+            for (int c = 0; c < RT; ++c)
+                if (c < P.R && c != d && c != od) a = a + mv[c];
+            *reinterpret_cast<vecf *>(P.out + (size_t)d * P.NL + e) = a;
+        }
+    }
+}
+
 // ---- fast path: V(mu, lambda) = f(|mu - lambda|) with f non-decreasing and constant (= fT)
 // from distance TW on (truncated linear / quadratic models, Sec. 5.1) ------------------------
 //
@@ -776,12 +819,12 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
     const float vz = mrf_opaque_zero_f();     // keeps the flags below in vector registers
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
         is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
@@ -867,9 +910,9 @@ mrf_fwd_sweep_window(const MrfFwdParams P)
                     v = rcur[u] * v;
                     v = v - mrm;
                 } else {
-                    v = v + carry[s];
 #pragma unroll
                     for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                    v = v + carry[s];
                 }
                 const int lam = lane + 64 * s;
                 if (lam < L) hbuf[lam] = v;
@@ -1215,12 +1258,12 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
         is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
@@ -1560,9 +1603,9 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
                     v = rho * v;
                     v = v - mrm;
                 } else {
-                    v = v + carry[s];
 #pragma unroll
                     for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c][s], v);
+                    v = v + carry[s];
                 }
                 const int lam = lane + 64 * s;
                 // (lanes past L rewrite the +inf their ring entries hold anyway: no divergence; what
@@ -1704,12 +1747,12 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
     const float vz = mrf_opaque_zero_f();     // keeps the flags below in vector registers
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
         is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
@@ -1782,9 +1825,9 @@ mrf_fwd_sweep_window_split(const MrfFwdParams P)
                 v = rho * v;
                 v = v - mrm;
             } else {
-                v = v + carry;
 #pragma unroll
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+                v = v + carry;
             }
             if (valid) hb[lam] = v;
             const float hloc = mrf_wave_min(valid ? v : INFINITY);
@@ -2081,12 +2124,12 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
     const int n_pre = P.n_pre[r], n_src = P.n_src[r], rm_slot = P.rm_slot[r];
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)P.src_dir[r][c - 1] * N * L : src[0];
         use[c] = ((c <= n_src) ? 1.0f : 0.0f) + vz;
         is_rm[c] = ((c - 1 == rm_slot) ? 1.0f : 0.0f) + vz;
     }
@@ -2187,9 +2230,9 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
                 v = rho * v;
                 v = v - mrm;
             } else {
-                v = v + carry;
 #pragma unroll
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+                v = v + carry;
             }
             // (lanes past L rewrite the +inf their ring entries hold anyway: no divergence; what
             // they carry from node to node is never looked at)
@@ -2392,12 +2435,12 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
 
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
-    src[0] = P.unary;
+    src[0] = P.unary + (size_t)P.unary_slab[r] * N * L;
     use[0] = 1.0f;
     is_rm[0] = 0.0f;
 #pragma unroll
     for (int c = 1; c < RMAX; ++c) {
-        src[c] = (c <= n_src) ? P.m_in + (size_t)sdir[c - 1] * N * L : P.unary;
+        src[c] = (c <= n_src) ? P.m_in + (size_t)sdir[c - 1] * N * L : src[0];
         use[c] = (c <= n_src) ? 1.0f : 0.0f;
         is_rm[c] = (c - 1 == rm_slot) ? 1.0f : 0.0f;
     }
@@ -2519,9 +2562,9 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
                 v = rho * v;
                 v = v - mrm;
             } else {
-                v = v + carry;
 #pragma unroll
                 for (int c = 1; c < RMAX; ++c) v = __builtin_fmaf(use[c], cur[u][c], v);
+                v = v + carry;
             }
             const int slot = IDX ? (nn & (NR - 1)) : 0;
             if (IDX) {

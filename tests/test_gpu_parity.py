@@ -168,6 +168,41 @@ def test_dense_sweep_with_a_slice_of_labels_per_wavefront(oracle, case):
         np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
 
 
+PRESUM_CASES = [
+    # seed, B, H, W, L, dirs, K, integer_valued, truncated
+    (701, 1, 6, 7, 40, DIRS8, 3, False, False), (702, 2, 5, 6, 21, DIRS8, 3, True, False),
+    (703, 1, 5, 5, 33, DIRS16, 3, False, False), (704, 1, 7, 9, 96, DIRS8, 3, False, True),
+    (705, 1, 6, 8, 192, DIRS16, 2, True, True), (706, 1, 9, 5, 70, DIRS4, 4, False, True),
+    (707, 1, 5, 7, 13, ((0, 1), (1, 0), (1, 1)), 3, False, False),      # no direction has its opposite in the set
+    (708, 1, 3, 5, 7, ((0, 1), (0, -1), (1, 0)), 3, True, False),       # one pair and a single direction; N L odd
+    (709, 1, 12, 11, 130, DIRS8, 2, False, False),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", PRESUM_CASES, ids=lambda c: "seed%d" % c[0])
+def test_isgmr_sums_of_the_previous_iteration_formed_once(oracle, case):
+    """ISGMR forward where a streaming pass per iteration sums the unary and the previous iteration's
+    messages once per pair of opposite directions and the sweeps read that one array (Eq. isgmr):
+    against the oracle, and bit for bit against the sweeps that read every array themselves."""
+    import paper_1910_10892_amd as mrf
+    print("case presum", case[:5], len(case[5]), case[6:], flush=True)
+    seed, B, H, W, L, dirs, K, iv, trunc = case
+    if trunc:
+        pr = truncated_problem(seed, "isgmr", H, W, L, dirs, K, 1, 3.0, iv, "pos")
+    else:
+        pr = random_problem(seed, "isgmr", B, H, W, L, dirs, K, integer_valued=iv, symmetric=False)
+    try:
+        assert mrf.mrf_tune(17, 2) == 0
+        a = full_check(oracle, pr, want_V=False)
+        assert mrf.mrf_tune(17, 1) == 0
+        b = full_check(oracle, pr, want_V=False)
+    finally:
+        mrf.mrf_tune(17, 0)
+    for name in ("p", "q", "labels", "cost", "messages"):
+        np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
+
+
 def truncated_problem(seed, algo, H, W, L, dirs, K, kind, trunc, integer_valued, weights):
     """Truncated linear (kind 1) / quadratic (kind 2) pairwise with the kind announced, so the
     library may take its window path.  weights: 'pos' | 'zero_mix' | 'neg_mix'."""
@@ -699,13 +734,13 @@ def _full_size_check(oracle, pr, want_V, fwd_launch, bwd_launch):
 def test_full_size_driving_stereo_config_isgmr(oracle):
     """The largest benchmark shape whole, as bench.py times it: ISGMR, 384 x 1248, L = 192, 8
     directions, K = 3 -- 9,788 scanlines per launch, message and index arrays beyond 2^31 bytes.
-    The first iteration runs the launch with zero messages, the later ones the launch that reads
-    seven message arrays.  (The oracle's share of the test is about 35 s per iteration on 16 host
+    The first iteration runs the launch with zero messages, the later ones the same launch on the
+    per-pair sums that a streaming pass forms from the previous iteration's messages.  (The oracle's share of the test is about 35 s per iteration on 16 host
     threads.)"""
     _progress("case full config 3")
     pr = make_config(3)
     _full_size_check(oracle, pr, False,
-                     "mrf_fwd_sweep_window<3,8,1,false,2> grid=9788 block=64",
+                     "mrf_fwd_sweep_window<3,4,2,false,2> grid=9788 block=64 after mrf_isgmr_presum<8,4>",
                      "mrf_bwd_sweep<3,1,2,false,true,false> grid=2447 block=256")
 
 
@@ -801,7 +836,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
@@ -964,7 +999,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
     f = oracle_forward(oracle, pr, threads=True)
     b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
