@@ -281,6 +281,21 @@ hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long bloc
     return hipErrorInvalidValue;
 }
 
+// ISGMR sweeps that read one array only
+template <int LP>
+hipError_t launch_window_one(const MrfFwdParams &P, int tw, long long blocks, hipStream_t st)
+{
+    note_launch(0, "mrf_fwd_sweep_window", blocks, 64, "%d,1,4,false,%d", LP, tw);
+#define MRF_W(twv) \
+    if (tw == twv) { \
+        hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, 1, 4, false, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2) MRF_W(8) MRF_W(16)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
 template <int LP, int RMAX, int D, int NI>
 hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
@@ -462,6 +477,12 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         }
         if (ms + 1 <= 8) {
             P.NW = 1;
+            // (nothing but the start term to read: the first iteration of ISGMR, and its later ones after
+            // mrf_isgmr_presum; a deeper prefetch fits in the registers the other sources would take)
+#define MRF_WCASE(lp) \
+            if (LPw == lp && ms == 0 && algo == MRF_ISGMR) return launch_window_one<lp>(P, tw, blocks, st);
+            MRF_WCASE(1) MRF_WCASE(2) MRF_WCASE(3) MRF_WCASE(4)
+#undef MRF_WCASE
 #define MRF_WCASE(lp) \
             if (LPw == lp && ms + 1 <= 4) return launch_window<lp, 4, (lp <= 2 ? 4 : 2)>(P, algo, tw, blocks, st); \
             if (LPw == lp) return launch_window<lp, 8, (lp <= 2 ? 2 : 1)>(P, algo, tw, blocks, st);
@@ -654,17 +675,20 @@ template <int LP, int NS, int D>
 hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
     const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_WAVES);
-    note_launch(1, "mrf_bwd_sweep", blocks, 64 * MRF_BWD_WAVES, "%d,%d,%d,%s,%s,%s", LP, NS, D,
-                (P.gw && P.v_mode == 0) ? "true" : "false",
-                (!(P.rho_e && P.gw && P.v_mode == 0) && !(P.rho_e || P.gE) && !(P.gw && P.v_mode == 0) && P.hot_label) ? "true" : "false",
-                (P.rho_e || P.gE) ? "true" : "false");
+    const bool hot = !(P.rho_e || P.gE) && !(P.gw && P.v_mode == 0) && P.hot_label;
+    const bool no_unary = hot && NS == 1 && P.unary_dir < 0;
+    note_launch(1, "mrf_bwd_sweep", blocks, 64 * MRF_BWD_WAVES, "%d,%d,%d,%s,%s,%s%s", LP, NS, D,
+                (P.gw && P.v_mode == 0) ? "true" : "false", hot ? "true" : "false",
+                (P.rho_e || P.gE) ? "true" : "false", no_unary ? ",false" : "");
     if (P.rho_e && P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false, true>), grid, block, lds, st, P);
     else if (P.rho_e || P.gE)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, false, true>), grid, block, lds, st, P);
     else if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false>), grid, block, lds, st, P);
-    else if (P.hot_label)
+    else if (no_unary) {
+        if constexpr (NS == 1) hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true, false, false>), grid, block, lds, st, P);
+    } else if (P.hot_label)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true>), grid, block, lds, st, P);
     else
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, false>), grid, block, lds, st, P);

@@ -97,7 +97,9 @@ __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L,
 // instead of per direction: what direction c scattered to node i came over the edge (i, i+c)
 // and carries that edge's rho.  Gradient of per-edge pairwise tables (P.gE): entry
 // (p(lambda), lambda) of the edge's table receives g(lambda) (Eq. supp-gradient-pairwise).
-template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false>
+// UNARY = false: no direction of the launch forms grad theta_i (P.unary_dir < 0: ISGMR leaves it to
+// mrf_isgmr_bwd_combine), so nothing of it is loaded or kept in registers.
+template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false, bool UNARY = true>
 __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
@@ -136,7 +138,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
         const long long head = ((long long)b * P.g.H + y0) * P.g.W + x0;
         const long long nstep = (long long)dh * P.g.W + dw;
         const double cscale = (double)P.carry_scale[r];
-        const bool own_unary = (r == P.unary_dir);
+        const bool own_unary = UNARY && (r == P.unary_dir);
         const bool unary_old = own_unary && !P.unary_init;
         const size_t umul = unary_old ? 1 : 0;
         const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
@@ -181,12 +183,12 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 
         // prefetch registers: step tt handles node len-1-tt (clamped at the first node)
         float cur[D][NS][LP], nxt[D][NS][LP];
-        float ucur[D][LP], unxt[D][LP];       // old grad theta_i (only read when accumulating)
+        float ucur[D][UNARY ? LP : 1], unxt[D][UNARY ? LP : 1];       // old grad theta_i (only read when accumulating)
         int pcur[D][LP], pnxt[D][LP];
         int qcur[D], qnxt[D];
         float wcur[D], wnxt[D];
         float rcur[D][NS + 1], rnxt[D][NS + 1];   // RHOE: rho of each source slot's edge, then of this direction's own edge
-        auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[LP], int (&pdst)[LP], int &qdst, float &wdst,
+        auto prefetch = [&](float (&dst)[NS][LP], float (&udst)[UNARY ? LP : 1], int (&pdst)[LP], int &qdst, float &wdst,
                             float (&rdst)[NS + 1], int tt) {
             int n = len - 1 - tt;
             n = n > 0 ? n : 0;
@@ -208,7 +210,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 const int lc = lam < L ? lam : 0;
 #pragma unroll
                 for (int c = 0; c < NS; ++c) dst[c][s] = src[c][(size_t)i * L + lc];
-                udst[s] = P.gunary[((size_t)i * L + lc) * umul];   // one cached word unless it is needed
+                if constexpr (UNARY) udst[s] = P.gunary[((size_t)i * L + lc) * umul];   // one cached word unless it is needed
                 pdst[s] = pbase[(size_t)i * L + lc];
             }
             qdst = qbase[(size_t)i + vzero];
@@ -253,7 +255,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     for (int c = 0; c < NS; ++c) acc = __builtin_fma(cGn[c], (double)cur[u][c][s], acc);
                     g[s] = (lane + 64 * s < L) ? acc : 0.0;
                 }
-                if (own_unary) {
+                if constexpr (UNARY) if (own_unary) {
                     // grad theta_i: everything every direction passed back to node i
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
@@ -297,17 +299,35 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                         if (lane + 64 * s < L && pv[s] == hot) hpart += g[s];
                 }
                 // back Eq. isgmr-norm: g(q) -= sum_lambda g(lambda)
-                const double tot = mrf_wave_sum_f64(part);
-                double hsum = 0.0;
+                double tot, hsum = 0.0;
                 int qv = __builtin_amdgcn_readfirstlane(qcur[u]);
                 qv = qv < L ? qv : L - 1;
+                // HOT: the edge-weight gradient sum_lambda g(lambda) V(p(lambda), lambda) is formed from g
+                // before the correction at q, in the same reduction as the two other sums, and corrected
+                // by tot V(p(q), q) afterwards
+                double gw_sum = 0.0;
                 if (HOT) {
-                    hsum = mrf_wave_sum_f64(hpart);
+                    double wpart = 0.0;
+                    float vq = 0.0f;
+                    if (P.gw) {
+#pragma unroll
+                        for (int s = 0; s < LP; ++s) {
+                            const int lam = lane + 64 * s;
+                            const int dist = pv[s] > lam ? pv[s] - lam : lam - pv[s];
+                            const float vv = vl[P.v_mode == 1 ? pv[s] * L + lam : dist];
+                            wpart = __builtin_fma(g[s], (double)vv, wpart);       // (g is 0 beyond L)
+                            if ((qv >> 6) == s) vq = mrf_readlane_f32(vv, qv & 63);
+                        }
+                    }
+                    mrf_wave_sum3_f64(part, hpart, wpart, tot, hsum, gw_sum);
                     int pq = 0;
 #pragma unroll
                     for (int s = 0; s < LP; ++s)
                         if ((qv >> 6) == s) pq = __builtin_amdgcn_readlane(pv[s], qv & 63);
                     if (pq == hot) hsum -= tot;
+                    gw_sum = __builtin_fma(-tot, (double)vq, gw_sum);
+                } else {
+                    tot = mrf_wave_sum_f64(part);
                 }
 #pragma unroll
                 for (int s = 0; s < LP; ++s)
@@ -338,7 +358,11 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
 
                 // pairwise gradients (off the node-to-node chain)
                 const double wgt = (double)wcur[u];
-                if (P.gw) {
+                if (HOT && P.gw) {
+                    if (update && lane == 0)
+                        __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)gw_sum, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                } else if (P.gw) {
                     double acc = 0.0;
 #pragma unroll
                     for (int s = 0; s < LP; ++s) {
@@ -393,7 +417,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                 for (int c = 0; c <= NS; ++c) rcur[u][c] = rnxt[u][c];
 #pragma unroll
                 for (int s = 0; s < LP; ++s) {
-                    ucur[u][s] = unxt[u][s];
+                    if constexpr (UNARY) ucur[u][s] = unxt[u][s];
                     pcur[u][s] = pnxt[u][s];
 #pragma unroll
                     for (int c = 0; c < NS; ++c) cur[u][c][s] = nxt[u][c][s];

@@ -740,8 +740,8 @@ def test_full_size_driving_stereo_config_isgmr(oracle):
     _progress("case full config 3")
     pr = make_config(3)
     _full_size_check(oracle, pr, False,
-                     "mrf_fwd_sweep_window<3,4,2,false,2> grid=9788 block=64 after mrf_isgmr_presum<8,4>",
-                     "mrf_bwd_sweep<3,1,2,false,true,false> grid=2447 block=256")
+                     "mrf_fwd_sweep_window<3,1,4,false,2> grid=9788 block=64 after mrf_isgmr_presum<8,4>",
+                     "mrf_bwd_sweep<3,1,2,false,true,false,false> grid=2447 block=256")
 
 
 def test_full_size_denoising_config_trwp(oracle):
