@@ -314,7 +314,7 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                         for (int s = 0; s < LP; ++s) {
                             const int lam = lane + 64 * s;
                             const int dist = pv[s] > lam ? pv[s] - lam : lam - pv[s];
-                            const float vv = vl[P.v_mode == 1 ? pv[s] * L + lam : dist];
+                            const float vv = lam < L ? vl[P.v_mode == 1 ? pv[s] * L + lam : dist] : 0.0f;
                             wpart = __builtin_fma(g[s], (double)vv, wpart);       // (g is 0 beyond L)
                             if ((qv >> 6) == s) vq = mrf_readlane_f32(vv, qv & 63);
                         }
