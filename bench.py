@@ -89,16 +89,20 @@ def cpu_baseline(index, algo, crop):
 def measure(index, algo, dense, steps, warmup, traffic, tune=()):
     """One benchmark shape with one algorithm: ms per forward + backward, the sweeps alone (HIP
     events the library records on its stream around its sweep launches), kernels, rooflines."""
-    import torch
     from mrf_inputs import make_config
-    from gpu_harness import GpuProblem
-    import paper_1910_10892_amd as mrf
-
     pr = make_config(index, algo=algo)
     if dense:
         # the same potentials announced as a general dense table: the O(L^2) sweep runs
         pr.pairwise_kind = 0
         pr.name += "_dense"
+    return measure_problem(pr, dense, steps, warmup, traffic)
+
+
+def measure_problem(pr, dense, steps, warmup, traffic):
+    import torch
+    from gpu_harness import GpuProblem
+    import paper_1910_10892_amd as mrf
+
     g = GpuProblem(pr, want_messages=False)
     updates = pr.message_updates()
     E = edges_per_direction(pr)
@@ -259,6 +263,28 @@ def heads(index, algo):
     return {"workload": pr.name, "energy": rf(e_bytes, t_e), "softmin_l1": rf(l_bytes, t_l)}
 
 
+def speed_table(steps):
+    """The shape of the paper's speed table (Sec. 5.3): one 256 x 512 image, 32 or 96 labels, 4, 8 or 16
+    directions, both algorithms, a general (dense) pairwise table with per-edge weights, forward and
+    backward with every gradient.  The paper does not state the iteration count of its timings: K = 5
+    here, and the times are given per iteration."""
+    from mrf_inputs import DIRS4, DIRS8, DIRS16, random_problem
+    rows = []
+    for L in (32, 96):
+        for dirs in (DIRS4, DIRS8, DIRS16):
+            for algo in ("isgmr", "trwp"):
+                pr = random_problem(19101089 + L + len(dirs), algo, 1, 256, 512, L, dirs, 5)
+                pr.name = "speed_table_256x512_L%d_R%d_%s" % (L, len(dirs), algo)
+                m = measure_problem(pr, False, steps, 1, {})
+                rows.append({"workload": pr.name, "algorithm": algo, "labels": L, "directions": len(dirs), "iterations": pr.K,
+                             "forward_ms_per_iteration": m["forward_sweeps_ms"] / pr.K,
+                             "backward_ms_per_iteration": m["backward_sweeps_ms"] / pr.K,
+                             "updates_per_s": m["updates_per_s"], "kernels": m["kernels"],
+                             "forward_frac": m["roofline_forward"]["frac"], "forward_bound": m["roofline_forward"]["bound"],
+                             "backward_frac": m["roofline_backward"]["frac"]})
+    return rows
+
+
 def energy_protocol():
     """The protocol of the paper's energy tables (Sec. 5.1) on the synthetic stereo and denoising
     shapes: K = 1 and K = 50 iterations of both algorithms, the energy of the labelling each returns
@@ -309,6 +335,9 @@ def main():
     ap.add_argument("--energy-protocol", action="store_true",
                     help="also run K = 1 and K = 50 iterations of both algorithms on configurations 2 and 4 and "
                          "report the energy of each labelling (extra \"energy_protocol\" array)")
+    ap.add_argument("--speed-table", action="store_true",
+                    help="also time the shape of the paper's speed table: 256 x 512, 32 / 96 labels, 4 / 8 / 16 "
+                         "directions, dense pairwise table, both algorithms (extra \"speed_table\" array)")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
                     help="experiment: set a kernel-choice knob of mrf_tune (results never depend on them)")
     args = ap.parse_args()
@@ -370,6 +399,8 @@ def main():
         out["heads"] = heads(head_run[0], head_run[1])
     if args.energy_protocol:
         out["energy_protocol"] = energy_protocol()
+    if args.speed_table:
+        out["speed_table"] = speed_table(max(2, min(args.steps, 3)))
     if not args.no_cpu_baseline:
         crops = {1: (32, 48), 2: (128, 256), 3: (56, 144), 4: (24, 32), 5: (256, 256)}
         out["cpu_baseline"] = cpu_baseline(head_run[0], head_run[1], crops[head_run[0]])

@@ -300,6 +300,8 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 17: ISGMR forward in which one streaming pass per iteration sums the unary and the previous
  *           iteration's messages once per pair of opposite directions, so that every sweep reads one array
  *           instead of R - 1: 0 = from six directions on, 1 = never, 2 = always (more than one iteration)
+ *   knob 18: backward sweep with grad_pairwise for 33..128 labels: the table accumulates in LDS, one per
+ *           workgroup of eight wavefronts, instead of in a slot per wavefront in global memory: 0 = yes, 1 = no
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
 int mrf_tune(int knob, int value);
 

@@ -122,6 +122,7 @@ MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
 MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_isgmr_lazy, 0); // ISGMR backward without a combine pass per iteration (up to 4 directions): 0 auto, 1 never
 MRF_G(int g_tune_isgmr_presum, 0); // ISGMR forward with the per-pair sums of the previous iteration formed once: 0 from six directions, 1 never, 2 always
+MRF_G(int g_tune_gv_tile, 0);      // V gradient of 33..128 labels in one LDS table per workgroup: 0 yes, 1 no (a slot per wavefront in global memory)
 MRF_G(int g_tune_dense_sliced, 0); // dense sweep for more than 64 labels with a slice of the labels per wavefront: 0 yes, 1 no
 MRF_G(int g_tune_spin_limit, 0); // turns a wait between wavefronts may take: 0 = default
 MRF_G(int g_tune_pack_idx, 0);   // index wavefronts in the packed dense sweep: 0 by launch size, 1 never, 2 always
@@ -695,6 +696,30 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
     return hipGetLastError();
 }
 
+// The V gradient in one LDS table per workgroup of MRF_BWD_TILE_WAVES wavefronts (33..128 labels)
+#define MRF_BWD_TILE_WAVES 8
+template <int LP, int NS, int D>
+hipError_t launch_bwd_tile(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
+{
+    const dim3 grid((unsigned)blocks), block(64 * MRF_BWD_TILE_WAVES);
+    const bool vg = P.gw && P.v_mode == 0;
+    note_launch(1, "mrf_bwd_sweep", blocks, 64 * MRF_BWD_TILE_WAVES, "%d,%d,%d,%s,false,false,true,%d", LP, NS, D, vg ? "true" : "false",
+                MRF_BWD_TILE_WAVES);
+#define MRF_T_GO(...) \
+    do { \
+        if (lds > 64 * 1024) { \
+            const hipError_t ea_ = hipFuncSetAttribute(reinterpret_cast<const void *>(&__VA_ARGS__), \
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (ea_ != hipSuccess) return ea_; \
+        } \
+        hipLaunchKernelGGL((__VA_ARGS__), grid, block, lds, st, P); \
+    } while (0)
+    if (vg) MRF_T_GO(mrf_bwd_sweep<LP, NS, D, true, false, false, true, MRF_BWD_TILE_WAVES>);
+    else MRF_T_GO(mrf_bwd_sweep<LP, NS, D, false, false, false, true, MRF_BWD_TILE_WAVES>);
+#undef MRF_T_GO
+    return hipGetLastError();
+}
+
 template <int NS, int D>
 hipError_t launch_bwd_split(const MrfBwdParams &P, long long blocks, size_t lds, hipStream_t st)
 {
@@ -855,6 +880,24 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         if (ns == 1) return launch_bwd_split<1, 4>(P, sblocks, slds, st);
         if (ns == 4) return launch_bwd_split<4, 4>(P, sblocks, slds, st);
         return launch_bwd_split<8, 2>(P, sblocks, slds, st);
+    }
+    // the V gradient of 33..128 labels: one table in LDS per workgroup, more wavefronts per workgroup
+    if (P.gV && !P.gv_lds && !(P.rho_e || P.gE) && LP <= 2 && g_tune_gv_tile != 1) {
+        const size_t tlds = sizeof(double) * ((size_t)MRF_BWD_TILE_WAVES * 64 * LP + (size_t)L * L) +
+                            sizeof(float) * (P.v_mode == 1 ? (size_t)L * L : (P.v_mode == 2 ? (size_t)L : 0));
+        if (tlds <= 156 * 1024) {
+            long long tblocks = (P.total_scanlines + MRF_BWD_TILE_WAVES - 1) / MRF_BWD_TILE_WAVES;
+            if (tblocks > grad_slots(L)) tblocks = grad_slots(L);
+            P.gv_lds = 2;
+            P.hot_label = 0;
+#define MRF_TCASE(lp) \
+            if (LP == lp && ns == 1) return launch_bwd_tile<lp, 1, 4>(P, tblocks, tlds, st); \
+            if (LP == lp && ns == 4) return launch_bwd_tile<lp, 4, 4>(P, tblocks, tlds, st); \
+            if (LP == lp && ns == 8) return launch_bwd_tile<lp, 8, 2>(P, tblocks, tlds, st); \
+            if (LP == lp && ns == 16) return launch_bwd_tile<lp, 16, 1>(P, tblocks, tlds, st);
+            MRF_TCASE(1) MRF_TCASE(2)
+#undef MRF_TCASE
+        }
     }
 #define MRF_BCASE(lp) \
     if (LP == lp && ns == 1) return launch_bwd<lp, 1, (lp >= 3 ? 2 : 4)>(P, blocks, lds, st); \
@@ -1364,6 +1407,7 @@ int mrf_tune(int knob, int value)
     if (knob == 15) { g_tune_isgmr_lazy = value; return MRF_OK; }
     if (knob == 16) { g_tune_dense_sliced = value; return MRF_OK; }
     if (knob == 17) { g_tune_isgmr_presum = value; return MRF_OK; }
+    if (knob == 18) { g_tune_gv_tile = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

@@ -65,7 +65,8 @@ struct MrfBwdParams {
     int unary_init;                        // grad theta_i is assigned (first iteration) / accumulated
     float *gw;                             // [R][N] or NULL, accumulated over iterations
     double *gV;                            // [slots][L][L] or NULL, one slot per wavefront
-    int gv_lds;                            // accumulate grad V in LDS and flush once per wavefront
+    int gv_lds;                            // grad V accumulates in LDS: 1 = a table per wavefront, flushed once per wavefront;
+                                           // 2 = one table per workgroup (LDS adds), flushed once into the workgroup's slot
     int v_mode;                            // V for grad w: 0 global, 1 copy in LDS, 2 first row in LDS
     int hot_label;                         // pre-reduce the most popular scatter target (truncated models)
     float carry_scale[MRF_MAXR];           // rho_d (TRWP) or 1 (ISGMR)
@@ -99,29 +100,32 @@ __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L,
 // (p(lambda), lambda) of the edge's table receives g(lambda) (Eq. supp-gradient-pairwise).
 // UNARY = false: no direction of the launch forms grad theta_i (P.unary_dir < 0: ISGMR leaves it to
 // mrf_isgmr_bwd_combine), so nothing of it is loaded or kept in registers.
-template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false, bool UNARY = true>
-__global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwdParams P)
+// WAVES: wavefronts per workgroup (more of them share the one V-gradient table of P.gv_lds == 2).
+template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false, bool UNARY = true, int WAVES = MRF_BWD_WAVES>
+__global__ void __launch_bounds__(64 * WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
     const int L = P.g.L;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     double *sbuf = reinterpret_cast<double *>(mrf_bsmem) + wv * 64 * LP;
-    double *gvl = reinterpret_cast<double *>(mrf_bsmem) + MRF_BWD_WAVES * 64 * LP + (P.gv_lds ? wv * L * L : 0);
-    float *vl = reinterpret_cast<float *>(reinterpret_cast<double *>(mrf_bsmem) + MRF_BWD_WAVES * 64 * LP +
-                                          (P.gv_lds ? MRF_BWD_WAVES * L * L : 0));
-    const long long slot = (long long)blockIdx.x * MRF_BWD_WAVES + wv;
-    const long long nslots = (long long)gridDim.x * MRF_BWD_WAVES;
+    double *gvl = reinterpret_cast<double *>(mrf_bsmem) + WAVES * 64 * LP + (P.gv_lds == 1 ? wv * L * L : 0);
+    float *vl = reinterpret_cast<float *>(reinterpret_cast<double *>(mrf_bsmem) + WAVES * 64 * LP +
+                                          (P.gv_lds == 1 ? WAVES * L * L : (P.gv_lds == 2 ? L * L : 0)));
+    const long long slot = (long long)blockIdx.x * WAVES + wv;
+    const long long nslots = (long long)gridDim.x * WAVES;
     const long long N = P.g.N;
-    double *gVs = P.gV ? P.gV + (size_t)slot * L * L : nullptr;
+    double *gVs = P.gV ? P.gV + (size_t)(P.gv_lds == 2 ? (long long)blockIdx.x : slot) * L * L : nullptr;
     const int vzero = mrf_opaque_zero();
 
     if (P.v_mode == 1)
         for (int e = threadIdx.x; e < L * L; e += blockDim.x) vl[e] = P.V[e];
     else if (P.v_mode == 2)
         for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
-    if (gVs && P.gv_lds)
+    if (gVs && P.gv_lds == 1)
         for (int e = lane; e < L * L; e += 64) gvl[e] = 0.0;
+    if (gVs && P.gv_lds == 2)
+        for (int e = threadIdx.x; e < L * L; e += blockDim.x) gvl[e] = 0.0;
     __syncthreads();
 
     for (long long sl = slot; sl < P.total_scanlines; sl += nslots) {
@@ -402,7 +406,9 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
                     for (int s = 0; s < LP; ++s) {
                         const int lam = lane + 64 * s;
                         if (update && lam < L) {
-                            if (P.gv_lds) gvl[pv[s] * L + lam] = __builtin_fma(wgt, g[s], gvl[pv[s] * L + lam]);
+                            if (P.gv_lds == 1) gvl[pv[s] * L + lam] = __builtin_fma(wgt, g[s], gvl[pv[s] * L + lam]);
+                            else if (P.gv_lds == 2) __hip_atomic_fetch_add(&gvl[pv[s] * L + lam], wgt * g[s], __ATOMIC_RELAXED,
+                                                                           __HIP_MEMORY_SCOPE_WORKGROUP);
                             else __hip_atomic_fetch_add(&gVs[(size_t)pv[s] * L + lam], wgt * g[s],
                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
@@ -425,9 +431,15 @@ __global__ void __launch_bounds__(64 * MRF_BWD_WAVES) mrf_bwd_sweep(const MrfBwd
             }
         }
     }
-    if (gVs && P.gv_lds) {
+    if (gVs && P.gv_lds == 1) {
         mrf_wave_lds_fence();
         for (int e = lane; e < L * L; e += 64) gVs[e] += gvl[e];
+    }
+    if (P.gv_lds == 2) {
+        // (every wavefront of the workgroup arrives here; the slot belongs to this workgroup alone)
+        __syncthreads();
+        if (gVs)
+            for (int e = threadIdx.x; e < L * L; e += blockDim.x) gVs[e] += gvl[e];
     }
 }
 

@@ -836,7 +836,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
@@ -999,7 +999,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
     f = oracle_forward(oracle, pr, threads=True)
     b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
