@@ -660,7 +660,9 @@ int run_forward(const mrf_problem *pr, int algo, float *cost, uint8_t *labels, u
     A.unary = pr->unary; A.m = final_m; A.cost = cost; A.labels = labels;
     long long ablocks = (N + 3) / 4;
     if (ablocks > 65536) ablocks = 65536;
-    hipLaunchKernelGGL(mrf_aggregate, dim3((unsigned)ablocks), dim3(256), 0, st, A);
+    if (R <= 4) hipLaunchKernelGGL(mrf_aggregate<4>, dim3((unsigned)ablocks), dim3(256), 0, st, A);
+    else if (R <= 8) hipLaunchKernelGGL(mrf_aggregate<8>, dim3((unsigned)ablocks), dim3(256), 0, st, A);
+    else hipLaunchKernelGGL(mrf_aggregate<16>, dim3((unsigned)ablocks), dim3(256), 0, st, A);
     { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
     if (messages) {
         const hipError_t e_ = hipMemcpyAsync(messages, final_m, pk * sizeof(float), hipMemcpyDeviceToDevice, st);
@@ -1379,7 +1381,7 @@ const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ?
 
 const char *mrf_last_sweep_launch(int backward) { return g_last_launch[backward ? 1 : 0]; }
 
-const char *mrf_version(void) { return "0.2.0"; }
+const char *mrf_version(void) { return "0.3.0"; }
 
 int mrf_set_sweep_events(void *start_event, void *stop_event)
 {

@@ -701,6 +701,8 @@ struct MrfAggParams {
     uint8_t *labels;     // may be NULL
 };
 
+// RT: bound on R (all loads of a node are issued before the first addition)
+template <int RT>
 __global__ void __launch_bounds__(256) mrf_aggregate(const MrfAggParams P)
 {
     const int lane = threadIdx.x & 63;
@@ -716,7 +718,13 @@ __global__ void __launch_bounds__(256) mrf_aggregate(const MrfAggParams P)
             c[s] = INFINITY;
             if (lam < L) {
                 float v = P.no_unary ? 0.0f : P.unary[(size_t)i * L + lam];
-                for (int d = 0; d < P.R; ++d) v = v + P.m[((size_t)d * P.N + i) * L + lam];
+                float mv[RT];
+#pragma unroll
+                for (int d = 0; d < RT; ++d)
+                    if (d < P.R) mv[d] = P.m[((size_t)d * P.N + i) * L + lam];
+#pragma unroll
+                for (int d = 0; d < RT; ++d)
+                    if (d < P.R) v = v + mv[d];
                 c[s] = v;
                 P.cost[(size_t)i * L + lam] = v;
             }
