@@ -98,6 +98,9 @@ def measure(index, algo, dense, steps, warmup, traffic, tune=()):
     return measure_problem(pr, dense, steps, warmup, traffic)
 
 
+GRAPH = False      # --graph: also time the same step replayed from a captured HIP graph
+
+
 def measure_problem(pr, dense, steps, warmup, traffic):
     import torch
     from gpu_harness import GpuProblem
@@ -128,6 +131,21 @@ def measure_problem(pr, dense, steps, warmup, traffic):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
+    ms_per_step_graph = None
+    if GRAPH:
+        # the library allocates nothing and never waits for the stream: the step can be captured once
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     for e in ev:
@@ -209,7 +227,7 @@ def measure_problem(pr, dense, steps, warmup, traffic):
         "passes": "forward+backward" if backward else "forward",
         "gradients": (["unary", "edge_weight"] + (["pairwise"] if want_V else [])) if backward else [],
         "ms_per_step": ms_per_step, "updates_per_s": updates / (ms_per_step * 1e-3),
-        "forward_sweeps_ms": fwd_sweeps_ms, "backward_sweeps_ms": bwd_sweeps_ms,
+        "forward_sweeps_ms": fwd_sweeps_ms, "backward_sweeps_ms": bwd_sweeps_ms, "ms_per_step_graph_replay": ms_per_step_graph,
         "forward_updates_per_s": updates / (fwd_sweeps_ms * 1e-3),
         "backward_updates_per_s": updates / (bwd_sweeps_ms * 1e-3) if backward else None,
         "kernels": {"forward": fwd_launch, "backward": bwd_launch if backward else None},
@@ -338,6 +356,9 @@ def main():
     ap.add_argument("--speed-table", action="store_true",
                     help="also time the shape of the paper's speed table: 256 x 512, 32 / 96 labels, 4 / 8 / 16 "
                          "directions, dense pairwise table, both algorithms (extra \"speed_table\" array)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture each step (forward + backward) into a HIP graph and time its replay "
+                         "(\"ms_per_step_graph_replay\" of every entry of \"configs\")")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
                     help="experiment: set a kernel-choice knob of mrf_tune (results never depend on them)")
     args = ap.parse_args()
@@ -349,6 +370,8 @@ def main():
     import torch
     import paper_1910_10892_amd as mrf
 
+    global GRAPH
+    GRAPH = args.graph
     mrf.load_library()      # no fallback: raises if libmrfmp.so is missing
     for kv in args.tune:
         knob, value = kv.split("=")
