@@ -499,8 +499,11 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
     const int rmax = (max_src + 1 <= 4) ? 4 : ((max_src + 1 <= 8) ? 8 : 16);
     // more than 64 labels: every wavefront owns 32 of them (unless a tuning knob or a per-edge variant asks
     // for the sweep in which every wavefront does the O(L) work of the whole node)
-    // (for 65..128 labels only on request: three wavefronts of 32 source labels are no faster than four of 24)
-    if ((LP >= 3 || (LP == 2 && g_tune_dense_sliced == 2)) && !generic && !P.sgm_std && g_tune_mch == 0 && g_tune_dense_sliced != 1) {
+    // (for 65..128 labels where the work outside the candidates is large: many source arrays, or a launch that
+    // fills the machine several times over; else three wavefronts of 32 source labels are no faster than four
+    // of 24: measured at 96 labels, 256 x 512, per iteration: TRWP with 8 directions 5.70 -> 4.01 ms, with 16
+    // 15.1 -> 8.8 ms, ISGMR with 16 directions 4.12 -> 3.74 ms, but TRWP with 4 directions 1.81 -> 1.96 ms)
+    if ((LP >= 3 || (LP == 2 && (g_tune_dense_sliced == 2 || rmax >= 8 || blocks >= 4096))) && !generic && !P.sgm_std && g_tune_mch == 0 && g_tune_dense_sliced != 1) {
         P.NW = (L + 31) / 32;
 #define MRF_SCASE(lp) \
         if (LP == lp && rmax == 4) return launch_fwd_sliced<lp, 4, 4>(P, algo, blocks, st); \
