@@ -1096,6 +1096,8 @@ mrf_fwd_sweep_window_duo(const MrfFwdParams P)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const bool index_wave = wave >= NW0;
+    // the wavefronts on the node-to-node chain go first wherever they share a SIMD with the others
+    if (!index_wave) __builtin_amdgcn_s_setprio(3);
 
     const long long blk = blockIdx.x;
     int ri = 0;
@@ -2000,6 +2002,8 @@ mrf_fwd_sweep_window_squad(const MrfFwdParams P)
     const MrfWaitBlock *const wait_block = &wait_lds;
     __syncthreads();
 
+    // the value wavefronts go first wherever they share a SIMD with index wavefronts
+    if (wv < NWV) __builtin_amdgcn_s_setprio(3);
     if (wv >= NWV) {
         // ---- p, q and all stores: index wavefront jw takes steps 1 + jw, 1 + jw + NI, ... ------
         const int jw = wv - NWV;
@@ -2406,6 +2410,7 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const bool index_wave = IDX && wave > 0;
+    if (IDX && !index_wave) __builtin_amdgcn_s_setprio(3);      // the value wavefront goes first on a shared SIMD
     const int seg = lane / SEG, lam = lane % SEG;
     const bool valid = lam < L;
     const int lamc = valid ? lam : 0;
