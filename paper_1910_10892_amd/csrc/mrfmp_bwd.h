@@ -318,7 +318,7 @@ __global__ void __launch_bounds__(64 * WAVES) mrf_bwd_sweep(const MrfBwdParams P
                         for (int s = 0; s < LP; ++s) {
                             const int lam = lane + 64 * s;
                             const int dist = pv[s] > lam ? pv[s] - lam : lam - pv[s];
-                            const float vv = lam < L ? vl[P.v_mode == 1 ? pv[s] * L + lam : dist] : 0.0f;
+                            const float vv = lam < L ? vl[P.v_mode == 1 ? __mul24(pv[s], L) + lam : dist] : 0.0f;
                             wpart = __builtin_fma(g[s], (double)vv, wpart);       // (g is 0 beyond L)
                             if ((qv >> 6) == s) vq = mrf_readlane_f32(vv, qv & 63);
                         }
@@ -374,10 +374,10 @@ __global__ void __launch_bounds__(64 * WAVES) mrf_bwd_sweep(const MrfBwdParams P
                         if (lam < L) {
                             float vv;
                             if (VG) {
-                                vv = P.V[(size_t)pv[s] * L + lam];
+                                vv = P.V[(size_t)__mul24(pv[s], L) + lam];
                             } else {
                                 const int dist = pv[s] > lam ? pv[s] - lam : lam - pv[s];
-                                vv = vl[P.v_mode == 1 ? pv[s] * L + lam : dist];
+                                vv = vl[P.v_mode == 1 ? __mul24(pv[s], L) + lam : dist];
                             }
                             acc = __builtin_fma(g[s], (double)vv, acc);
                         }
@@ -406,10 +406,10 @@ __global__ void __launch_bounds__(64 * WAVES) mrf_bwd_sweep(const MrfBwdParams P
                     for (int s = 0; s < LP; ++s) {
                         const int lam = lane + 64 * s;
                         if (update && lam < L) {
-                            if (P.gv_lds == 1) gvl[pv[s] * L + lam] = __builtin_fma(wgt, g[s], gvl[pv[s] * L + lam]);
-                            else if (P.gv_lds == 2) __hip_atomic_fetch_add(&gvl[pv[s] * L + lam], wgt * g[s], __ATOMIC_RELAXED,
+                            if (P.gv_lds == 1) gvl[__mul24(pv[s], L) + lam] = __builtin_fma(wgt, g[s], gvl[__mul24(pv[s], L) + lam]);
+                            else if (P.gv_lds == 2) __hip_atomic_fetch_add(&gvl[__mul24(pv[s], L) + lam], wgt * g[s], __ATOMIC_RELAXED,
                                                                            __HIP_MEMORY_SCOPE_WORKGROUP);
-                            else __hip_atomic_fetch_add(&gVs[(size_t)pv[s] * L + lam], wgt * g[s],
+                            else __hip_atomic_fetch_add(&gVs[(size_t)__mul24(pv[s], L) + lam], wgt * g[s],
                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
@@ -796,9 +796,9 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                         if (P.gw) {
                             float vv;
                             if (GV) {
-                                vv = vl[pv * L + lam];
+                                vv = vl[__mul24(pv, L) + lam];
                             } else if (VG) {
-                                vv = P.V[(size_t)pv * L + lam];
+                                vv = P.V[(size_t)__mul24(pv, L) + lam];
                             } else {
                                 const int dist = pv > lam ? pv - lam : lam - pv;
                                 vv = vl[dist];
@@ -806,7 +806,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                             acc = __builtin_fma(g, (double)vv, acc);
                         }
                         if (GV && update)
-                            gvl[pv * L + lam] = __builtin_fma((double)wlast, g, gvl[pv * L + lam]);
+                            gvl[__mul24(pv, L) + lam] = __builtin_fma((double)wlast, g, gvl[__mul24(pv, L) + lam]);
                     }
                 }
                 if (P.gw) {
@@ -995,10 +995,10 @@ __global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
                     if (valid) {
                         float vv;
                         if (VG) {
-                            vv = P.V[(size_t)pv * L + lam];
+                            vv = P.V[(size_t)__mul24(pv, L) + lam];
                         } else {
                             const int dist = pv > lam ? pv - lam : lam - pv;
-                            vv = vl[P.v_mode == 1 ? pv * L + lam : dist];
+                            vv = vl[P.v_mode == 1 ? __mul24(pv, L) + lam : dist];
                         }
                         acc = gn * (double)vv;
                     }
@@ -1007,7 +1007,7 @@ __global__ void __launch_bounds__(256) mrf_bwd_sweep_split(const MrfBwdParams P)
                     gw_node = update ? i : -1;
                 }
                 if (gVs && update && valid)
-                    __hip_atomic_fetch_add(&gVs[(size_t)pv * L + lam], wgt * gn, __ATOMIC_RELAXED,
+                    __hip_atomic_fetch_add(&gVs[(size_t)__mul24(pv, L) + lam], wgt * gn, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
                 par ^= 1;
             }
@@ -1233,13 +1233,13 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
 
                 const double wgt = (double)wcur[u];
                 if (P.gw) {
-                    double acc = valid ? g * (double)vl[pv * L + lc] : 0.0;
+                    double acc = valid ? g * (double)vl[__mul24(pv, L) + lc] : 0.0;
                     acc = mrf_segment_sum_f64<SEG>(acc);
                     if (update && lam == 0)
                         __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
                 }
-                if (gVs && update && valid) gvl[pv * L + lam] = __builtin_fma(wgt, g, gvl[pv * L + lam]);
+                if (gVs && update && valid) gvl[__mul24(pv, L) + lam] = __builtin_fma(wgt, g, gvl[__mul24(pv, L) + lam]);
             }
 #pragma unroll
             for (int u = 0; u < D; ++u) {

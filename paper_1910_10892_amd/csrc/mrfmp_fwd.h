@@ -361,7 +361,7 @@ mrf_fwd_sweep_sliced(const MrfFwdParams P)
     __shared__ __align__(16) float hbuf_all[NWMAX][MCH];         // h of every wavefront's slice (read by its owner only)
     __shared__ float2 part[NWMAX][SLOTS];                        // partial (min, argmin) of wavefront w for label lambda
     __shared__ float2 hmin[NWMAX];                               // home minimum and its label, per wavefront
-    const int L = P.g.L, NW = P.NW;
+    const int L = P.g.L;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     float *hbuf = hbuf_all[wv];
@@ -2445,6 +2445,11 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
         head = ((long long)b * P.g.H + y0) * P.g.W + x0;
     }
     const long long nstep = (long long)dh * P.g.W + dw;
+    // Entry offsets walk along the scanline by additions: every lane has a scanline of its own, and a 64-bit
+    // product per access and node costs four issue slots each.
+    const long long stepL = nstep * L;
+    const long long out0 = ((long long)r * N + head) * L + lam;      // entry of the first node in m_out / p
+    const long long outq0 = (long long)r * N + head;                 // and in q
 
     const float *src[RMAX];
     float use[RMAX], carry_at[RMAX + 1], is_rm[RMAX];
@@ -2493,7 +2498,9 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
         // index wavefront jw takes steps 1 + jw, 1 + jw + IDX, ...
         const int jw = wave - 1;
         int seen = 0;
-        for (int nn = 1 + jw; nn < maxlen; nn += (IDX > 0 ? IDX : 1)) {
+        long long io = out0 + (1 + jw) * stepL, iq = outq0 + (1 + jw) * nstep;
+        const long long io_step = (IDX > 0 ? IDX : 1) * stepL, iq_step = (IDX > 0 ? IDX : 1) * nstep;
+        for (int nn = 1 + jw; nn < maxlen; nn += (IDX > 0 ? IDX : 1), io += io_step, iq += iq_step) {
             int wait_turns = 0;
             while (seen < nn) {
                 seen = __builtin_amdgcn_readfirstlane(
@@ -2503,7 +2510,6 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
             const int slot = nn & (NR - 1);
             const bool act = act_seg && nn < len;
-            const long long i = head + (long long)nn * nstep;
             const float wgt = wring[slot][lane];
             float dl[MU];
 #pragma unroll
@@ -2527,9 +2533,9 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             const float tq = mrf_segment_min<SEG>(tv);
             const int qidx = mrf_segment_first<SEG>(__ballot(tv == tq), lane);
             if (act && valid) {
-                P.m_out[((size_t)r * N + i) * L + lam] = tv - tq;
-                P.p[((size_t)r * N + i) * L + lam] = (uint8_t)bidx;
-                if (lam == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+                P.m_out[io] = tv - tq;
+                P.p[io] = (uint8_t)bidx;
+                if (lam == 0) P.q[iq] = (uint8_t)qidx;
             }
         }
         return;
@@ -2539,27 +2545,33 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
     const int lastsrc = len >= 2 ? len - 2 : 0;
     float cur[D][RMAX], nxt[D][RMAX];
     float wcur[D], wnxt[D];
-    auto prefetch = [&](float (&dst)[RMAX], float &wdst, int nj) {
-        nj = nj < lastsrc ? nj : lastsrc;          // past the end: reload the last one, never used
-        const long long j = head + (long long)nj * nstep;
+    // source nodes 0, 1, 2, ... in the order of the calls; past the end: reload the last one, never used
+    int pf_n = 0;
+    long long pf_off = head * L + lamc;
+    long long pf_w = (len >= 2 ? head + nstep : head) * P.w_mul;
+    const long long stepW = nstep * P.w_mul;
+    auto prefetch = [&](float (&dst)[RMAX], float &wdst) {
 #pragma unroll
-        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][(size_t)j * L + lamc];
-        const long long iw = len >= 2 ? j + nstep : j;
-        wdst = wbase[(size_t)(iw * P.w_mul)];
+        for (int c = 0; c < RMAX; ++c) dst[c] = src[c][pf_off];
+        wdst = wbase[pf_w];
+        const bool more = pf_n < lastsrc;
+        pf_off += more ? stepL : 0;
+        pf_w += more ? stepW : 0;
+        ++pf_n;
     };
 #pragma unroll
-    for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u], u);
+    for (int u = 0; u < D; ++u) prefetch(cur[u], wcur[u]);
+    long long so = out0 + stepL, sq = outq0 + nstep;        // entries of node 1, the first one updated
 
     float carry = 0.0f;
     int freed = 0;          // every step <= freed has been read by the index wavefront (possibly stale view)
     for (int n0 = 1; n0 < maxlen; n0 += D) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u], n0 - 1 + D + u);
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], wnxt[u]);
 #pragma unroll
-        for (int u = 0; u < D; ++u) {
+        for (int u = 0; u < D; ++u, so += stepL, sq += nstep) {
             const int nn = n0 + u;
             const bool act = act_seg && nn < len;       // this segment still has a node to update
-            const long long i = head + (long long)nn * nstep;
             const float wgt = wcur[u];
 
             float v = cur[u][0];
@@ -2637,9 +2649,9 @@ mrf_fwd_sweep_packed(const MrfFwdParams P)
             const int qidx = mrf_segment_first<SEG>(__ballot(tv == tq), lane);
 
             if (act && valid) {
-                P.m_out[((size_t)r * N + i) * L + lam] = carry;
-                P.p[((size_t)r * N + i) * L + lam] = (uint8_t)bidx;
-                if (lam == 0) P.q[(size_t)r * N + i] = (uint8_t)qidx;
+                P.m_out[so] = carry;
+                P.p[so] = (uint8_t)bidx;
+                if (lam == 0) P.q[sq] = (uint8_t)qidx;
             }
         }
 #pragma unroll
