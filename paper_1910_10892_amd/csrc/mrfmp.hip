@@ -409,11 +409,12 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
 {
     // few labels: several scanlines per wavefront (dense evaluation), unless the launch is so
     // small that it is latency bound and a truncated model can use the shorter window step
+    // (up to 16 labels the window templates evaluate 15 candidates, no fewer than the dense step)
     if (P.Te) return launch_edge(P, algo, blocks, st);
     // (TRW coefficients per edge: the two one-wavefront-per-scanline sweeps read them)
     const bool generic = P.rho_e != nullptr;
     if (P.sgm_std) tw = 0;         // standard SGM: the dense sweep is the one that knows it
-    if (!P.sgm_std && !generic && P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024)) {
+    if (!P.sgm_std && !generic && P.g.L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || tw == 0 || blocks >= 1024 || P.g.L <= 16)) {
         int ms = 0;
         for (int r = P.r_first; r < P.r_first + P.r_count; ++r)
             if (P.n_src[r] > ms) ms = P.n_src[r];
