@@ -386,6 +386,13 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9      # bytes read + written
         del a, b
 
     if args.config:
@@ -418,6 +425,8 @@ def main():
         "library_version": mrf.mrf_version(),
         "configs": configs,
     }
+    if args.copy_probe:
+        out["copy_probe"] = {"what": "1 GiB device-to-device copy, bytes read + written per second", "value": copy_gbs, "unit": "GB/s"}
     if args.heads:
         out["heads"] = heads(head_run[0], head_run[1])
     if args.energy_protocol:
