@@ -124,11 +124,10 @@ int mrf_validate(const mrf_problem *prob, int algo);
 
 /* Which forward kernel the sweeps of the second and later iterations get: 0 = the dense O(L^2)
  * sweep, w > 0 = the window sweep that evaluates 2w - 1 source labels per label (truncated models
- * whose truncation distance is at most 16 and below L, and whose update reads at most seven message
- * arrays: up to 9 directions in opposite pairs for ISGMR, 8 for TRWP).  The choice is made per
- * launch: where this returns 0 for a truncated model, the early TRWP launches of the first
- * iteration, which read fewer arrays, may still take the window sweep.  Results are identical
- * either way.  Negative mrf_status for an invalid problem.  Host arithmetic. */
+ * whose truncation distance is at most 16 and below L; any direction set: with the default kernel-choice
+ * rules an ISGMR sweep reads a single array from six directions on and at most seven message arrays
+ * below that, a TRWP sweep up to fifteen).  Results are identical either way.  Negative mrf_status for
+ * an invalid problem.  Host arithmetic. */
 int mrf_forward_window(const mrf_problem *prob, int algo);
 
 /* Forward propagation of ISGMR (Alg. 1; update Eq. isgmr, reparametrisation

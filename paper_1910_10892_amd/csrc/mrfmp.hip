@@ -297,6 +297,23 @@ hipError_t launch_window_one(const MrfFwdParams &P, int tw, long long blocks, hi
     return hipErrorInvalidValue;
 }
 
+// TRWP with nine to sixteen directions: up to fifteen message arrays per update
+template <int LP>
+hipError_t launch_window_many(const MrfFwdParams &P, int tw, long long blocks, hipStream_t st)
+{
+    // (prefetch two nodes deep where the registers allow: a node step otherwise waits a whole memory round trip)
+    constexpr int D = LP <= 2 ? 2 : 1;
+    note_launch(0, "mrf_fwd_sweep_window", blocks, 64, "%d,16,%d,true,%d", LP, D, tw);
+#define MRF_W(twv) \
+    if (tw == twv) { \
+        hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, 16, D, true, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_W(2) MRF_W(8) MRF_W(16)
+#undef MRF_W
+    return hipErrorInvalidValue;
+}
+
 template <int LP, int RMAX, int D, int NI>
 hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long blocks, hipStream_t st)
 {
@@ -490,6 +507,13 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
             if (LPw == lp) return launch_window<lp, 8, (lp <= 2 ? 2 : 1)>(P, algo, tw, blocks, st);
             MRF_WCASE(1) MRF_WCASE(2) MRF_WCASE(3) MRF_WCASE(4)
 #undef MRF_WCASE
+        }
+        if (algo == MRF_TRWP && ms + 1 <= 16) {
+            P.NW = 1;
+            if (LPw == 1) return launch_window_many<1>(P, tw, blocks, st);
+            if (LPw == 2) return launch_window_many<2>(P, tw, blocks, st);
+            if (LPw == 3) return launch_window_many<3>(P, tw, blocks, st);
+            if (LPw == 4) return launch_window_many<4>(P, tw, blocks, st);
         }
     }
     const int L = P.g.L;
@@ -1156,17 +1180,20 @@ int mrf_forward_window(const mrf_problem *prob, int algo)
 {
     const int rc = check_problem(prob, algo, false);
     if (rc != MRF_OK) return rc;
-    // the window sweeps take up to seven message arrays next to the unary (as dispatch_fwd decides per
-    // launch); count what a launch of the later iterations reads
-    int most = 0;
-    for (int r = 0; r < prob->R; ++r) {
-        bool has_opp = false;
-        for (int d = 0; d < prob->R; ++d)
-            if (prob->dirs[2 * d] == -prob->dirs[2 * r] && prob->dirs[2 * d + 1] == -prob->dirs[2 * r + 1]) has_opp = true;
-        const int n = prob->R - 1 - ((algo == MRF_ISGMR && has_opp) ? 1 : 0);
-        if (n > most) most = n;
+    // The window sweeps take up to fifteen message arrays next to the unary for TRWP (any direction set the
+    // library accepts) and up to seven for ISGMR, whose sweeps read a single array from six directions on
+    // (run_forward); count what an ISGMR launch of the later iterations reads with fewer directions.
+    if (algo == MRF_ISGMR && !(prob->R >= 6 && prob->K > 1)) {
+        int most = 0;
+        for (int r = 0; r < prob->R; ++r) {
+            bool has_opp = false;
+            for (int d = 0; d < prob->R; ++d)
+                if (prob->dirs[2 * d] == -prob->dirs[2 * r] && prob->dirs[2 * d + 1] == -prob->dirs[2 * r + 1]) has_opp = true;
+            const int n = prob->R - 1 - (has_opp ? 1 : 0);
+            if (n > most) most = n;
+        }
+        if (most + 1 > 8) return 0;
     }
-    if (most + 1 > 8) return 0;
     return window_width(prob);
 }
 

@@ -97,13 +97,14 @@ def test_forward_kernel_choice_is_host_arithmetic():
     assert W(L=64, pairwise_kind=3, trunc=5.0) == 8
     assert W(L=64, pairwise_kind=4, trunc=2.0) == -7          # unknown kind
     assert W(L=0, pairwise_kind=1, trunc=4.0) == -3
-    # the window sweeps take at most seven message arrays per update
+    # any direction set: TRWP sweeps take up to fifteen message arrays, ISGMR sweeps read one array from six
+    # directions on
     d8 = [(0, 1), (0, -1), (1, 0), (-1, 0), (1, 1), (-1, -1), (1, -1), (-1, 1)]
-    d10 = d8 + [(1, 2), (-1, -2)]
+    d16 = d8 + [(1, 2), (-1, -2), (2, 1), (-2, -1), (1, -2), (-1, 2), (2, -1), (-2, 1)]
     T = lambda dirs, algo: lib.mrf_forward_window(ctypes.byref(_cprob(dirs=dirs, L=96, pairwise_kind=1, trunc=8.0)), algo)
     assert T(d8, 0) == 8 and T(d8, 1) == 8
-    assert T(d8 + [(1, 2)], 0) == 0          # ISGMR: the direction without an opposite reads 8 arrays
-    assert T(d10, 0) == 0 and T(d10, 1) == 0
+    assert T(d8 + [(1, 2)], 0) == 8 and T(d8 + [(1, 2)], 1) == 8
+    assert T(d16, 0) == 8 and T(d16, 1) == 8
 
 
 def test_entry_points_reject_before_any_gpu_work():
