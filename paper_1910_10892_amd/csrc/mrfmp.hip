@@ -473,7 +473,12 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
             const long long st = ((long long)mrf_iabs(P.g.dh[r]) * P.g.W + mrf_iabs(P.g.dw[r])) * P.g.L;
             if (st > 0x7fffffffLL) step_fits = false;
         }
-        const bool duo = !generic && step_fits && g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= 4096);
+        // (a second wavefront per scanline pays while the scanlines alone leave SIMD slots free; measured on
+        // square grids with four directions: ISGMR at 2,048 scanlines 1.41 ms with it against 1.52 ms without,
+        // at 2,560 scanlines 2.74 against 2.21 ms with 96 labels but 1.27 against 1.37 ms with 40; TRWP at 2,048
+        // scanlines 4.92 against 4.32 ms)
+        const long long duo_max = algo == MRF_TRWP ? 1536 : (LPw == 1 ? 3072 : 2048);
+        const bool duo = !generic && step_fits && g_tune_duo != 1 && (g_tune_duo == 2 || blocks <= duo_max);
         if (ms + 1 <= 8 && duo) {
             P.NW = 1;
             // two index wavefronts while the launch is far from filling the machine
@@ -875,7 +880,10 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     const bool chain_fits = !generic && step_fits && ns <= 8 && g_tune_chain != 1 &&
                             (!gv || (LP == 1 && P.total_scanlines * ni <= grad_slots(L))) &&
                             mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
-    const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= (LP <= 2 ? 2048 : 512));
+    // (65..128 labels with several source arrays, TRWP: at 2,048 scanlines per launch the plain sweep is ahead,
+    // 5.1 against 7.5 ms on 4 x 512 x 512 with 96 labels; at 1,024 the chain, 2.3 against 3.6 ms)
+    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : 2048) : 512;
+    const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= chain_max);
     // few labels: several scanlines per wavefront, once there are enough of them
     if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
         !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= 1024)))
