@@ -356,6 +356,10 @@ def main():
     ap.add_argument("--speed-table", action="store_true",
                     help="also time the shape of the paper's speed table: 256 x 512, 32 / 96 labels, 4 / 8 / 16 "
                          "directions, dense pairwise table, both algorithms (extra \"speed_table\" array)")
+    ap.add_argument("--shape", default=None, metavar="ALGO:BxHxW:L:R:K[:TRUNC]",
+                    help="time a shape of your own instead of a benchmark configuration: isgmr|trwp, grid, labels, 4|8|16 "
+                         "directions, iterations, truncated-linear pairwise with that truncation (0 or absent: a general "
+                         "dense table with all gradients); seeded random unaries and per-edge weights")
     ap.add_argument("--graph", action="store_true",
                     help="also capture each step (forward + backward) into a HIP graph and time its replay "
                          "(\"ms_per_step_graph_replay\" of every entry of \"configs\")")
@@ -395,6 +399,17 @@ def main():
         copy_gbs = 10 * 2 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9      # bytes read + written
         del a, b
 
+    shape_problem = None
+    if args.shape:
+        from mrf_inputs import DIRS4, DIRS8, DIRS16, random_problem, truncated_linear
+        f = args.shape.split(":")
+        algo_s, (B_s, H_s, W_s), L_s, R_s, K_s = f[0], [int(v) for v in f[1].split("x")], int(f[2]), int(f[3]), int(f[4])
+        trunc_s = float(f[5]) if len(f) > 5 else 0.0
+        shape_problem = random_problem(19101089, algo_s, B_s, H_s, W_s, L_s, {4: DIRS4, 8: DIRS8, 16: DIRS16}[R_s], K_s)
+        if trunc_s > 0:
+            shape_problem.pairwise = truncated_linear(L_s, trunc_s, 1.0)
+            shape_problem.pairwise_kind, shape_problem.trunc, shape_problem.scale = 1, trunc_s, 1.0
+        shape_problem.name = "shape_" + args.shape.replace(":", "_")
     if args.config:
         from mrf_inputs import make_config
         algo = args.algo or make_config(args.config, crop=(4, 4)).algo
@@ -403,7 +418,11 @@ def main():
     else:
         head_run = HEADLINE
         others = [r for r in ALL_RUNS if r != HEADLINE]
-    head = measure(*head_run, args.steps, args.warmup, traffic)
+    if shape_problem is not None:
+        head = measure_problem(shape_problem, False, args.steps, args.warmup, traffic)
+        others = []
+    else:
+        head = measure(*head_run, args.steps, args.warmup, traffic)
     configs = [head]
     for run in others:
         configs.append(measure(*run, max(2, min(args.steps, 5)), 1, traffic))
@@ -433,7 +452,7 @@ def main():
         out["energy_protocol"] = energy_protocol()
     if args.speed_table:
         out["speed_table"] = speed_table(max(2, min(args.steps, 3)))
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and shape_problem is None:
         crops = {1: (32, 48), 2: (128, 256), 3: (56, 144), 4: (24, 32), 5: (256, 256)}
         out["cpu_baseline"] = cpu_baseline(head_run[0], head_run[1], crops[head_run[0]])
     print(json.dumps(out))
