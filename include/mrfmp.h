@@ -295,7 +295,7 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           0 = for small problems (launch bound), 1 = never, 2 = always
  *   knob 16: dense forward sweep in which every wavefront owns 32 labels (loads, merge, normalisation and
  *           stores divided among the wavefronts) instead of doing that work for all labels (the layout knob 0
- *           tunes): 0 = for more than 128 labels, and for 65..128 labels where a sweep reads more than three message
+ *           tunes): 0 = for more than 96 labels, and for 65..96 labels where a sweep reads more than three message
  *           arrays or the launch has at least 4096 scanlines, 1 = never, 2 = for more than 64 labels
  *   knob 17: ISGMR forward in which one streaming pass per iteration sums the unary and the previous
  *           iteration's messages once per pair of opposite directions, so that every sweep reads one array

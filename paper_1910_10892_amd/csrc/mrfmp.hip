@@ -226,11 +226,14 @@ hipError_t launch_fwd_sliced(const MrfFwdParams &P, int algo, long long blocks, 
 
 // source labels per wavefront: small enough that the slice of V fits in registers, large
 // enough that at most 16 wavefronts share a node
-int pick_mch(int L, int LP, bool many_sources)
+// (33..64 labels: four wavefronts of 16 source labels while the launch leaves SIMD slots free, two of 32 from
+// 2,048 scanlines on: 512 x 512, 64 labels, ISGMR 2.64 -> 2.02 ms; TRWP on 4 x 512 x 512 11.4 -> 8.2 ms, but on
+// 1 x 512 x 512 4.5 against 5.2 ms)
+int pick_mch(int L, int LP, bool many_sources, long long blocks)
 {
     static const int allowed[4][5] = { {8, 16, 32, 0, 0}, {8, 12, 16, 24, 32}, {16, 24, 32, 48, 0}, {32, 0, 0, 0, 0} };
     int want = g_tune_mch;
-    if (want <= 0) want = LP == 1 ? (L <= 32 ? 32 : 16) : (LP == 2 ? 24 : 32);
+    if (want <= 0) want = LP == 1 ? ((L <= 32 || blocks >= 2048) ? 32 : 16) : (LP == 2 ? 24 : 32);
     if (many_sources) want = (LP <= 2) ? (want < 16 ? 16 : (want == 24 || want == 12 ? 16 : want)) : 32;
     int best = 0;
     for (int i = 0; i < 5; ++i) {
@@ -533,7 +536,10 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
     // fills the machine several times over; else three wavefronts of 32 source labels are no faster than four
     // of 24: measured at 96 labels, 256 x 512, per iteration: TRWP with 8 directions 5.70 -> 4.01 ms, with 16
     // 15.1 -> 8.8 ms, ISGMR with 16 directions 4.12 -> 3.74 ms, but TRWP with 4 directions 1.81 -> 1.96 ms)
-    if ((LP >= 3 || (LP == 2 && (g_tune_dense_sliced == 2 || rmax >= 8 || blocks >= 4096))) && !generic && !P.sgm_std && g_tune_mch == 0 && g_tune_dense_sliced != 1) {
+    // (from 97 labels on the other sweep needs five or six wavefronts of 24 source labels: 256 x 256, 128 labels,
+    // ISGMR 3.80 -> 2.03 ms, TRWP 4.1 -> 3.8 ms; at 72 and 80 labels the two are level for ISGMR and this one is
+    // behind for TRWP)
+    if ((LP >= 3 || (LP == 2 && (g_tune_dense_sliced == 2 || rmax >= 8 || blocks >= 4096 || L > 96))) && !generic && !P.sgm_std && g_tune_mch == 0 && g_tune_dense_sliced != 1) {
         P.NW = (L + 31) / 32;
 #define MRF_SCASE(lp) \
         if (LP == lp && rmax == 4) return launch_fwd_sliced<lp, 4, 4>(P, algo, blocks, st); \
@@ -542,7 +548,7 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         MRF_SCASE(2) MRF_SCASE(3) MRF_SCASE(4)
 #undef MRF_SCASE
     }
-    const int mch = pick_mch(L, LP, rmax > 4);
+    const int mch = pick_mch(L, LP, rmax > 4, blocks);
     P.NW = (L + mch - 1) / mch;
     // prefetch depth: as deep as the register file allows next to the slice of V
 #define MRF_CASE(lp, m) \
