@@ -454,8 +454,11 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         // few scanlines in the launch and many labels: spread each node step over one
         // wavefront per 64 labels
         // (wide windows over many labels only: otherwise the value/index pair below is faster)
+        // (measured with four directions: window 16, 192 or 256 labels, ISGMR with 1,536 to 3,072 scanlines: 2.2
+        // against 3.8 ms, 2.6 against 5.4 ms, 5.0 against 7.2 ms, 7.3 against 8.2 ms for the next best layout; window
+        // 8, 192 or 256 labels: the value/index pair is ahead, TRWP 2.3 against 3.9 ms, ISGMR 1.3 against 1.6 ms)
         const bool split = !generic && LPw > 1 && g_tune_split != 1 &&
-                           (g_tune_split == 2 || (LPw >= 3 && tw >= 8 && blocks * LPw <= 4096));
+                           (g_tune_split == 2 || (LPw >= 3 && tw >= 16 && blocks * LPw <= 16384));
         if (ms + 1 <= 8 && split && g_tune_squad != 1 && (g_tune_squad == 2 || blocks <= 512)) {
             // the value wavefronts of the split layout, with the index work on wavefronts of their own
             P.NW = LPw;
@@ -888,11 +891,13 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
                             mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
     // (65..128 labels with several source arrays, TRWP: at 2,048 scanlines per launch the plain sweep is ahead,
     // 5.1 against 7.5 ms on 4 x 512 x 512 with 96 labels; at 1,024 the chain, 2.3 against 3.6 ms)
-    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : 2048) : 512;
+    // (more than 128 labels, one source array, ISGMR: at 1,536 scanlines the chain is ahead, 1.7 against 2.4 ms
+    // with 192 labels, at 2,048 the plain sweep, 3.1 against 3.6 ms; several source arrays: level at 1,024)
+    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : 2048) : (ns == 1 ? 1536 : 512);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= chain_max);
     // few labels: several scanlines per wavefront, once there are enough of them
     if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
-        !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= 1024)))
+        !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= ((ns == 1 && !gv) ? 1536 : 1024))))
     {
         // three scanlines per wavefront: measured slower than two on the segmentation shape (the LDS
         // scatter, not instruction issue, bounds this sweep), so only on request
@@ -915,7 +920,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     }
     // few scanlines and many labels: one wavefront per 64 labels
     const bool split = !generic && LP >= 3 && g_tune_split != 1 && ns <= 8 &&
-                       (g_tune_split == 2 || (P.total_scanlines < 1024 && P.total_scanlines * LP <= 4096));
+                       (g_tune_split == 2 || ((P.total_scanlines < 1024 || (P.total_scanlines == 1024 && LP == 3)) && P.total_scanlines * LP <= 4096));
     if (split) {
         long long sblocks = P.total_scanlines;
         if (P.gV && sblocks > grad_slots(L)) sblocks = grad_slots(L);
