@@ -893,7 +893,9 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     // 5.1 against 7.5 ms on 4 x 512 x 512 with 96 labels; at 1,024 the chain, 2.3 against 3.6 ms)
     // (more than 128 labels, one source array, ISGMR: at 1,536 scanlines the chain is ahead, 1.7 against 2.4 ms
     // with 192 labels, at 2,048 the plain sweep, 3.1 against 3.6 ms; several source arrays: level at 1,024)
-    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : 2048) : (ns == 1 ? 1536 : 512);
+    // (a launch of eight or more directions has many short diagonal scanlines: the chain stays ahead longer,
+    // 0.80 against 1.04 ms at 2,876 scanlines of a 160 x 320 grid, 0.81 against 0.89 ms at 3,452 of 192 x 384)
+    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : (P.r_count >= 8 ? 3584 : 2048)) : (ns == 1 ? 1536 : 512);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= chain_max);
     // few labels: several scanlines per wavefront, once there are enough of them
     if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
