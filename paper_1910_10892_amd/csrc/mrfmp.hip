@@ -895,7 +895,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     // with 192 labels, at 2,048 the plain sweep, 3.1 against 3.6 ms; several source arrays: level at 1,024)
     // (a launch of eight or more directions has many short diagonal scanlines: the chain stays ahead longer,
     // 0.80 against 1.04 ms at 2,876 scanlines of a 160 x 320 grid, 0.81 against 0.89 ms at 3,452 of 192 x 384)
-    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : (P.r_count >= 8 ? 3584 : 2048)) : (ns == 1 ? 1536 : 512);
+    const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : (P.r_count >= 8 ? 3584 : 2560)) : (ns == 1 ? 1536 : 512);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= chain_max);
     // few labels: several scanlines per wavefront, once there are enough of them
     if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
