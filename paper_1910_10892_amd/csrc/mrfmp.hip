@@ -1070,7 +1070,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         // Pays only where the pass is bound by its launches (the combine passes are a third of them): on the
         // stereo and segmentation shapes the sweeps, which are bound by instruction issue and latency, lose
         // more on the extra arrays (2.29 against 1.80 ms, 4.05 against 3.76 ms) than the combine passes cost.
-        const bool lazy = R <= 4 && g_tune_isgmr_lazy != 1 && (g_tune_isgmr_lazy == 2 || NL <= (1LL << 20));
+        const bool lazy = R <= 4 && g_tune_isgmr_lazy != 1 && (g_tune_isgmr_lazy == 2 || NL <= (1LL << 19));
         for (int k = K - 1; lazy && k >= 0; --k) {
             float *s_cur = ((K - 1 - k) & 1) ? buf0 : buf1, *s_prev = ((K - 1 - k) & 1) ? buf1 : buf0;
             P.S = s_cur;
