@@ -1122,6 +1122,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
             else if (R <= 4) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<4, 1>), cg, cb, 0, st, C);
             else if (R <= 8 && cvec) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<8, 4>), cg, cb, 0, st, C);
             else if (R <= 8) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<8, 1>), cg, cb, 0, st, C);
+            else if (cvec) hipLaunchKernelGGL((mrf_isgmr_bwd_combine<16, 4>), cg, cb, 0, st, C);
             else hipLaunchKernelGGL((mrf_isgmr_bwd_combine<16, 1>), cg, cb, 0, st, C);
             { const hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return hip_fail(e_, "hipGetLastError"); }
         }
