@@ -103,6 +103,13 @@ inline size_t gradv_bytes(const mrf_problem *pr)
     return align_up((size_t)grad_slots(pr->L) * pr->L * pr->L * sizeof(double));
 }
 
+// room for the node gradients that mrf_bwd_gv_from_g reads (65..128 labels)
+inline size_t gstore_bytes(const mrf_problem *pr)
+{
+    if (pr->L <= 64 || pr->L > 128) return 0;
+    return align_up((size_t)pr->B * pr->H * pr->W * pr->L * sizeof(double));
+}
+
 // ---- process-global state: defined in the translation unit of the entry points ----------
 // tuning knobs (0 = heuristic)
 #if MRF_HAS_API
@@ -122,6 +129,7 @@ MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
 MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_isgmr_lazy, 0); // ISGMR backward without a combine pass per iteration (up to 4 directions): 0 auto, 1 never
 MRF_G(int g_tune_isgmr_presum, 0); // ISGMR forward with the per-pair sums of the previous iteration formed once: 0 from six directions, 1 never, 2 always
+MRF_G(int g_tune_gv_apart, 0);     // V gradient of 65..128 labels by a streaming pass behind the chain backward sweep: 0 yes, 1 no
 MRF_G(int g_tune_gv_tile, 0);      // V gradient of 33..128 labels in one LDS table per workgroup: 0 yes, 1 no (a slot per wavefront in global memory)
 MRF_G(int g_tune_dense_sliced, 0); // dense sweep for more than 64 labels with a slice of the labels per wavefront: 0 yes, 1 no
 MRF_G(int g_tune_spin_limit, 0); // turns a wait between wavefronts may take: 0 = default
@@ -872,7 +880,11 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         const long long stp = ((long long)mrf_iabs(P.g.dh[r]) * P.g.W + mrf_iabs(P.g.dw[r])) * L;
         if (stp > 0x7fffffffLL) step_fits = false;
     }
-    const bool gv = P.gV != nullptr;
+    const bool gv_any = P.gV != nullptr;
+    // 65..128 labels, one direction per launch: the chain layout has no room for the V-gradient table, so its
+    // helpers store the node gradients and a streaming pass adds them up afterwards (mrf_bwd_gv_from_g)
+    const bool gv_apart = gv_any && LP == 2 && P.gstore_buf && P.r_count == 1 && !P.rho_e && !P.force_plain && g_tune_gv_apart != 1;
+    const bool gv = gv_any && !gv_apart;      // the V gradient inside the sweep that runs
     // as many helpers as keep up with the chain while the machine and the LDS have room
     // (measured per launch shape at L = 96: 256 scanlines 165 / 121 / 98 / 90 us with 4 / 6 / 8 / 12
     // helpers; 512 scanlines, two workgroups per compute unit, 94 / 78 / 98 us with 4 / 6 / 8)
@@ -913,6 +925,29 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         // where LDS throughput, not the latency of the chain, bounds the launch
         P.hot_label = (pairwise_kind != MRF_PAIRWISE_DENSE && !gv && g_tune_chain_hot != 1 &&
                        (g_tune_chain_hot == 2 || L > 128 || P.total_scanlines > 1024)) ? 1 : 0;
+        if (gv_apart) {
+            double *const slots = P.gV;
+            P.gV = nullptr; P.gstore = P.gstore_buf;
+            hipError_t e = hipErrorInvalidValue;
+            if (ns == 1) e = launch_bwd_chain<2, 1, 2>(P, ni, vg, st);
+            else if (ns == 4) e = launch_bwd_chain<2, 4, 2>(P, ni, vg, st);
+            else if (ns == 8) e = launch_bwd_chain<2, 8, 1>(P, ni, vg, st);
+            P.gV = slots; P.gstore = nullptr;
+            if (e != hipSuccess) return e;
+            MrfGvParams G;
+            G.N = P.g.N; G.L = L; G.g = P.gstore_buf;
+            G.p = P.p + (size_t)P.r_first * P.g.N * L;
+            G.w = P.w + (P.w_mul ? (size_t)P.r_first * P.g.N : 0); G.w_mul = P.w_mul;
+            G.gV = slots;
+            const size_t glds = sizeof(double) * (size_t)L * L;
+            if (glds > 64 * 1024) {
+                const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(&mrf_bwd_gv_from_g),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)glds);
+                if (ea != hipSuccess) return ea;
+            }
+            hipLaunchKernelGGL(mrf_bwd_gv_from_g, dim3(256), dim3(512), glds, st, G);
+            return hipGetLastError();
+        }
 #define MRF_CCASE(lp) \
         if (LP == lp && ns == 1) return launch_bwd_chain<lp, 1, 2>(P, ni, vg, st); \
         if (LP == lp && ns == 4) return launch_bwd_chain<lp, 4, (lp <= 2 ? 2 : 1)>(P, ni, vg, st); \
@@ -1008,7 +1043,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
 
-    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots]
+    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots][node gradients for mrf_bwd_gv_from_g (65..128 labels)]
     char *ws = (char *)workspace;
     float *scal = (float *)ws;
     float *buf0 = (float *)(ws + kAlign);                   // ISGMR: grad m-hat   TRWP: s per direction
@@ -1030,6 +1065,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
         { const hipError_t e_ = fill(grad_V, (long long)R * N * L * L, 0.0f, st); if (e_ != hipSuccess) return hip_fail(e_, "fill"); }
     } else if (grad_V) {
         P.gV = gvslots;
+        if (gstore_bytes(pr) > 0) P.gstore_buf = (double *)((char *)gvslots + gradv_bytes(pr));
         { const hipError_t e_ = fill64(gvslots, grad_slots(L) * L * L, st); if (e_ != hipSuccess) return hip_fail(e_, "fill64"); }
     }
 
@@ -1193,7 +1229,7 @@ size_t mrf_workspace_bytes(const mrf_problem *prob, int algo, int backward)
 {
     if (check_problem(prob, algo, false) != MRF_OK) return 0;
     if (!backward) return kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob);
-    return kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob) + gradv_bytes(prob);
+    return kAlign + (algo == MRF_ISGMR ? 2 : 1) * msg_bytes(prob) + gradv_bytes(prob) + gstore_bytes(prob);
 }
 
 int mrf_validate(const mrf_problem *prob, int algo) { return check_problem(prob, algo, true); }
@@ -1463,6 +1499,7 @@ int mrf_tune(int knob, int value)
     if (knob == 16) { g_tune_dense_sliced = value; return MRF_OK; }
     if (knob == 17) { g_tune_isgmr_presum = value; return MRF_OK; }
     if (knob == 18) { g_tune_gv_tile = value; return MRF_OK; }
+    if (knob == 19) { g_tune_gv_apart = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

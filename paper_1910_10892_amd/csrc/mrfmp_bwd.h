@@ -75,6 +75,9 @@ struct MrfBwdParams {
     float *gE;                             // [R][N][L][L] gradient of per-edge pairwise tables (zeroed by the host,
                                            // accumulated over iterations), or NULL; mrf_bwd_sweep<..., RHOE> only
     int force_plain;                       // the problem has no V: only mrf_bwd_sweep may run
+    double *gstore_buf;                    // [N][L] room for gstore (workspace), or NULL
+    double *gstore;                        // mrf_bwd_sweep_chain: if not NULL, its helpers store the gradient vector g of
+                                           // every node here (0 where no update is replayed) for mrf_bwd_gv_from_g
     int *fault;                            // launch-wide word raised when a wait between wavefronts is given up (mrf_wait_turn)
     int spin_limit;                        // microseconds after which a wait is given up
 };
@@ -703,6 +706,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     float *guw = P.gunary + (size_t)head * L;                       // stores of stage "post"
     float *sw = P.S + ((size_t)r * N + head) * L;
     float *gww = P.gw ? P.gw + (size_t)r * N + head : nullptr;
+    double *gsw = P.gstore ? P.gstore + (size_t)head * L : nullptr;
 
     int chain_seen = -1;
     for (int it0 = 0; it0 < T + 1 && T > 0; it0 += D) {
@@ -790,9 +794,10 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     if (own_unary && lam < L)
                         guw[oi + lam] = (float)(cin + (double)a_extT[slot * LL + lam]);
                     if (update && lam < L) sw[oj + lam] = (float)b_sv[slot * LL + lam];
-                    if ((P.gw || GV) && lam < L) {
+                    if ((P.gw || GV || gsw) && lam < L) {
                         const double g = cin + a_ext[slot * LL + lam];    // as the chain formed it
                         const int pv = a_p[slot * LL + lam];
+                        if (gsw) gsw[oi + lam] = update ? g : 0.0;
                         if (P.gw) {
                             float vv;
                             if (GV) {
@@ -838,6 +843,52 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
         double *gVs = P.gV + ((size_t)blockIdx.x * NI + jw) * L * L;
         for (int e = lane; e < L * L; e += 64) gVs[e] += gvl[e];
     }
+}
+
+// ---- grad V apart from the sweep (65..128 labels beside mrf_bwd_sweep_chain) --------------------
+// Eq. supp-gradient-smoothness: entry (p(lambda), lambda) of the table receives theta_{i-r,i} g(lambda) at
+// every replayed update.  Nothing of it depends on the order of the nodes, so where the chain layout has no
+// room for the table its helpers store g per node and this streaming pass does the additions: one wavefront
+// per node, lanes over lambda, the L x L table of a workgroup in LDS (`ds_add_f64`), added to the workgroup's
+// slot at the end.
+struct MrfGvParams {
+    long long N;
+    int L;
+    const double *g;         // [N][L]
+    const uint8_t *p;        // [N][L] of this direction and iteration
+    const float *w;          // [N] edge weights of this direction, or the scalar at w[0] when w_mul == 0
+    int w_mul;
+    double *gV;              // [gridDim.x][L][L] slots
+};
+
+__global__ void __launch_bounds__(512) mrf_bwd_gv_from_g(const MrfGvParams P)
+{
+    extern __shared__ __align__(16) unsigned char mrf_gvsmem[];
+    double *tile = reinterpret_cast<double *>(mrf_gvsmem);
+    const int L = P.L;
+    for (int e = threadIdx.x; e < L * L; e += blockDim.x) tile[e] = 0.0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long nwaves = (long long)gridDim.x * (blockDim.x >> 6);
+    for (long long i = wave; i < P.N; i += nwaves) {
+        const double wgt = (double)P.w[(size_t)(i * P.w_mul)];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int lam = lane + 64 * s;
+            if (lam < L) {
+                const double g = P.g[(size_t)i * L + lam];
+                if (g != 0.0) {
+                    int pv = P.p[(size_t)i * L + lam];
+                    pv = pv < L ? pv : L - 1;
+                    __hip_atomic_fetch_add(&tile[__mul24(pv, L) + lam], wgt * g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    double *slot = P.gV + (size_t)blockIdx.x * L * L;
+    for (int e = threadIdx.x; e < L * L; e += blockDim.x) slot[e] += tile[e];
 }
 
 // ---- index replay, one label per lane, ceil(L/64) wavefronts per scanline --------------------

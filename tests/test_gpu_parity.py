@@ -203,6 +203,36 @@ def test_isgmr_sums_of_the_previous_iteration_formed_once(oracle, case):
         np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
 
 
+GV_APART_CASES = [
+    # seed, B, H, W, L, dirs, K, integer_valued, per_edge
+    (751, 1, 6, 9, 96, DIRS4, 3, False, True), (752, 2, 5, 7, 128, DIRS8, 2, True, True),
+    (753, 1, 7, 5, 65, ((0, 1), (1, 0), (1, 1)), 2, False, False), (754, 1, 4, 33, 100, DIRS4, 2, False, True),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", GV_APART_CASES, ids=lambda c: "seed%d" % c[0])
+def test_pairwise_gradient_added_up_behind_the_chain_sweep(oracle, case):
+    """TRWP with 65..128 labels and grad_pairwise: the chain sweep stores the node gradients and a streaming
+    pass forms the table (Eq. supp-gradient-smoothness); against the oracle, and against the sweep that
+    accumulates the table itself."""
+    import paper_1910_10892_amd as mrf
+    print("case grad V apart", case[:5], len(case[5]), case[6:], flush=True)
+    seed, B, H, W, L, dirs, K, iv, per_edge = case
+    pr = random_problem(seed, "trwp", B, H, W, L, dirs, K, integer_valued=iv, per_edge=per_edge, symmetric=False,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    pr.grad_cost = (pr.grad_cost * 0.2).astype(np.float32)
+    try:
+        a = full_check(oracle, pr, want_V=True)
+        assert mrf.mrf_last_sweep_kernel(True) == "mrf_bwd_sweep_chain", mrf.mrf_last_sweep_launch(True)
+        assert mrf.mrf_tune(19, 1) == 0
+        b = full_check(oracle, pr, want_V=True)
+        assert mrf.mrf_last_sweep_kernel(True) != "mrf_bwd_sweep_chain"
+    finally:
+        mrf.mrf_tune(19, 0)
+    check_grad("grad_pairwise (two layouts)", a.grad_pairwise, None, b.grad_pairwise.astype(np.float64))
+
+
 def truncated_problem(seed, algo, H, W, L, dirs, K, kind, trunc, integer_valued, weights):
     """Truncated linear (kind 1) / quadratic (kind 2) pairwise with the kind announced, so the
     library may take its window path.  weights: 'pos' | 'zero_mix' | 'neg_mix'."""
@@ -845,7 +875,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2)), 19: int(rng.integers(0, 2))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
@@ -1008,7 +1038,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2)), 19: int(rng.integers(0, 2))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
     f = oracle_forward(oracle, pr, threads=True)
     b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
