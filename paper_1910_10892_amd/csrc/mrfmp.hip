@@ -103,10 +103,10 @@ inline size_t gradv_bytes(const mrf_problem *pr)
     return align_up((size_t)grad_slots(pr->L) * pr->L * pr->L * sizeof(double));
 }
 
-// room for the node gradients that mrf_bwd_gv_from_g reads (65..128 labels)
+// room for the node gradients that mrf_bwd_gv_from_g reads (33..128 labels)
 inline size_t gstore_bytes(const mrf_problem *pr)
 {
-    if (pr->L <= 64 || pr->L > 128) return 0;
+    if (pr->L <= 32 || pr->L > 128) return 0;
     return align_up((size_t)pr->B * pr->H * pr->W * pr->L * sizeof(double));
 }
 
@@ -881,9 +881,12 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         if (stp > 0x7fffffffLL) step_fits = false;
     }
     const bool gv_any = P.gV != nullptr;
-    // 65..128 labels, one direction per launch: the chain layout has no room for the V-gradient table, so its
+    // 33..128 labels, one direction per launch: the chain layout has little or no room for V-gradient tables, so its
     // helpers store the node gradients and a streaming pass adds them up afterwards (mrf_bwd_gv_from_g)
-    const bool gv_apart = gv_any && LP == 2 && P.gstore_buf && P.r_count == 1 && !P.rho_e && !P.force_plain && g_tune_gv_apart != 1;
+    // (up to 512 scanlines per launch: beyond that the helpers' gathers from V in global memory hold the chain
+    // layout back, 7.8 against 4.5 ms at 1,024 scanlines of 2 x 512 x 512 with 96 labels)
+    const bool gv_apart = gv_any && LP <= 2 && L > 32 && P.gstore_buf && P.r_count == 1 && !P.rho_e && !P.force_plain &&
+                          P.total_scanlines <= 512 && g_tune_gv_apart != 1;
     const bool gv = gv_any && !gv_apart;      // the V gradient inside the sweep that runs
     // as many helpers as keep up with the chain while the machine and the LDS have room
     // (measured per launch shape at L = 96: 256 scanlines 165 / 121 / 98 / 90 us with 4 / 6 / 8 / 12
@@ -929,7 +932,10 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
             double *const slots = P.gV;
             P.gV = nullptr; P.gstore = P.gstore_buf;
             hipError_t e = hipErrorInvalidValue;
-            if (ns == 1) e = launch_bwd_chain<2, 1, 2>(P, ni, vg, st);
+            if (LP == 1 && ns == 1) e = launch_bwd_chain<1, 1, 2>(P, ni, vg, st);
+            else if (LP == 1 && ns == 4) e = launch_bwd_chain<1, 4, 2>(P, ni, vg, st);
+            else if (LP == 1 && ns == 8) e = launch_bwd_chain<1, 8, 1>(P, ni, vg, st);
+            else if (ns == 1) e = launch_bwd_chain<2, 1, 2>(P, ni, vg, st);
             else if (ns == 4) e = launch_bwd_chain<2, 4, 2>(P, ni, vg, st);
             else if (ns == 8) e = launch_bwd_chain<2, 8, 1>(P, ni, vg, st);
             P.gV = slots; P.gstore = nullptr;
@@ -1043,7 +1049,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
 
-    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots][node gradients for mrf_bwd_gv_from_g (65..128 labels)]
+    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots][node gradients for mrf_bwd_gv_from_g (33..128 labels)]
     char *ws = (char *)workspace;
     float *scal = (float *)ws;
     float *buf0 = (float *)(ws + kAlign);                   // ISGMR: grad m-hat   TRWP: s per direction
