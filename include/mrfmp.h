@@ -302,7 +302,7 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *           instead of R - 1: 0 = from six directions on, 1 = never, 2 = always (more than one iteration)
  *   knob 18: backward sweep with grad_pairwise for 33..128 labels: the table accumulates in LDS, one per
  *           workgroup of eight wavefronts, instead of in a slot per wavefront in global memory: 0 = yes, 1 = no
- *   knob 19: grad_pairwise for 33..128 labels where the sweep of knob 6 runs one direction of up to 512 scanlines per launch (TRWP): its
+ *   knob 19: grad_pairwise for 65..128 labels where the sweep of knob 6 runs one direction of up to 512 scanlines per launch (TRWP): its
  *           helpers store the gradient vector of every node and a streaming pass adds them into the table
  *           afterwards: 0 = yes, 1 = no (then another sweep accumulates the table itself)
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */

@@ -103,10 +103,10 @@ inline size_t gradv_bytes(const mrf_problem *pr)
     return align_up((size_t)grad_slots(pr->L) * pr->L * pr->L * sizeof(double));
 }
 
-// room for the node gradients that mrf_bwd_gv_from_g reads (33..128 labels)
+// room for the node gradients that mrf_bwd_gv_from_g reads (65..128 labels)
 inline size_t gstore_bytes(const mrf_problem *pr)
 {
-    if (pr->L <= 32 || pr->L > 128) return 0;
+    if (pr->L <= 64 || pr->L > 128) return 0;
     return align_up((size_t)pr->B * pr->H * pr->W * pr->L * sizeof(double));
 }
 
@@ -798,11 +798,13 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
 {
     const dim3 grid((unsigned)P.total_scanlines);
     const bool gv = P.gV != nullptr;
+    const bool gs = LP == 2 && P.gstore != nullptr;       // the helpers store the node gradients (V in LDS, no tables)
+    if (gs) vg = false;
     note_launch(1, "mrf_bwd_sweep_chain", P.total_scanlines, 64 * (1 + ni), "%d,%d,%d,%d,%s,%s,%s", LP, NS, D, ni,
-                (!(LP == 1 && gv) && vg) ? "true" : "false", (LP == 1 && gv) ? "true" : "false",
-                (!(LP == 1 && gv) && !vg && P.hot_label) ? "true" : "false");
+                (!(LP == 1 && gv) && vg) ? "true" : "false", ((LP == 1 && gv) || gs) ? "true" : "false",
+                (!(LP == 1 && gv) && !gs && !vg && P.hot_label) ? "true" : "false");
     if (gv && (LP != 1 || P.total_scanlines * ni > grad_slots(P.g.L))) return hipErrorInvalidValue;
-    const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg, gv);
+    const size_t lds = mrf_bwd_chain_lds_bytes(LP, ni, P.g.L, P.unary_dir >= 0, vg, gv || gs);
     if (lds > chain_lds_cap(P.total_scanlines)) return hipErrorInvalidValue;
     // (more than 64 KB of dynamic LDS has to be announced per kernel)
 #define MRF_CH_GO(...) \
@@ -818,6 +820,12 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
     if (ni == n) { \
         if constexpr (LP == 1) { \
             if (gv) { \
+                MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, false, true, false>); \
+                return hipGetLastError(); \
+            } \
+        } \
+        if constexpr (LP == 2) { \
+            if (gs) { \
                 MRF_CH_GO(mrf_bwd_sweep_chain<LP, NS, D, n, false, true, false>); \
                 return hipGetLastError(); \
             } \
@@ -881,11 +889,11 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
         if (stp > 0x7fffffffLL) step_fits = false;
     }
     const bool gv_any = P.gV != nullptr;
-    // 33..128 labels, one direction per launch: the chain layout has little or no room for V-gradient tables, so its
+    // 65..128 labels, one direction per launch: the chain layout has no room for V-gradient tables, so its
     // helpers store the node gradients and a streaming pass adds them up afterwards (mrf_bwd_gv_from_g)
     // (up to 512 scanlines per launch: beyond that the helpers' gathers from V in global memory hold the chain
     // layout back, 7.8 against 4.5 ms at 1,024 scanlines of 2 x 512 x 512 with 96 labels)
-    const bool gv_apart = gv_any && LP <= 2 && L > 32 && P.gstore_buf && P.r_count == 1 && !P.rho_e && !P.force_plain &&
+    const bool gv_apart = gv_any && LP == 2 && P.gstore_buf && P.r_count == 1 && !P.rho_e && !P.force_plain &&
                           P.total_scanlines <= 512 && g_tune_gv_apart != 1;
     const bool gv = gv_any && !gv_apart;      // the V gradient inside the sweep that runs
     // as many helpers as keep up with the chain while the machine and the LDS have room
@@ -896,14 +904,16 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
                                 : (P.total_scanlines <= 512 ? (LP >= 2 ? 6 : 8) : (P.total_scanlines <= 1024 ? 6 : 4)));
     if (!g_tune_chain_ni && gv && P.total_scanlines > 384 && ni > 6) ni = 6;   // (the accumulators take LDS)
     const bool vg = P.gw && pairwise_kind == MRF_PAIRWISE_DENSE;
-    while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) > chain_lds_cap(P.total_scanlines) ||
+    // (LDS of the chain layout: with the node gradients stored apart it holds all of V, as with its own tables)
+    const bool vg_lds = vg && !gv_apart, gv_lds = gv || gv_apart;
+    while (ni > 2 && (mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg_lds, gv_lds) > chain_lds_cap(P.total_scanlines) ||
                       (gv && P.total_scanlines * ni > grad_slots(L)))) ni = (ni == 12) ? 8 : ni - 2;
     // TRW coefficients or pairwise tables per edge: mrf_bwd_sweep handles them (and is the one
     // sweep that never touches V when no edge-weight gradient is asked for)
     const bool generic = P.rho_e != nullptr || P.force_plain;
     const bool chain_fits = !generic && step_fits && ns <= 8 && g_tune_chain != 1 &&
                             (!gv || (LP == 1 && P.total_scanlines * ni <= grad_slots(L))) &&
-                            mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg, gv) <= chain_lds_cap(P.total_scanlines);
+                            mrf_bwd_chain_lds_bytes(LP, ni, L, P.unary_dir >= 0, vg_lds, gv_lds) <= chain_lds_cap(P.total_scanlines);
     // (65..128 labels with several source arrays, TRWP: at 2,048 scanlines per launch the plain sweep is ahead,
     // 5.1 against 7.5 ms on 4 x 512 x 512 with 96 labels; at 1,024 the chain, 2.3 against 3.6 ms)
     // (more than 128 labels, one source array, ISGMR: at 1,536 scanlines the chain is ahead, 1.7 against 2.4 ms
@@ -932,10 +942,7 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
             double *const slots = P.gV;
             P.gV = nullptr; P.gstore = P.gstore_buf;
             hipError_t e = hipErrorInvalidValue;
-            if (LP == 1 && ns == 1) e = launch_bwd_chain<1, 1, 2>(P, ni, vg, st);
-            else if (LP == 1 && ns == 4) e = launch_bwd_chain<1, 4, 2>(P, ni, vg, st);
-            else if (LP == 1 && ns == 8) e = launch_bwd_chain<1, 8, 1>(P, ni, vg, st);
-            else if (ns == 1) e = launch_bwd_chain<2, 1, 2>(P, ni, vg, st);
+            if (ns == 1) e = launch_bwd_chain<2, 1, 2>(P, ni, vg, st);
             else if (ns == 4) e = launch_bwd_chain<2, 4, 2>(P, ni, vg, st);
             else if (ns == 8) e = launch_bwd_chain<2, 8, 1>(P, ni, vg, st);
             P.gV = slots; P.gstore = nullptr;
@@ -1049,7 +1056,7 @@ int run_backward(const mrf_problem *pr, int algo, const float *grad_cost, const 
     P.rho_e = (algo == MRF_TRWP) ? pr->rho_edge : nullptr;
     const size_t pk = (size_t)R * N * L, qk = (size_t)R * N;
 
-    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots][node gradients for mrf_bwd_gv_from_g (33..128 labels)]
+    // workspace: [scalars 256 B][buf0][buf1 (ISGMR only)][V-gradient slots][node gradients for mrf_bwd_gv_from_g (65..128 labels)]
     char *ws = (char *)workspace;
     float *scal = (float *)ws;
     float *buf0 = (float *)(ws + kAlign);                   // ISGMR: grad m-hat   TRWP: s per direction
@@ -1476,7 +1483,7 @@ const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ?
 
 const char *mrf_last_sweep_launch(int backward) { return g_last_launch[backward ? 1 : 0]; }
 
-const char *mrf_version(void) { return "0.3.3"; }
+const char *mrf_version(void) { return "0.3.4"; }
 
 int mrf_set_sweep_events(void *start_event, void *stop_event)
 {

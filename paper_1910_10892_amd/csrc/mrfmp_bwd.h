@@ -89,7 +89,7 @@ struct MrfBwdParams {
 __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L, bool with_theta, bool vg, bool gv)
 {
     const size_t NR = 2 * (size_t)NI, LL = 64 * (size_t)LP;
-    const size_t arrays = sizeof(double) * (3 * NR * LL + LL + (gv ? (size_t)NI * L * L : 0)) +
+    const size_t arrays = sizeof(double) * (3 * NR * LL + LL + ((gv && LP == 1) ? (size_t)NI * L * L : 0)) +
                           sizeof(float) * (with_theta ? NR * LL : 0) + sizeof(int) * (3 * MRF_CHAIN_MAX_HELPERS + 1) +
                           sizeof(float) * (gv ? (size_t)L * L : (vg ? 0 : (size_t)L)) + NR * LL;
     return (arrays + 7) / 8 * 8 + sizeof(MrfWaitBlock);      // the deadline of the waits sits behind the arrays
@@ -470,7 +470,10 @@ __global__ void __launch_bounds__(64 * WAVES) mrf_bwd_sweep(const MrfBwdParams P
 // pre(t) in its helper, needs the chain to have passed step t - 2 NI + 1 only.
 //
 // GV (L <= 64, as far as LDS has room): the launch also wants the V gradient; every helper keeps an accumulator of
-// its own in LDS, lane lambda owning column lambda, and adds it to its own slot at the end.
+// its own in LDS, lane lambda owning column lambda, and adds it to its own slot at the end.  With more than
+// one label per lane the tables do not fit: GV then means that the helpers store the gradient vector g of every
+// node in P.gstore (0 where no update is replayed), from which mrf_bwd_gv_from_g forms the table afterwards;
+// V is still copied to LDS for the edge-weight gradient.
 // HOT: truncated models send most labels to one source label, and the chain wavefront's LDS
 // adds would queue at that one word; the helpers guess it (as in mrf_bwd_sweep) and the chain
 // sums its lanes with a DPP tree while the LDS round trip is under way.  Costs the chain some
@@ -489,7 +492,9 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
     double *b_sv = b_cin + NR * LL;                              // [NR][LL]                scattered vector that left it
     double *sbuf = b_sv + NR * LL;                               // [LL] scatter target of the chain
     double *gvacc = sbuf + LL;                                   // [NI][L*L] V-gradient accumulators (GV)
-    float *a_extT = reinterpret_cast<float *>(gvacc + (GV ? NI * P.g.L * P.g.L : 0));   // [NR][LL] pre -> post (launches that form grad theta)
+    constexpr bool GVT = GV && LP == 1;      // V-gradient tables in LDS
+    constexpr bool GS = GV && LP != 1;       // node gradients stored for mrf_bwd_gv_from_g
+    float *a_extT = reinterpret_cast<float *>(gvacc + (GVT ? NI * P.g.L * P.g.L : 0));   // [NR][LL] pre -> post (launches that form grad theta)
     int *pre_done = reinterpret_cast<int *>(a_extT + (P.unary_dir >= 0 ? NR * LL : 0));   // [MRF_CHAIN_MAX_HELPERS] per helper: last step published
     int *chain_done = pre_done + MRF_CHAIN_MAX_HELPERS;          // last step the chain finished
     int *a_hot = chain_done + 1;                                 // [NR] pre -> chain: most popular scatter target, or -1
@@ -504,7 +509,8 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
 
     if (GV) {
         for (int e = threadIdx.x; e < L * L; e += blockDim.x) vl[e] = P.V[e];
-        for (int e = threadIdx.x; e < NI * L * L; e += blockDim.x) gvacc[e] = 0.0;
+        if (GVT)
+            for (int e = threadIdx.x; e < NI * L * L; e += blockDim.x) gvacc[e] = 0.0;
     } else if (!VG) {
         for (int e = threadIdx.x; e < L; e += blockDim.x) vl[e] = P.V[e];
     }
@@ -695,18 +701,18 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
             pdst[s] = pb[o + lc];
         }
         qdst = qb[(long long)n * step_n + vzero];
-        wdst = GV ? wb[(long long)n * step_w + vzero] : 0.0f;
+        wdst = GVT ? wb[(long long)n * step_w + vzero] : 0.0f;
     };
     if (T > 0) {
 #pragma unroll
         for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
     }
-    double *gvl = gvacc + (GV ? jw * L * L : 0);
+    double *gvl = gvacc + (GVT ? jw * L * L : 0);
     float wlast = 0.0f;                     // weight of the node whose post stage comes next
     float *guw = P.gunary + (size_t)head * L;                       // stores of stage "post"
     float *sw = P.S + ((size_t)r * N + head) * L;
     float *gww = P.gw ? P.gw + (size_t)r * N + head : nullptr;
-    double *gsw = P.gstore ? P.gstore + (size_t)head * L : nullptr;
+    double *gsw = GS ? P.gstore + (size_t)head * L : nullptr;
 
     int chain_seen = -1;
     for (int it0 = 0; it0 < T + 1 && T > 0; it0 += D) {
@@ -794,10 +800,10 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                     if (own_unary && lam < L)
                         guw[oi + lam] = (float)(cin + (double)a_extT[slot * LL + lam]);
                     if (update && lam < L) sw[oj + lam] = (float)b_sv[slot * LL + lam];
-                    if ((P.gw || GV || gsw) && lam < L) {
+                    if ((P.gw || GV) && lam < L) {
                         const double g = cin + a_ext[slot * LL + lam];    // as the chain formed it
                         const int pv = a_p[slot * LL + lam];
-                        if (gsw) gsw[oi + lam] = update ? g : 0.0;
+                        if constexpr (GS) gsw[oi + lam] = update ? g : 0.0;
                         if (P.gw) {
                             float vv;
                             if (GV) {
@@ -810,7 +816,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
                             }
                             acc = __builtin_fma(g, (double)vv, acc);
                         }
-                        if (GV && update)
+                        if (GVT && update)
                             gvl[__mul24(pv, L) + lam] = __builtin_fma((double)wlast, g, gvl[__mul24(pv, L) + lam]);
                     }
                 }
@@ -837,7 +843,7 @@ __global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain(const MrfBw
             }
         }
     }
-    if (GV) {
+    if (GVT) {
         // one slot per helper of every workgroup
         mrf_wave_lds_fence();
         double *gVs = P.gV + ((size_t)blockIdx.x * NI + jw) * L * L;
