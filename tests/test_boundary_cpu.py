@@ -86,7 +86,8 @@ def test_forward_kernel_choice_is_host_arithmetic():
     """Truncation distance -> window width (0 = dense sweep); no GPU involved."""
     lib = mrf.load_library()
     W = lambda **kw: lib.mrf_forward_window(ctypes.byref(_cprob(**kw)), 0)
-    assert W(L=16, pairwise_kind=1, trunc=4.0) == 8
+    assert W(L=16, pairwise_kind=1, trunc=4.0) == 4
+    assert W(L=16, pairwise_kind=1, trunc=3.0) == 4 and W(L=16, pairwise_kind=1, trunc=4.5) == 8
     assert W(L=96, pairwise_kind=1, trunc=8.0) == 8
     assert W(L=192, pairwise_kind=1, trunc=2.0) == 2
     assert W(L=256, pairwise_kind=2, trunc=200.0) == 16      # ceil(sqrt(200)) = 15
