@@ -195,7 +195,7 @@ inline int window_width(const mrf_problem *pr)
     int ti = (int)ceil(t);
     if (ti < 1) ti = 1;
     if (ti >= pr->L) return 0;
-    return ti <= 2 ? 2 : (ti <= 4 ? 4 : (ti <= 8 ? 8 : 16));
+    return ti <= 2 ? 2 : (ti <= 4 ? 4 : (ti <= 8 ? 8 : (ti <= 12 ? 12 : 16)));
 }
 
 // the three parts
@@ -288,7 +288,7 @@ hipError_t launch_window(const MrfFwdParams &P, int algo, int tw, long long bloc
         else hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, RMAX, D, false, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
         return hipGetLastError(); \
     }
-    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(16)
+    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(12) MRF_W(16)
 #undef MRF_W
     return hipErrorInvalidValue;
 }
@@ -303,7 +303,7 @@ hipError_t launch_window_one(const MrfFwdParams &P, int tw, long long blocks, hi
         hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, 1, 4, false, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
         return hipGetLastError(); \
     }
-    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(16)
+    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(12) MRF_W(16)
 #undef MRF_W
     return hipErrorInvalidValue;
 }
@@ -320,7 +320,7 @@ hipError_t launch_window_many(const MrfFwdParams &P, int tw, long long blocks, h
         hipLaunchKernelGGL((mrf_fwd_sweep_window<LP, 16, D, true, twv>), dim3((unsigned)blocks), dim3(64), 0, st, P); \
         return hipGetLastError(); \
     }
-    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(16)
+    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(12) MRF_W(16)
 #undef MRF_W
     return hipErrorInvalidValue;
 }
@@ -336,7 +336,7 @@ hipError_t launch_window_duo(const MrfFwdParams &P, int algo, int tw, long long 
         else hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, RMAX, D, false, twv, NI, false>), dim3((unsigned)blocks), dim3(64 * (1 + NI)), 0, st, P); \
         return hipGetLastError(); \
     }
-    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(16)
+    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(12) MRF_W(16)
 #undef MRF_W
     return hipErrorInvalidValue;
 }
@@ -351,7 +351,7 @@ hipError_t launch_window_loader(const MrfFwdParams &P, int tw, long long blocks,
         hipLaunchKernelGGL((mrf_fwd_sweep_window_duo<LP, 4, (LP <= 2 ? 4 : 2), true, twv, 2, true>), dim3((unsigned)blocks), dim3(256), 0, st, P); \
         return hipGetLastError(); \
     }
-    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(16)
+    MRF_W(2) MRF_W(4) MRF_W(8) MRF_W(12) MRF_W(16)
 #undef MRF_W
     return hipErrorInvalidValue;
 }
@@ -465,9 +465,9 @@ hipError_t dispatch_fwd(MrfFwdParams &P, int algo, int tw, long long blocks, hip
         // (measured with four directions: window 16, 192 or 256 labels, ISGMR with 1,536 to 3,072 scanlines: 2.2
         // against 3.8 ms, 2.6 against 5.4 ms, 5.0 against 7.2 ms, 7.3 against 8.2 ms for the next best layout; window
         // 8, 192 or 256 labels: the value/index pair is ahead, TRWP 2.3 against 3.9 ms, ISGMR 1.3 against 1.6 ms)
-        const int tws = tw == 4 ? 8 : tw;      // (these two layouts exist for windows 2, 8 and 16: a wider window is as exact)
+        const int tws = tw == 4 ? 8 : (tw == 12 ? 16 : tw);      // (these two layouts exist for windows 2, 8 and 16: a wider window is as exact)
         const bool split = !generic && LPw > 1 && g_tune_split != 1 &&
-                           (g_tune_split == 2 || (LPw >= 3 && tw >= 16 && blocks * LPw <= 16384));
+                           (g_tune_split == 2 || (LPw >= 3 && tws >= 16 && blocks * LPw <= 16384));
         if (ms + 1 <= 8 && split && g_tune_squad != 1 && (g_tune_squad == 2 || blocks <= 512)) {
             // the value wavefronts of the split layout, with the index work on wavefronts of their own
             P.NW = LPw;

@@ -91,6 +91,7 @@ def test_forward_kernel_choice_is_host_arithmetic():
     assert W(L=96, pairwise_kind=1, trunc=8.0) == 8
     assert W(L=192, pairwise_kind=1, trunc=2.0) == 2
     assert W(L=256, pairwise_kind=2, trunc=200.0) == 16      # ceil(sqrt(200)) = 15
+    assert W(L=256, pairwise_kind=2, trunc=100.0) == 12 and W(L=64, pairwise_kind=1, trunc=9.0) == 12
     assert W(L=21, pairwise_kind=0) == 0
     assert W(L=12, pairwise_kind=1, trunc=20.0) == 0          # never truncates inside the label range
     assert W(L=200, pairwise_kind=1, trunc=40.0) == 0         # window wider than the kernel supports

@@ -265,6 +265,8 @@ WINDOW_CASES = [
     # scanlines several times longer than the ring between the value and index wavefronts
     (50, "trwp", 3, 41, 96, DIRS4, 2, 1, 8.0, False, "pos"),
     (54, "trwp", 5, 9, 70, DIRS4, 3, 1, 4.0, False, "pos"),          # window 4
+    (57, "trwp", 4, 7, 96, DIRS4, 2, 1, 11.0, False, "pos"),         # window 12
+    (58, "isgmr", 5, 6, 256, DIRS8, 2, 2, 100.0, True, "zero_mix"),  # quadratic, window 10 -> 12; the 64-label layouts take 16
     (55, "isgmr", 6, 7, 130, DIRS8, 2, 1, 3.0, True, "zero_mix"),
     (56, "trwp", 4, 6, 200, DIRS4, 2, 2, 10.0, True, "pos"),         # quadratic, sqrt(10) -> window 4
     (51, "trwp", 6, 8, 40, DIRS16, 2, 1, 3.0, False, "pos"),       # sixteen directions: fifteen message arrays per update
