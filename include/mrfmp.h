@@ -240,29 +240,30 @@ int mrf_workspace_fault(const void *workspace, void *hip_stream);
 const char *mrf_strerror(int status);
 
 /* After a call returned MRF_ERR_HIP: which runtime call or launch failed and the runtime's
- * own text for the error ("" if none has failed yet).  Process-global, not thread-safe; the
+ * own text for the error ("" if none has failed yet).  Kept per calling thread; the
  * library owns the string. */
 const char *mrf_last_error_detail(void);
 
 /* Name of the kernel template that the most recent forward (backward = 0) or backward
  * (backward != 0) call launched for its last scanline sweep, "" before the first call: which
- * of the sweep layouts the launch-size rules picked.  For reports; process-global. */
+ * of the sweep layouts the launch-size rules picked.  For reports; kept per calling thread. */
 const char *mrf_last_sweep_kernel(int backward);
 
 /* The same launch in full: "name<template arguments> grid=G block=T", e.g.
  * "mrf_fwd_sweep_window<3,8,1,false,2> grid=9788 block=64" -- the instantiation a profiler
  * lists and the launch shape.  For reports and for tests that pin which instantiation a
- * benchmark shape gets; process-global, the library owns the string. */
+ * benchmark shape gets; kept per calling thread, the library owns the string. */
 const char *mrf_last_sweep_launch(int backward);
 
 /* Profiling hook: while set (both non-NULL hipEvent_t handles), every forward or backward
  * call records `start_event` on its stream just before its first scanline-sweep launch and
  * `stop_event` just after its last one, so a caller can time the sweeps apart from the
- * surrounding element-wise kernels.  Pass NULL, NULL to clear.  Process-global, not
- * thread-safe; the caller owns the events. */
+ * surrounding element-wise kernels.  Pass NULL, NULL to clear.  Applies to the calls of the
+ * thread that set it; the caller owns the events. */
 int mrf_set_sweep_events(void *start_event, void *stop_event);
 
-/* Process-global tuning knobs for experiments; results never depend on them.
+/* Tuning knobs for experiments; results never depend on them.  A setting applies to the calls of the
+ * thread that made it (the library keeps these knobs, the hooks above and nothing else, per thread).
  *   knob 0: source labels per wavefront in the dense forward sweep (8, 12, 16, 24, 32, 48; 0 = heuristic)
  *   knob 1: non-zero = ignore pairwise_kind and always run the dense forward sweep
  *   knob 2: window sweep layout: 0 = by launch size, 1 = one wavefront per scanline,
@@ -305,7 +306,7 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 19: grad_pairwise for 65..128 labels where the sweep of knob 6 runs one direction of up to 512 scanlines per launch (TRWP): its
  *           helpers store the gradient vector of every node and a streaming pass adds them into the table
  *           afterwards: 0 = yes, 1 = no (then another sweep accumulates the table itself)
- * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob.  Not thread-safe. */
+ * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob. */
 int mrf_tune(int knob, int value);
 
 /* Library version, e.g. "0.1.0". */

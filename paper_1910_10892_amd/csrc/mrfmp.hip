@@ -113,9 +113,9 @@ inline size_t gstore_bytes(const mrf_problem *pr)
 // ---- process-global state: defined in the translation unit of the entry points ----------
 // tuning knobs (0 = heuristic)
 #if MRF_HAS_API
-#define MRF_G(decl, init) decl = init
+#define MRF_G(decl, init) thread_local decl = init
 #else
-#define MRF_G(decl, init) extern decl
+#define MRF_G(decl, init) extern thread_local decl
 #endif
 MRF_G(int g_tune_mch, 0);
 MRF_G(int g_tune_no_window, 0);
@@ -141,13 +141,13 @@ MRF_G(hipEvent_t g_ev_start, nullptr);
 MRF_G(hipEvent_t g_ev_stop, nullptr);
 #undef MRF_G
 #if MRF_HAS_API
-char g_error_detail[256] = "";
-const char *g_last_sweep[2] = {"", ""};      // kernel of the last forward / backward sweep launch
-char g_last_launch[2][160] = {"", ""};       // the same with template arguments and launch shape
+thread_local char g_error_detail[256] = "";
+thread_local const char *g_last_sweep[2] = {"", ""};      // kernel of the last forward / backward sweep launch
+thread_local char g_last_launch[2][160] = {"", ""};       // the same with template arguments and launch shape
 #else
-extern char g_error_detail[256];
-extern const char *g_last_sweep[2];
-extern char g_last_launch[2][160];
+extern thread_local char g_error_detail[256];
+extern thread_local const char *g_last_sweep[2];
+extern thread_local char g_last_launch[2][160];
 #endif
 
 // records the kernel of a sweep launch: its name, and "name<template arguments> grid=.. block=.."

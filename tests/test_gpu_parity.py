@@ -203,6 +203,40 @@ def test_isgmr_sums_of_the_previous_iteration_formed_once(oracle, case):
         np.testing.assert_array_equal(getattr(a, name), getattr(b, name), err_msg=name)
 
 
+@pytest.mark.gpu
+def test_knobs_and_reports_are_kept_per_thread(oracle):
+    """The kernel-choice knobs and the launch reports are the library's only state and belong to the calling
+    thread: another thread neither sees this thread's knob nor disturbs its report."""
+    import threading
+    import paper_1910_10892_amd as mrf
+    from gpu_harness import GpuProblem
+    pr = make_config(1, algo="isgmr")
+    g = GpuProblem(pr)
+    seen = {}
+    try:
+        assert mrf.mrf_tune(3, 1) == 0                    # this thread: never the packed sweep
+        g.forward()
+        torch_sync = __import__("torch").cuda.synchronize
+        torch_sync()
+        mine = mrf.mrf_last_sweep_kernel(False)
+        assert mine != "mrf_fwd_sweep_packed"
+
+        def other():
+            seen["before"] = mrf.mrf_last_sweep_kernel(False)
+            g2 = GpuProblem(pr)
+            g2.forward()
+            torch_sync()
+            seen["after"] = mrf.mrf_last_sweep_kernel(False)
+        t = threading.Thread(target=other)
+        t.start()
+        t.join()
+        assert seen["before"] == ""                       # nothing launched from that thread yet
+        assert seen["after"] == "mrf_fwd_sweep_packed"    # its own default rules, not this thread's knob
+        assert mrf.mrf_last_sweep_kernel(False) == mine
+    finally:
+        mrf.mrf_tune(3, 0)
+
+
 GV_APART_CASES = [
     # seed, B, H, W, L, dirs, K, integer_valued, per_edge
     (751, 1, 6, 9, 96, DIRS4, 3, False, True), (752, 2, 5, 7, 128, DIRS8, 2, True, True),
