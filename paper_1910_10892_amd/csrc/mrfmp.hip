@@ -852,7 +852,8 @@ hipError_t launch_bwd_packed(const MrfBwdParams &P, int ns, hipStream_t st)
     note_launch(1, "mrf_bwd_sweep_packed", blocks, 64, "%d,%d,%d", SEG, ns, ns <= 4 ? 4 : (ns == 8 ? 2 : 1));
     const size_t lds = sizeof(double) * (64 + (P.gV ? (size_t)NSEG * L * L : 0)) + sizeof(float) * (size_t)L * L;
     const dim3 grid((unsigned)blocks), block(64);
-    if (ns == 1) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 1, 4>), grid, block, lds, st, P);
+    if (ns == 1 && P.unary_dir < 0) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 1, 4, false>), grid, block, lds, st, P);
+    else if (ns == 1) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 1, 4>), grid, block, lds, st, P);
     else if (ns == 4) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 4, 4>), grid, block, lds, st, P);
     else if (ns == 8) hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 8, 2>), grid, block, lds, st, P);
     else hipLaunchKernelGGL((mrf_bwd_sweep_packed<SEG, 16, 1>), grid, block, lds, st, P);

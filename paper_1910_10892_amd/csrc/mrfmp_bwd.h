@@ -1139,7 +1139,8 @@ __device__ inline double mrf_segment_sum_f64(double v)
     return v;
 }
 
-template <int SEG, int NS, int D>
+// UNARY = false: no direction of the launch forms grad theta_i (ISGMR with its combine passes)
+template <int SEG, int NS, int D, bool UNARY = true>
 __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
 {
     constexpr int NSEG = 64 / SEG;
@@ -1163,7 +1164,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     sbuf[lam] = 0.0;
     __syncthreads();
 
-    const bool any_unary = P.unary_dir >= P.r_first && P.unary_dir < P.r_first + P.r_count;
+    const bool any_unary = UNARY && P.unary_dir >= P.r_first && P.unary_dir < P.r_first + P.r_count;
     const long long npacks = (P.total_scanlines + NSEG - 1) / NSEG;
     for (long long pk = blockIdx.x; pk < npacks; pk += gridDim.x) {
         const long long sl = pk * NSEG + seg;
@@ -1196,7 +1197,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
         }
         const long long nstep = (long long)dh * P.g.W + dw;
         const double cscale = (double)cscale_f;
-        const bool own_unary = act_seg && (r == P.unary_dir);
+        const bool own_unary = UNARY && act_seg && (r == P.unary_dir);
         const bool unary_old = own_unary && !P.unary_init;
         const size_t umul = unary_old ? 1 : 0;
         const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
@@ -1232,7 +1233,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
             const long long i = head + (long long)n * nstep;
 #pragma unroll
             for (int c = 0; c < NS; ++c) dst[c] = src[c][(size_t)i * L + lc];
-            udst = P.gunary[((size_t)i * L + lc) * umul];
+            if constexpr (UNARY) udst = P.gunary[((size_t)i * L + lc) * umul]; else udst = 0.0f;
             pdst = pbase[(size_t)i * L + lc];
             qdst = qbase[(size_t)i];
             wdst = wbase[(size_t)(i * P.w_mul)];
@@ -1268,7 +1269,7 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
                 const long long j = i - nstep;
 
                 double g = valid ? carry + ext[u] : 0.0;
-                if (any_unary) {        // (uniform) some scanline of this launch forms grad theta
+                if constexpr (UNARY) if (any_unary) {        // (uniform) some scanline of this launch forms grad theta
                     double accT = carry;
 #pragma unroll
                     for (int c = 0; c < NS; ++c) accT = __builtin_fma(cT[c], (double)cur[u][c], accT);
