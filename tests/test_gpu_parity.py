@@ -1064,10 +1064,10 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     if kind:
         scale = 1.0 if iv else 0.41
         if kind == 1:
-            trunc = float(rng.choice([2.0, 8.0, 16.0]))
+            trunc = float(rng.choice([2.0, 3.0, 8.0, 11.0, 16.0]))
             pr.pairwise = truncated_linear(L, trunc, scale)
         elif kind == 2:
-            trunc = float(rng.choice([4.0, 30.0, 200.0]))
+            trunc = float(rng.choice([4.0, 12.0, 30.0, 110.0, 200.0]))
             pr.pairwise = truncated_quadratic(L, trunc, scale)
         else:
             trunc = 2.0
