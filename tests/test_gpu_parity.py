@@ -9,6 +9,8 @@ carries its sums in double and rounds once on store; the float32 instantiation o
 oracle rounds after every addition and is itself up to about one tolerance away from the
 double one on the larger problems -- its distance is printed, not asserted).
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -885,7 +887,11 @@ def _drawn_problem(seed):
     return pr, bool(rng.integers(0, 2))
 
 
-@pytest.mark.parametrize("seed", range(150))
+# MRF_TEST_EXTRA_SEEDS=n adds n further seeds to each of the three drawn-problem tests (a longer soak)
+EXTRA_SEEDS = int(os.environ.get("MRF_TEST_EXTRA_SEEDS", "0"))
+
+
+@pytest.mark.parametrize("seed", range(150 + EXTRA_SEEDS))
 def test_drawn_problems_default_dispatch(oracle, seed):
     """Whatever kernels the launch rules pick for a randomly drawn small problem, with and without
     a grad_pairwise buffer."""
@@ -904,7 +910,7 @@ def test_drawn_problems_default_dispatch(oracle, seed):
     full_check(oracle, pr, want_V=want_V)
 
 
-@pytest.mark.parametrize("seed", range(120))
+@pytest.mark.parametrize("seed", range(120 + EXTRA_SEEDS))
 def test_drawn_problems_forced_layouts(oracle, seed):
     """The same kind of random problems with the kernel-choice knobs drawn at random too, so that
     layouts meet shapes they would not be picked for (the results may not depend on the knobs)."""
@@ -1045,7 +1051,7 @@ def test_per_edge_tables_argument_errors():
         mrf.mrf_isgmr_backward(prob, z(1, 2, 2, L), p, q, z(1, 2, 2, L), z(4, 1, 2, 2), None, ws)
 
 
-@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("seed", range(30 + EXTRA_SEEDS))
 def test_drawn_medium_problems_forced_layouts(oracle, seed):
     """Random problems whose scanlines are several times longer than the LDS rings of the
     taken-apart layouts (20..69 nodes), with the kernel-choice knobs drawn at random."""
