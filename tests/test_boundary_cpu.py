@@ -193,3 +193,14 @@ def test_scanline_geometry_errors():
     assert mrf.mrf_scanline_count(4, 4, 0, 0) == -5
     with pytest.raises(mrf.MrfError):
         mrf.mrf_scanline_head(4, 4, 0, 1, 4)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other --gpus ends with a message and a non-zero status before
+    anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
