@@ -741,7 +741,12 @@ hipError_t launch_bwd(const MrfBwdParams &P, long long blocks, size_t lds, hipSt
     else if (P.gw && P.v_mode == 0)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, true, false>), grid, block, lds, st, P);
     else if (no_unary) {
-        if constexpr (NS == 1) hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true, false, false>), grid, block, lds, st, P);
+        if constexpr (NS == 1) {
+            if (P.g.L == 64 * LP)
+                hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true, false, false, MRF_BWD_WAVES, true>), grid, block, lds, st, P);
+            else
+                hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true, false, false>), grid, block, lds, st, P);
+        }
     } else if (P.hot_label)
         hipLaunchKernelGGL((mrf_bwd_sweep<LP, NS, D, false, true>), grid, block, lds, st, P);
     else

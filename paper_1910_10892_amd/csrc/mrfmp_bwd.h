@@ -104,11 +104,13 @@ __host__ __device__ inline size_t mrf_bwd_chain_lds_bytes(int LP, int NI, int L,
 // UNARY = false: no direction of the launch forms grad theta_i (P.unary_dir < 0: ISGMR leaves it to
 // mrf_isgmr_bwd_combine), so nothing of it is loaded or kept in registers.
 // WAVES: wavefronts per workgroup (more of them share the one V-gradient table of P.gv_lds == 2).
-template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false, bool UNARY = true, int WAVES = MRF_BWD_WAVES>
+// FULL: the launch has exactly 64 LP labels (the host checks it), so every label test folds away and the
+// strides are constants.
+template <int LP, int NS, int D, bool VG, bool HOT, bool RHOE = false, bool UNARY = true, int WAVES = MRF_BWD_WAVES, bool FULL = false>
 __global__ void __launch_bounds__(64 * WAVES) mrf_bwd_sweep(const MrfBwdParams P)
 {
     extern __shared__ __align__(16) unsigned char mrf_bsmem[];
-    const int L = P.g.L;
+    const int L = FULL ? 64 * LP : P.g.L;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform, and known to be
     double *sbuf = reinterpret_cast<double *>(mrf_bsmem) + wv * 64 * LP;
