@@ -306,6 +306,8 @@ int mrf_set_sweep_events(void *start_event, void *stop_event);
  *   knob 19: grad_pairwise for 65..128 labels where the sweep of knob 6 runs one direction of up to 512 scanlines per launch (TRWP): its
  *           helpers store the gradient vector of every node and a streaming pass adds them into the table
  *           afterwards: 0 = yes, 1 = no (then another sweep accumulates the table itself)
+ *   knob 20: backward sweep of knob 6 with two scanlines of up to 32 labels per workgroup (one direction per
+ *           launch, TRWP): 0 = for 1,025 to 2,048 scanlines per launch, 1 = never, 2 = whenever it applies
  * Returns MRF_OK, or MRF_ERR_BAD_ALGORITHM for an unknown knob. */
 int mrf_tune(int knob, int value);
 

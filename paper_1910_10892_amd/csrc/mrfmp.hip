@@ -129,6 +129,7 @@ MRF_G(int g_tune_squad_ni, 0);   // how many: 0 auto, 4, 8
 MRF_G(int g_tune_pack3, 0);      // three scanlines per wavefront for 17..21 labels: 0 by launch size, 1 never, 2 always
 MRF_G(int g_tune_isgmr_lazy, 0); // ISGMR backward without a combine pass per iteration (up to 4 directions): 0 auto, 1 never
 MRF_G(int g_tune_isgmr_presum, 0); // ISGMR forward with the per-pair sums of the previous iteration formed once: 0 from six directions, 1 never, 2 always
+MRF_G(int g_tune_chain_pk, 0);     // chain backward with two scanlines of up to 32 labels per workgroup: 0 = 1,025..2,048 scanlines of one direction, 1 never, 2 always
 MRF_G(int g_tune_gv_apart, 0);     // V gradient of 65..128 labels by a streaming pass behind the chain backward sweep: 0 yes, 1 no
 MRF_G(int g_tune_gv_tile, 0);      // V gradient of 33..128 labels in one LDS table per workgroup: 0 yes, 1 no (a slot per wavefront in global memory)
 MRF_G(int g_tune_dense_sliced, 0); // dense sweep for more than 64 labels with a slice of the labels per wavefront: 0 yes, 1 no
@@ -847,6 +848,28 @@ hipError_t launch_bwd_chain(const MrfBwdParams &P, int ni, bool vg, hipStream_t 
     return hipErrorInvalidValue;
 }
 
+// two scanlines of up to 32 labels per workgroup: chain wavefront + ni helpers
+template <int NS, int D>
+hipError_t launch_bwd_chain_pk(const MrfBwdParams &P, int ni, hipStream_t st)
+{
+    const long long blocks = (P.total_scanlines + 1) / 2;
+    const bool gv = P.gV != nullptr;
+    note_launch(1, "mrf_bwd_sweep_chain_pk", blocks, 64 * (1 + ni), "%d,%d,%d,%s", NS, D, ni, gv ? "true" : "false");
+    if (gv && blocks * 2 > grad_slots(P.g.L)) return hipErrorInvalidValue;
+    const size_t lds = mrf_bwd_chain_pk_lds_bytes(ni, P.g.L, gv);
+    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(64 * (1 + ni));
+#define MRF_PK(n) \
+    if (ni == n) { \
+        if (gv) hipLaunchKernelGGL((mrf_bwd_sweep_chain_pk<NS, D, n, true>), grid, block, lds, st, P); \
+        else hipLaunchKernelGGL((mrf_bwd_sweep_chain_pk<NS, D, n, false>), grid, block, lds, st, P); \
+        return hipGetLastError(); \
+    }
+    MRF_PK(2) MRF_PK(4) MRF_PK(8)
+#undef MRF_PK
+    return hipErrorInvalidValue;
+}
+
 template <int SEG>
 hipError_t launch_bwd_packed(const MrfBwdParams &P, int ns, hipStream_t st)
 {
@@ -929,6 +952,21 @@ hipError_t dispatch_bwd(MrfBwdParams &P, int pairwise_kind, hipStream_t st)
     // 0.80 against 1.04 ms at 2,876 scanlines of a 160 x 320 grid, 0.81 against 0.89 ms at 3,452 of 192 x 384)
     const long long chain_max = LP <= 2 ? ((LP == 2 && ns >= 4) ? 1536 : (P.r_count >= 8 ? 3584 : 2560)) : (ns == 1 ? 1536 : 512);
     const bool chain = chain_fits && (g_tune_chain == 2 || P.total_scanlines <= chain_max);
+    // few labels, one direction per launch (TRWP), more scanlines than the chain layout takes one by one: two
+    // scanlines per workgroup around a chain wavefront
+    if (!generic && L <= 32 && P.r_count == 1 && ns <= 8 && g_tune_chain != 1 && g_tune_pack != 2 && g_tune_chain_pk != 1 &&
+        (g_tune_chain_pk == 2 || (P.total_scanlines > 1024 && P.total_scanlines <= 2048))) {
+        // (helpers: 4 x 512 x 512, 32 labels, 2,048 scanlines: 3.0 ms with four, 3.2 with eight, 3.5 ms for the packed
+        // sweep; 3 x 512 x 512, 16 labels, 8 directions, 1,536 scanlines: 5.0 / 4.3 / 5.4 ms; the LDS of a compute unit,
+        // which four such workgroups share, sets the pace)
+        const int nip = (g_tune_chain_ni == 2 || g_tune_chain_ni == 4 || g_tune_chain_ni == 8) ? g_tune_chain_ni
+                                                                                            : (P.total_scanlines <= 1536 ? 8 : 4);
+        if (!(gv_any && (P.total_scanlines + 1) / 2 * 2 > grad_slots(L))) {
+            if (ns == 1) return launch_bwd_chain_pk<1, 2>(P, nip, st);
+            if (ns == 4) return launch_bwd_chain_pk<4, 2>(P, nip, st);
+            return launch_bwd_chain_pk<8, 1>(P, nip, st);
+        }
+    }
     // few labels: several scanlines per wavefront, once there are enough of them
     if (!generic && L <= 32 && g_tune_pack != 1 && (g_tune_pack == 2 || P.total_scanlines >= 256) &&
         !(chain && g_tune_pack != 2 && (g_tune_chain == 2 || P.total_scanlines <= ((ns == 1 && !gv) ? 1536 : 1024))))
@@ -1520,6 +1558,7 @@ int mrf_tune(int knob, int value)
     if (knob == 17) { g_tune_isgmr_presum = value; return MRF_OK; }
     if (knob == 18) { g_tune_gv_tile = value; return MRF_OK; }
     if (knob == 19) { g_tune_gv_apart = value; return MRF_OK; }
+    if (knob == 20) { g_tune_chain_pk = value; return MRF_OK; }
     if (knob == 7) { g_tune_chain_ni = (value == 2 || value == 4 || value == 6 || value == 8 || value == 12) ? value : 0; return MRF_OK; }
     return MRF_ERR_BAD_ALGORITHM;
 }

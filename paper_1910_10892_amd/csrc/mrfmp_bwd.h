@@ -1319,6 +1319,283 @@ __global__ void __launch_bounds__(64) mrf_bwd_sweep_packed(const MrfBwdParams P)
     }
 }
 
+// ---- the chain layout for up to 32 labels: two scanlines per workgroup -------------------------
+//
+// mrf_bwd_sweep_chain with the lanes of every wavefront divided as in mrf_bwd_sweep_packed: lanes 0-31 hold
+// the labels of one scanline, lanes 32-63 those of the next (one direction per launch, so everything but the
+// head and the length of the scanline is shared).  Ring entries are indexed by lane; a scatter target is
+// stored as 32 seg + p, so the chain wavefront's step is that of mrf_bwd_sweep_chain unchanged: it neither
+// knows nor cares that its 64 entries are two vectors.  A scanline that is shorter than its neighbour gets
+// zeros with targets of their own for the steps past its first node, and nothing of those steps is stored.
+// For launches of more than 1,024 scanlines of up to 32 labels with one direction (TRWP), where
+// mrf_bwd_sweep_packed leaves a lone wavefront per SIMD to do all of a node's work in sequence.
+__host__ __device__ inline size_t mrf_bwd_chain_pk_lds_bytes(int NI, int L, bool gv)
+{
+    const size_t NR = 2 * (size_t)NI, LL = 64;
+    const size_t arrays = sizeof(double) * (3 * NR * LL + LL + (gv ? (size_t)2 * L * L : 0)) +
+                          sizeof(float) * (NR * LL + (size_t)L * L) + sizeof(int) * (MRF_CHAIN_MAX_HELPERS + 4) + NR * LL;
+    return (arrays + 7) / 8 * 8 + sizeof(MrfWaitBlock);
+}
+
+template <int NS, int D, int NI, bool GV>
+__global__ void __launch_bounds__(64 * (1 + NI)) mrf_bwd_sweep_chain_pk(const MrfBwdParams P)
+{
+    constexpr int NR = 2 * NI;
+    constexpr int LL = 64;
+    static_assert(NI >= 2 && NI <= MRF_CHAIN_MAX_HELPERS, "helpers per pair of scanlines");
+    extern __shared__ __align__(16) unsigned char mrf_bsmem[];
+    const int L = P.g.L;
+    // carved in the order of mrf_bwd_chain_pk_lds_bytes
+    double *a_ext = reinterpret_cast<double *>(mrf_bsmem);       // [NR][LL] pre -> chain, post
+    double *b_cin = a_ext + NR * LL;                             // [NR][LL] chain -> post: carry that entered the node
+    double *b_sv = b_cin + NR * LL;                              // [NR][LL]                scattered vector that left it
+    double *sbuf = b_sv + NR * LL;                               // [LL] scatter target of the chain
+    double *gvacc = sbuf + LL;                                   // [2][L*L] V-gradient tables of the two scanlines (GV): LDS adds by all helpers
+    float *a_extT = reinterpret_cast<float *>(gvacc + (GV ? 2 * L * L : 0));   // [NR][LL] pre -> post (grad theta)
+    float *vl = a_extT + NR * LL;                                // [L*L] V
+    int *pre_done = reinterpret_cast<int *>(vl + L * L);         // [MRF_CHAIN_MAX_HELPERS] per helper: last step published
+    int *chain_done = pre_done + MRF_CHAIN_MAX_HELPERS;          // last step the chain finished
+    uint8_t *a_p = reinterpret_cast<uint8_t *>(chain_done + 4);  // [NR][LL]
+    MrfWaitBlock &wait_lds = *reinterpret_cast<MrfWaitBlock *>(
+        mrf_bsmem + ((a_p + NR * LL - mrf_bsmem) + 7) / 8 * 8);
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int seg = lane >> 5, lam = lane & 31;
+    const bool valid = lam < L;
+    const int lc = valid ? lam : 0;
+    const long long N = P.g.N;
+
+    for (int e = threadIdx.x; e < L * L; e += blockDim.x) vl[e] = P.V[e];
+    if (GV)
+        for (int e = threadIdx.x; e < 2 * L * L; e += blockDim.x) gvacc[e] = 0.0;
+    if (threadIdx.x < MRF_CHAIN_MAX_HELPERS) pre_done[threadIdx.x] = (int)threadIdx.x - NI;
+    if (threadIdx.x == 0) { *chain_done = -1; chain_done[1] = 0; mrf_wait_init(&wait_lds, P.fault, P.spin_limit); }
+    for (int e = threadIdx.x; e < LL; e += blockDim.x) sbuf[e] = 0.0;
+    __syncthreads();
+
+    // one direction per launch; the two scanlines of the workgroup
+    const int r = P.r_first;
+    const long long sl = (long long)blockIdx.x * 2 + seg;
+    const bool act_seg = sl < P.total_scanlines;
+    const int dh = P.g.dh[r], dw = P.g.dw[r];
+    int y0 = 0, x0 = 0, len = 0;
+    long long head = 0;
+    if (act_seg) {
+        const int nsc = P.g.nscan[r];
+        const int b = (int)(sl / nsc);
+        const long long t = sl - (long long)b * nsc;
+        mrf_geom_head(P.g.H, P.g.W, dh, dw, t, y0, x0, len);
+        head = ((long long)b * P.g.H + y0) * P.g.W + x0;
+    }
+    const long long nstep = (long long)dh * P.g.W + dw;
+    const int len0 = __builtin_amdgcn_readlane(len, 0), len1 = __builtin_amdgcn_readlane(len, 32);
+    const int maxlen = len0 > len1 ? len0 : len1;
+
+    if (wv == 0) {
+        // ---- the chain: step tt handles node len-1-tt of either scanline (mrf_bwd_sweep_chain's step) ----
+        const double cscale = (double)P.carry_scale[r];
+        double carry = 0.0, ext;
+        int pv;
+        auto await = [&](int u, int tt) {
+            int sn;
+            int wait_turns = 0;
+            do {
+                sn = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(&pre_done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (sn < tt) mrf_wait_turn(&wait_lds, wait_turns);
+            } while (sn < tt);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        };
+        if (maxlen > 0) {
+            await(0, 0);
+            ext = a_ext[lane];
+            pv = a_p[lane];
+        } else {
+            ext = 0.0;
+            pv = lane;
+        }
+        int sb = 0;
+        for (int t0 = 0; t0 < maxlen; t0 += NI) {
+#pragma unroll
+            for (int u = 0; u < NI; ++u) {
+                const int tt = t0 + u;
+                if (tt < maxlen) {
+                    const int slot = sb + u;
+                    const int un = (u + 1 == NI) ? 0 : u + 1;
+                    const int slotn = (u + 1 == NI) ? (sb == 0 ? NI : 0) : slot + 1;
+                    const bool more = tt + 1 < maxlen;
+                    const double g = carry + ext;
+                    b_cin[slot * LL + lane] = carry;
+                    __hip_atomic_fetch_add(&sbuf[pv], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    mrf_wave_lds_fence();
+                    const int flag = __hip_atomic_load(&pre_done[un], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    ext = a_ext[slotn * LL + lane];
+                    pv = a_p[slotn * LL + lane];
+                    const double sv = sbuf[lane];
+                    if (__builtin_expect(more && __builtin_amdgcn_readfirstlane(flag) < tt + 1, 0)) {
+                        await(un, tt + 1);
+                        ext = a_ext[slotn * LL + lane];
+                        pv = a_p[slotn * LL + lane];
+                    }
+                    // everything this wavefront sent to LDS before the reads above has landed
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                    __builtin_amdgcn_wave_barrier();
+                    if (tt > 0)
+                        __hip_atomic_store(chain_done, tt - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    sbuf[lane] = 0.0;
+                    b_sv[slot * LL + lane] = sv;
+                    carry = cscale * sv;
+                }
+            }
+            sb = (sb == 0) ? NI : 0;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) __hip_atomic_store(chain_done, maxlen - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return;
+    }
+
+    // ---- helpers ---------------------------------------------------------------------------
+    const int jw = wv - 1;
+    const bool own_unary = (r == P.unary_dir);
+    const bool unary_old = own_unary && !P.unary_init;
+    const uint8_t *pbase = P.p + (size_t)r * N * L;
+    const uint8_t *qbase = P.q + (size_t)r * N;
+    const float *wbase = P.w + (P.w_mul ? (size_t)r * N : 0);
+
+    const float *src[NS];
+    double cG[NS], cT[NS];
+    const int nsrc = P.n_src[r];
+#pragma unroll
+    for (int c = 0; c < NS; ++c) {
+        const bool live = c < nsrc;
+        const bool isgc = (c == nsrc) && P.use_gc;
+        src[c] = live ? P.src_base + (size_t)P.src_dir[r][c] * P.src_stride : P.gc;
+        cG[c] = live ? (double)P.coefG[r][c] : (isgc ? 1.0 : 0.0);
+        cT[c] = live ? (double)P.coefT[r][c] : (isgc ? 1.0 : 0.0);
+    }
+
+    // the last node of a scanline has no successor in direction r
+    if (jw == 0 && act_seg && valid && len > 0)
+        P.S[((size_t)r * N + head + (long long)(len - 1) * nstep) * L + lam] = 0.0f;
+
+    // own steps: tt = jw + it * NI, it = 0 .. T-1; one more turn for the last post
+    const int T = maxlen > jw ? (maxlen - jw + NI - 1) / NI : 0;
+    float cur[D][NS], nxt[D][NS];
+    float ucur[D], unxt[D];
+    int pcur[D], pnxt[D], qcur[D], qnxt[D];
+    float wcur[D], wnxt[D];                 // edge weight of the node's incoming edge (GV)
+    auto prefetch = [&](float (&dst)[NS], float &udst, int &pdst, int &qdst, float &wdst, int it) {
+        int n = len - 1 - (jw + it * NI);
+        n = n > 0 ? n : 0;
+        const long long i = head + (long long)n * nstep;
+#pragma unroll
+        for (int c = 0; c < NS; ++c) dst[c] = src[c][(size_t)i * L + lc];
+        udst = P.gunary[unary_old ? (size_t)i * L + lc : 0];      // one cached word unless it is needed
+        pdst = pbase[(size_t)i * L + lc];
+        qdst = qbase[(size_t)i];
+        wdst = GV ? wbase[(size_t)(i * P.w_mul)] : 0.0f;
+    };
+    if (T > 0) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(cur[u], ucur[u], pcur[u], qcur[u], wcur[u], u);
+    }
+    double *gvl = gvacc + (GV ? seg * L * L : 0);
+    float wlast = 0.0f;                     // weight of the node whose post stage comes next
+
+    int chain_seen = -1;
+    for (int it0 = 0; it0 < T + 1 && T > 0; it0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) prefetch(nxt[u], unxt[u], pnxt[u], qnxt[u], wnxt[u], it0 + D + u);
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int tt = jw + (it0 + u) * NI;
+            if (tt < maxlen) {
+                // ---- pre(tt): everything of node len-1-tt that does not need the carry -------
+                const int slot = tt % NR;
+                const bool live = valid && tt < len;       // (false for the whole of a scanline that has ended)
+                double e = 0.0, eT = 0.0;
+#pragma unroll
+                for (int c = 0; c < NS; ++c) e = __builtin_fma(cG[c], (double)cur[u][c], e);
+                if (own_unary) {
+#pragma unroll
+                    for (int c = 0; c < NS; ++c) eT = __builtin_fma(cT[c], (double)cur[u][c], eT);
+                    eT += unary_old ? (double)ucur[u] : 0.0;     // (the buffer may hold anything at first)
+                    a_extT[slot * LL + lane] = (float)eT;
+                }
+                const double ev = live ? e : 0.0;
+                // (labels past L and scanlines that have ended scatter their zeros to entries of their own)
+                a_p[slot * LL + lane] = (uint8_t)(live ? 32 * seg + (pcur[u] < L ? pcur[u] : L - 1) : lane);
+                // back Eq. isgmr-norm, on the part of g that is known here: the entry at q loses the label sum
+                const double tot = mrf_segment_sum_f64<32>(ev);
+                const int qv = qcur[u] < L ? qcur[u] : L - 1;
+                a_ext[slot * LL + lane] = (live && lam == qv) ? ev - tot : ev;
+                // (LDS keeps a wavefront's operations in order: the counter lands behind the entries)
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                if (lane == 0) __hip_atomic_store(&pre_done[jw], tt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            const int tp = tt - NI;
+            if (tp >= 0 && tp < maxlen) {
+                // ---- post(tp): what is left of node len-1-tp once the chain has passed --------
+                int wait_turns = 0;
+                while (chain_seen < tp) {
+                    chain_seen = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(chain_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    if (chain_seen < tp) mrf_wait_turn(&wait_lds, wait_turns);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                const int slot = tp % NR;
+                const int n = len - 1 - tp;
+                const bool act = valid && n >= 0;        // the node exists
+                const bool update = valid && n > 0;      // and has a predecessor: its update is replayed
+                const long long i = head + (long long)(n > 0 ? n : 0) * nstep;
+                const double cin = b_cin[slot * LL + lane];
+                if (own_unary && act) P.gunary[(size_t)i * L + lam] = (float)(cin + (double)a_extT[slot * LL + lane]);
+                if (update) P.S[((size_t)r * N + i - nstep) * L + lam] = (float)b_sv[slot * LL + lane];
+                if (P.gw || GV) {
+                    const double g = cin + a_ext[slot * LL + lane];    // as the chain formed it
+                    const int pv = update ? (int)a_p[slot * LL + lane] - 32 * seg : 0;
+                    if (P.gw) {
+                        double acc = update ? g * (double)vl[__mul24(pv, L) + lam] : 0.0;
+                        acc = mrf_segment_sum_f64<32>(acc);
+                        // one writer per entry and launch: a no-return atomic is a plain accumulate
+                        if (n > 0 && lam == 0)
+                            __hip_atomic_fetch_add(&P.gw[(size_t)r * N + i], (float)acc, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if (GV && update)
+                        __hip_atomic_fetch_add(&gvl[__mul24(pv, L) + lam], (double)wlast * g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+            wlast = wcur[u];
+        }
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            qcur[u] = qnxt[u];
+            wcur[u] = wnxt[u];
+            ucur[u] = unxt[u];
+            pcur[u] = pnxt[u];
+#pragma unroll
+            for (int c = 0; c < NS; ++c) cur[u][c] = nxt[u][c];
+        }
+    }
+    if (GV) {
+        // the helper that finishes last adds the two tables to the workgroup's two slots
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_wave_barrier();
+        int before = 0;
+        if (lane == 0) before = __hip_atomic_fetch_add(&chain_done[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        before = __builtin_amdgcn_readfirstlane(before);
+        if (before == NI - 1) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            double *gVs = P.gV + ((size_t)blockIdx.x * 2 + seg) * L * L;
+            if (valid)
+                for (int e = lam; e < L * L; e += L) gVs[e] += gvl[e];
+        }
+    }
+}
+
 // ISGMR, after the sweeps of iteration k: grad theta_i += sum_r s^r_i, and the gradient of
 // m^d (= m-hat^d of iteration k-1) is sum over r not in {d, d-} of s^r_i.
 struct MrfCombineParams {

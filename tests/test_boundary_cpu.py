@@ -141,12 +141,12 @@ def test_workspace_fault_query_rejects_null():
 
 
 def test_every_documented_knob_is_known_and_others_are_refused():
-    """mrf_tune: knobs 0..19 as the header lists them; an unknown knob is an error, not a silent no-op."""
-    for knob in range(20):
+    """mrf_tune: knobs 0..20 as the header lists them; an unknown knob is an error, not a silent no-op."""
+    for knob in range(21):
         assert mrf.mrf_tune(knob, 0) == 0, knob
-    assert mrf.mrf_tune(20, 0) != 0 and mrf.mrf_tune(-1, 0) != 0
+    assert mrf.mrf_tune(21, 0) != 0 and mrf.mrf_tune(-1, 0) != 0
     header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "mrfmp.h")).read()
-    for knob in range(20):
+    for knob in range(21):
         assert "knob %d:" % knob in header, knob
 
 

@@ -239,6 +239,42 @@ def test_knobs_and_reports_are_kept_per_thread(oracle):
         mrf.mrf_tune(3, 0)
 
 
+CHAIN_PK_CASES = [
+    # seed, B, H, W, L, dirs, K, integer_valued, per_edge, want_V
+    (771, 1, 6, 9, 21, DIRS4, 3, False, True, True), (772, 3, 5, 7, 32, DIRS8, 2, True, True, False),
+    (773, 1, 7, 5, 5, ((0, 1), (1, 0), (1, 1)), 2, False, False, True), (774, 1, 1, 13, 17, DIRS4, 2, False, True, True),
+    (775, 2, 9, 4, 1, DIRS4, 2, False, True, True), (776, 1, 23, 31, 16, DIRS8, 2, True, True, True),
+    (777, 1, 40, 37, 21, DIRS4, 2, False, True, True),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", CHAIN_PK_CASES, ids=lambda c: "seed%d" % c[0])
+def test_chain_backward_with_two_scanlines_per_workgroup(oracle, case):
+    """TRWP with up to 32 labels: the chain layout with two scanlines per workgroup (odd scanline counts,
+    diagonal scanlines of unequal length, one-node scanlines, with and without grad_pairwise) against the oracle
+    and against the layout the rules would pick."""
+    import paper_1910_10892_amd as mrf
+    print("case chain pk", case[:5], len(case[5]), case[6:], flush=True)
+    seed, B, H, W, L, dirs, K, iv, per_edge, want_V = case
+    pr = random_problem(seed, "trwp", B, H, W, L, dirs, K, integer_valued=iv, per_edge=per_edge, symmetric=False,
+                        rho=np.linspace(0.3, 0.9, len(dirs)))
+    pr.grad_cost = (pr.grad_cost * 0.2).astype(np.float32)
+    try:
+        for ni in (2, 4, 8):
+            assert mrf.mrf_tune(20, 2) == 0 and mrf.mrf_tune(7, ni) == 0
+            a = full_check(oracle, pr, want_V=want_V)
+            assert mrf.mrf_last_sweep_kernel(True) == "mrf_bwd_sweep_chain_pk", mrf.mrf_last_sweep_launch(True)
+        assert mrf.mrf_tune(20, 1) == 0 and mrf.mrf_tune(7, 0) == 0
+        b = full_check(oracle, pr, want_V=want_V)
+        assert mrf.mrf_last_sweep_kernel(True) != "mrf_bwd_sweep_chain_pk"
+    finally:
+        mrf.mrf_tune(20, 0)
+        mrf.mrf_tune(7, 0)
+    for name in ("grad_unary", "grad_edge_weight") + (("grad_pairwise",) if want_V else ()):
+        check_grad(name + " (two layouts)", getattr(a, name), None, getattr(b, name).astype(np.float64))
+
+
 GV_APART_CASES = [
     # seed, B, H, W, L, dirs, K, integer_valued, per_edge
     (751, 1, 6, 9, 96, DIRS4, 3, False, True), (752, 2, 5, 7, 128, DIRS8, 2, True, True),
@@ -920,7 +956,7 @@ def test_drawn_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2)), 19: int(rng.integers(0, 2))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2)), 19: int(rng.integers(0, 2)), 20: int(rng.integers(0, 3))}
     print("case drawn+knobs", seed, pr.algo, pr.shape, len(pr.dirs), pr.K, pr.pairwise_kind, pr.trunc, want_V, knobs,
           flush=True)
     f = oracle_forward(oracle, pr)
@@ -1083,7 +1119,7 @@ def test_drawn_medium_problems_forced_layouts(oracle, seed):
     knobs = {2: int(rng.integers(0, 3)), 3: int(rng.integers(0, 3)), 4: int(rng.integers(0, 3)),
              5: int(rng.integers(0, 3)), 6: int(rng.integers(0, 3)), 7: int(rng.choice([0, 2, 4, 6, 8, 12])),
              8: int(rng.integers(0, 3)), 9: int(rng.integers(0, 3)), 10: int(rng.choice([0, 4, 8])),
-             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2)), 19: int(rng.integers(0, 2))}
+             11: int(rng.integers(0, 3)), 12: int(rng.integers(0, 3)), 13: int(rng.integers(0, 3)), 15: int(rng.integers(0, 3)), 16: int(rng.integers(0, 3)), 17: int(rng.integers(0, 3)), 18: int(rng.integers(0, 2)), 19: int(rng.integers(0, 2)), 20: int(rng.integers(0, 3))}
     print("case drawn medium", seed, algo, (B, H, W, L), len(dirs), K, kind, want_V, knobs, flush=True)
     f = oracle_forward(oracle, pr, threads=True)
     b = oracle_backward(oracle, pr, f.p, f.q, np.float64)
