@@ -1528,7 +1528,7 @@ const char *mrf_last_sweep_kernel(int backward) { return g_last_sweep[backward ?
 
 const char *mrf_last_sweep_launch(int backward) { return g_last_launch[backward ? 1 : 0]; }
 
-const char *mrf_version(void) { return "0.3.7"; }
+const char *mrf_version(void) { return "0.3.8"; }
 
 int mrf_set_sweep_events(void *start_event, void *stop_event)
 {
