@@ -676,17 +676,22 @@ def test_waits_between_wavefronts_are_bounded(oracle):
     import paper_1910_10892_amd as mrf
     from gpu_harness import GpuProblem
     print("case bounded waits", flush=True)
-    cases = [make_config(2, crop=(24, 40), algo="trwp"),       # value / loader / index wavefronts, chain backward
-             make_config(4, crop=(10, 12), algo="trwp", K=2),  # value wavefronts that meet through LDS, index wavefronts
-             make_config(5, crop=(24, 32), algo="trwp")]       # packed scanlines with index wavefronts
-    for pr in cases:
+    cases = [(make_config(2, crop=(24, 40), algo="trwp"), {}),       # value / loader / index wavefronts, chain backward
+             (make_config(4, crop=(10, 12), algo="trwp", K=2), {}),  # value wavefronts that meet through LDS, index wavefronts
+             (make_config(5, crop=(24, 32), algo="trwp"), {}),       # packed scanlines with index wavefronts
+             (make_config(5, crop=(24, 32), algo="trwp"), {20: 2})]  # chain backward with two scanlines per workgroup
+    for pr, knobs in cases:
         g = GpuProblem(pr)
+        for k, v in knobs.items():
+            assert mrf.mrf_tune(k, v) == 0
         try:
             assert mrf.mrf_tune(14, 1) == 0
             g.forward()
             fwd = mrf.mrf_workspace_fault(g.workspace)
             g.backward(want_V=False)
             bwd = mrf.mrf_workspace_fault(g.workspace)
+            if knobs:
+                assert mrf.mrf_last_sweep_kernel(True) == "mrf_bwd_sweep_chain_pk" and bwd == -11
         finally:
             mrf.mrf_tune(14, 0)
         print("  ", pr.name, mrf.mrf_last_sweep_launch(False), fwd, mrf.mrf_last_sweep_launch(True), bwd, flush=True)
@@ -703,6 +708,8 @@ def test_waits_between_wavefronts_are_bounded(oracle):
         check_forward(got, f)
         b64 = oracle_backward(oracle, pr, f.p, f.q, np.float64)
         check_grad("grad_unary", got.grad_unary, None, b64.grad_unary)
+        for k in knobs:
+            mrf.mrf_tune(k, 0)
 
 
 def test_workspace_too_small_is_an_error_not_a_fault():
